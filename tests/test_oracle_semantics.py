@@ -1,0 +1,168 @@
+"""Hand-reasoned timelines and invariants for the oracle (CPU only).
+
+Each expected value below follows from the reading of the paper's section 2.1 stated in the design doc
+(occurrence filter: a key is admitted once its counted occurrences reach the threshold; expiry: a
+key inactive for the configured number of steps is removed), not from running the oracle.
+"""
+import numpy as np
+import pytest
+
+from oracle import Oracle
+from paper_2209_07663_amd import synth
+from tests import table_checks as tc
+
+KINDS = ["map", "cuckoo"]
+
+
+def one_bag(keys):
+    return np.asarray(keys, dtype=np.int64), np.array([0, len(keys)], dtype=np.int64)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_admission_at_threshold_counts_occurrences_not_batches(kind):
+    o = Oracle(64, 4, seed=1, freq_threshold=3, kind=kind)
+    # key 10: one occurrence per step -> absent, absent, present at its third occurrence
+    # key 20: three occurrences in the first batch -> all three present at once (batch semantics)
+    # key 30: two occurrences, then one -> present at step 1
+    assert o.lookup_or_insert(np.array([10, 20, 20, 20, 30, 30]), 0).tolist() == [False, True, True, True, False, False]
+    assert o.lookup_or_insert(np.array([10, 30]), 1).tolist() == [False, True]
+    assert o.lookup_or_insert(np.array([10]), 2).tolist() == [True]
+    d = o.dump()
+    assert d["keys"].tolist() == [10, 20, 30]
+    assert d["last_seen"].tolist() == [2, 0, 1]          # admission stamps the step
+    # hits do not touch the counters: key 20's counter still reads 3 from step 0
+    assert o.filter_words(o.filter_index(20), 1)[0] == (0 << 8) | 3
+    o.lookup_or_insert(np.array([20, 20]), 5)
+    assert o.filter_words(o.filter_index(20), 1)[0] == (0 << 8) | 3
+    assert o.dump()["last_seen"].tolist() == [2, 5, 1]   # ... but they refresh last_seen
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("thr", [0, 1])
+def test_threshold_zero_and_one_admit_on_first_sight(kind, thr):
+    o = Oracle(256, 2, seed=2, freq_threshold=thr, kind=kind)
+    keys = np.random.default_rng(0).integers(0, 500, size=100).astype(np.int64)
+    assert o.lookup_or_insert(keys, 0).all()
+    assert o.dump()["keys"].tolist() == sorted(set(keys.tolist()))
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_padding_key_is_never_stored_nor_counted(kind):
+    o = Oracle(64, 2, seed=3, freq_threshold=1, kind=kind)
+    assert o.lookup_or_insert(np.array([-1, 5, -1]), 0).tolist() == [False, True, False]
+    assert o.dump()["keys"].tolist() == [5]
+    keys, offsets = one_bag([-1, 5, -1])
+    assert (o.pool(keys, offsets)[0] == o.dump()["rows"][0]).all()
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_expiry_boundary_and_readmission(kind):
+    o = Oracle(64, 4, seed=4, freq_threshold=2, expire_steps=3, kind=kind)
+    o.lookup_or_insert(np.array([7, 7, 8, 8]), 10)             # both admitted at step 10
+    row7 = o.dump()["rows"][0].copy()
+    o.lookup_or_insert(np.array([8]), 11)                      # 8 refreshed at 11
+    assert o.expire_sweep(12).tolist() == []                   # 12 - 10 = 2 < 3
+    assert o.expire_sweep(13).tolist() == [7]                  # 13 - 10 = 3 >= 3: gone; 8: 13 - 11 = 2
+    assert o.dump()["keys"].tolist() == [8]
+    assert o.expire_sweep(14).tolist() == [8]
+    assert o.dump()["keys"].shape[0] == 0
+    # 7 comes back: it is a new key again.  Its counter (count 2, last touched at step 10) is 5 steps
+    # old at step 15 >= 3, so it restarts: one occurrence is not enough, two are.
+    assert o.lookup_or_insert(np.array([7]), 15).tolist() == [False]
+    assert o.filter_words(o.filter_index(7), 1)[0] == (15 << 8) | 1
+    assert o.lookup_or_insert(np.array([7]), 16).tolist() == [True]
+    d = o.dump()
+    assert (d["rows"][0] == row7).all() and d["acc"][0] == 0 and d["last_seen"][0] == 16
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_expire_zero_keeps_everything(kind):
+    o = Oracle(64, 2, seed=5, freq_threshold=1, expire_steps=0, kind=kind)
+    o.lookup_or_insert(np.array([1, 2, 3]), 0)
+    assert o.expire_sweep(10**6).tolist() == []
+    assert o.dump()["keys"].tolist() == [1, 2, 3]
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_update_does_not_refresh_last_seen_and_drops_absent_keys(kind):
+    o = Oracle(64, 2, seed=6, freq_threshold=2, expire_steps=2, kind=kind)
+    o.lookup_or_insert(np.array([1, 1, 2]), 0)                 # 1 admitted, 2 not
+    keys, offsets = one_bag([1, 2])
+    before = o.dump()
+    o.apply_grad_adagrad(keys, offsets, np.ones((1, 2), dtype=np.float32), 0.05, 1e-8)
+    after = o.dump()
+    assert after["keys"].tolist() == [1] and after["last_seen"].tolist() == [0]
+    assert (after["rows"] != before["rows"]).all()
+    assert o.expire_sweep(2).tolist() == [1]
+
+
+def test_filter_over_counts_only_when_keys_share_a_counter():
+    """One hashed counter array: never under-counts; two keys on one counter add up."""
+    o = Oracle(16, 2, seed=7, freq_threshold=2, kind="cuckoo", n_filter=2)
+    # with two counters, among three keys two share one: find such a pair
+    idx = {k: o.filter_index(k) for k in (100, 200, 300)}
+    a, b = [(x, y) for x in idx for y in idx if x < y and idx[x] == idx[y]][0]
+    assert o.lookup_or_insert(np.array([a]), 0).tolist() == [False]
+    assert o.lookup_or_insert(np.array([b]), 0).tolist() == [True]   # shared counter reads 2
+    assert o.dump()["keys"].tolist() == [b]
+
+
+def test_invariants_through_a_streaming_run_at_high_load():
+    """I1-I5 on a few thousand keys driven to ~0.9 load with expiry, zero failed chains."""
+    cap, dim, seed = 1 << 12, 4, 11
+    n_filter = 1 << 22                                         # wide: false admissions stay rare
+    o = Oracle(cap, dim, seed, freq_threshold=2, expire_steps=6, kind="cuckoo", bucket=8, max_kicks=512,
+               n_filter=n_filter)
+    rng = np.random.default_rng(3)
+    counts = {}
+    hot = rng.permutation(1 << 20)[: int(0.9 * cap)].astype(np.int64)
+    total_admitted = total_expired = 0
+    for step in range(30):
+        cold = rng.integers(1 << 21, 1 << 30, size=300).astype(np.int64)
+        hot[rng.integers(0, 2000, size=25)] = rng.integers(1 << 40, 1 << 41, size=25)  # the hot set rotates
+        keys = np.concatenate([hot, hot[: 2000], cold])
+        rng.shuffle(keys)
+        before = set(o.dump()["keys"].tolist())
+        present = o.lookup_or_insert(keys, step)
+        d = o.dump()
+        now_in = set(d["keys"].tolist())
+        total_admitted += len(now_in - before)
+        for k in keys.tolist():
+            if k not in before:
+                counts[k] = counts.get(k, 0) + 1
+        for k in now_in - before:
+            # the counter never under-counts (it may over-count when keys share it)
+            word = int(o.filter_words(int(tc.filter_index([k], n_filter, seed)[0]), 1)[0])
+            assert (word & 255) >= max(2, min(255, counts[k])) and (word >> 8) == step, "I3"
+        in_batch = set(keys.tolist())
+        for k, c in counts.items():
+            if c >= 2 and k in in_batch and k not in before:
+                assert k in now_in, "I3: exact count reached the threshold but the key is absent"
+        assert present.tolist() == [k in now_in for k in keys.tolist()]
+        assert o.insert_failures == 0
+        tc.check_placement(d, cap, 8, seed)                      # I1, I2
+        erased = o.expire_sweep(step)
+        total_expired += erased.shape[0]
+        d2 = o.dump()
+        assert ((step - d2["last_seen"].astype(np.int64)) < 6).all()  # I4
+        assert set(erased.tolist()) == now_in - set(d2["keys"].tolist())
+        for k in erased.tolist():
+            counts.pop(k, None)                                  # must re-qualify (its counter is aged anyway)
+        assert d2["keys"].shape[0] == total_admitted - total_expired <= cap  # I5
+    assert d2["keys"].shape[0] > 0.85 * cap
+    assert total_expired > 0
+
+
+def test_oracle_runs_the_small_configuration():
+    """configs[0]: 2^16 rows, dim 16, one batch of 4096 uniform IDs, threshold 1: everything admitted."""
+    wl = synth.CONFIGS["cfg1"]
+    b = synth.make_batch(wl, seed=1, step=0)
+    o = Oracle(wl.capacity, wl.dim, seed=1, freq_threshold=wl.freq_threshold, kind="cuckoo")
+    assert o.lookup_or_insert(b["keys"], 0).all()
+    d = o.dump()
+    assert d["keys"].tolist() == sorted(set(b["keys"].tolist()))
+    tc.check_placement(d, wl.capacity, 8, 1)
+    out = o.pool(b["keys"], b["offsets"])
+    pos = np.searchsorted(d["keys"], b["keys"])
+    assert (out == d["rows"][pos]).all()                          # one ID per bag: pooled = the row
+    assert (d["rows"] == tc.init_rows(d["keys"], wl.dim, 1).astype(np.float32)).all()
