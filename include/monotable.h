@@ -1,0 +1,137 @@
+/* monotable.h — C ABI of the MI355X-native collisionless embedding table.
+ *
+ * The operations are those of the `HashTable` of arxiv 2209.07663 (Monolith), section 2.1: a
+ * key-value table for sparse parameters built on a cuckoo hashmap with two sub-tables T0/T1 and two
+ * hash functions h0/h1 (an element lives in exactly one of T0[h0(x)], T1[h1(x)]; an insertion that
+ * finds its cell occupied evicts the occupant, which is re-inserted in the other sub-table), with
+ * the two memory-saving heuristics of the same section: IDs are filtered by their number of
+ * occurrences before they are admitted, and IDs that stay inactive for a configured time expire.
+ * "Look-ups and updates" are separate operations (end of section 2.1).  Pooling, duplicate-ID
+ * gradient reduction and row-wise Adagrad are the build's own problem statement around that table.
+ *
+ * Conventions
+ *  - Every pointer named d_* is DEVICE memory owned by the caller; h_* is HOST memory owned by
+ *    the caller.  The library never frees caller memory and keeps no pointer to it after a call
+ *    returns (work already queued on the stream still reads/writes it: keep it alive until the
+ *    stream has passed the call).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All hot calls only
+ *    queue work on that stream and never synchronise.  Calls on one table must be issued in
+ *    stream order on one stream; two calls on the same table that overlap race.
+ *  - Return value: MONO_OK or a negative error; argument and launch errors only.  Data-dependent
+ *    events (a failed eviction chain, a full table) are counted on the device and read with
+ *    mono_table_stats.
+ *  - Key -1 (all ones) is reserved as padding: it resolves to row -1 and is never counted or
+ *    stored.  Every other int64 bit pattern is a legal key.
+ *  - `step` / `now` are the caller's training-step counter: non-decreasing from call to call and
+ *    below 2^24.
+ */
+#ifndef MONOTABLE_H_
+#define MONOTABLE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mono_table mono_table; /* opaque; one table = one embedding dimension */
+
+enum { MONO_OK = 0, MONO_EINVAL = -1, MONO_ENOMEM = -2, MONO_EHIP = -3 };
+enum { MONO_ROWS_FP32 = 0, MONO_ROWS_BF16 = 1 }; /* `flags`: storage type of the embedding rows */
+
+typedef struct mono_stats {
+  uint64_t capacity;        /* slots = rows */
+  uint64_t size;            /* keys currently stored (stash included) */
+  uint64_t n_admitted;      /* keys admitted since creation */
+  uint64_t n_expired;       /* keys removed by expire_sweep since creation */
+  uint64_t n_insert_failed; /* eviction chains that hit the kick bound (element went to the stash) */
+  uint64_t n_lost;          /* elements dropped because the stash was full too (must stay 0) */
+  uint64_t n_full;          /* admissible keys refused because no row was free */
+  uint64_t stash_size;      /* elements currently in the stash */
+  uint64_t max_chain;       /* longest eviction chain seen */
+} mono_stats;
+
+/* Bytes of device memory a table needs (table proper + per-call workspace for batches of at most
+ * max_ids IDs in at most max_bags bags).  0 on invalid arguments. */
+size_t mono_table_bytes(uint64_t capacity, uint32_t dim, uint32_t flags, uint64_t max_ids, uint64_t max_bags);
+
+/* Creates a table (section 2.1: cuckoo hashmap + occurrence filter + expiry).
+ *   capacity        total slots = embedding rows; power of two in [16, 2^30]; each sub-table has half
+ *   dim             embedding dimension; multiple of 4 in [4, 256]
+ *   seed            fixes h0, h1, the counter hash and the initial value of every row
+ *   freq_threshold  a key is admitted once its occurrence counter reaches it; 0 and 1 admit on
+ *                   first sight; at most 255
+ *   expire_steps    a key unseen for this many steps is removed by mono_expire_sweep; 0 = never
+ *   flags           MONO_ROWS_FP32 or MONO_ROWS_BF16
+ *   max_ids/max_bags largest batch any later call will pass (1 <= max_ids < 2^31)
+ *   d_arena         NULL: the library allocates (and frees in destroy) its own device memory;
+ *                   else caller-owned device memory of arena_bytes >= mono_table_bytes(...),
+ *                   256-byte aligned, which must outlive the table
+ * Initialisation is queued on `stream`.  Errors: MONO_EINVAL (bad argument, arena too small),
+ * MONO_ENOMEM (allocation failed), MONO_EHIP (a HIP call failed). */
+int mono_table_create(mono_table** out, uint64_t capacity, uint32_t dim, uint64_t seed, uint32_t freq_threshold,
+                      uint32_t expire_steps, uint32_t flags, uint64_t max_ids, uint64_t max_bags, void* d_arena,
+                      size_t arena_bytes, void* stream);
+
+/* Frees the table (synchronises the device first).  The caller's arena, if any, is not freed. */
+int mono_table_destroy(mono_table* t);
+
+/* Batched lookup-or-insert (section 2.1: lookup in T0[h0(x)] / T1[h1(x)]; insertion with eviction
+ * chain; admission gated by the occurrence filter; keys are time-stamped for expiry).
+ * Batch semantics: hits and misses are judged against the table before the call; every miss
+ * occurrence is counted; then every distinct missing key whose counter reached freq_threshold is
+ * admitted with its initial row, accumulator 0 and last_seen = step; hit keys get last_seen = step.
+ *   d_keys[n]      int64 keys (device)
+ *   d_rows_out[n]  receives the embedding row index of each occurrence, or -1 if its key is not
+ *                  in the table (not admitted, padding, or no room).  Row indices stay valid
+ *                  until the key expires.
+ * Errors: MONO_EINVAL if n > max_ids, step >= 2^24 or step went backwards. */
+int mono_lookup_or_insert(mono_table* t, const int64_t* d_keys, uint64_t n, uint32_t step, int32_t* d_rows_out,
+                          void* stream);
+
+/* Embedding gather with per-bag sum pooling: d_out[b, :] = sum of the rows d_rows[i] >= 0 for
+ * i in [d_offsets[b], d_offsets[b+1]).  d_offsets[n_bags + 1] is int64, non-decreasing, starts at
+ * 0 and ends at n.  d_out[n_bags * dim] is fp32 whatever the storage type; empty bags give zeros.
+ * Errors: MONO_EINVAL if n > max_ids or n_bags > max_bags. */
+int mono_gather_pool(mono_table* t, const int32_t* d_rows, uint64_t n, const int64_t* d_offsets, uint64_t n_bags,
+                     float* d_out, void* stream);
+
+/* Sparse update ("PS ... updates them according to gradients computed by Workers", section 2):
+ * the pooled gradient d_grad[n_bags * dim] (fp32) of bag b is the gradient of each of its
+ * occurrences; gradients of occurrences of the same row are summed, then row-wise Adagrad is
+ * applied once per distinct row: acc += mean_j g_j^2; w_j -= lr * g_j / (sqrt(acc) + eps).
+ * Occurrences with row -1 are dropped.  d_rows / d_offsets as in mono_gather_pool. */
+int mono_apply_grad_adagrad(mono_table* t, const int32_t* d_rows, uint64_t n, const int64_t* d_offsets,
+                            uint64_t n_bags, const float* d_grad, float lr, float eps, void* stream);
+
+/* Expiry (section 2.1, second heuristic): removes every key with now - last_seen >= expire_steps
+ * (nothing if expire_steps == 0) and frees its row.
+ *   d_n_expired     nullable; receives the number of keys removed by this call
+ *   d_expired_keys  nullable; receives up to max_expired of the removed keys, in no particular order */
+int mono_expire_sweep(mono_table* t, uint32_t now, uint64_t* d_n_expired, int64_t* d_expired_keys,
+                      uint64_t max_expired, void* stream);
+
+/* ---- observability / test surface (not part of the timed path; these synchronise `stream`) ---- */
+
+int mono_table_stats(mono_table* t, mono_stats* h_out, void* stream);
+
+/* Dumps up to max_n stored keys in no particular order.  Any of the d_* outputs may be NULL.
+ *   d_keys[max_n], d_row[max_n] (row index), d_last_seen[max_n],
+ *   d_slot[max_n]: global slot = sub-table * capacity/2 + bucket * 8 + lane, or -2 for the stash,
+ *   d_values[max_n * dim]: the rows widened to fp32, d_acc[max_n]: Adagrad accumulators.
+ * *h_n receives the number of keys stored (which may exceed max_n; only max_n are written). */
+int mono_table_export(mono_table* t, int64_t* d_keys, int32_t* d_row, uint32_t* d_last_seen, int64_t* d_slot,
+                      float* d_values, float* d_acc, uint64_t max_n, uint64_t* h_n, void* stream);
+
+/* Occurrence counters [first, first + count) in canonical form (step & 0xFFFFFF) << 8 | min(count, 255).
+ * There are 4 * capacity counters. */
+int mono_filter_export(mono_table* t, uint32_t* d_words, uint64_t first, uint64_t count, void* stream);
+
+/* Static description of an error code. */
+const char* mono_strerror(int err);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MONOTABLE_H_ */

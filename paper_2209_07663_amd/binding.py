@@ -1,0 +1,183 @@
+"""Thin ctypes binding of include/monotable.h — argument marshalling only.
+
+Every step of the path runs in the HIP kernels of `libmonotable.so`; torch is used for device
+memory and for the current stream.  There is no fallback: if the library is missing, loading fails.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmonotable.so")
+
+MONO_OK, MONO_EINVAL, MONO_ENOMEM, MONO_EHIP = 0, -1, -2, -3
+MONO_ROWS_FP32, MONO_ROWS_BF16 = 0, 1
+
+_u64, _u32, _vp, _f32 = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_float
+
+
+class mono_stats(ctypes.Structure):
+    _fields_ = [(n, _u64) for n in ("capacity", "size", "n_admitted", "n_expired", "n_insert_failed", "n_lost",
+                                    "n_full", "stash_size", "max_chain")]
+
+
+# every symbol include/monotable.h declares: name -> (restype, argtypes)
+SYMBOLS = {
+    "mono_table_bytes": (ctypes.c_size_t, [_u64, _u32, _u32, _u64, _u64]),
+    "mono_table_create": (ctypes.c_int, [ctypes.POINTER(_vp), _u64, _u32, _u64, _u32, _u32, _u32, _u64, _u64, _vp,
+                                         ctypes.c_size_t, _vp]),
+    "mono_table_destroy": (ctypes.c_int, [_vp]),
+    "mono_lookup_or_insert": (ctypes.c_int, [_vp, _vp, _u64, _u32, _vp, _vp]),
+    "mono_gather_pool": (ctypes.c_int, [_vp, _vp, _u64, _vp, _u64, _vp, _vp]),
+    "mono_apply_grad_adagrad": (ctypes.c_int, [_vp, _vp, _u64, _vp, _u64, _vp, _f32, _f32, _vp]),
+    "mono_expire_sweep": (ctypes.c_int, [_vp, _u32, _vp, _vp, _u64, _vp]),
+    "mono_table_stats": (ctypes.c_int, [_vp, ctypes.POINTER(mono_stats), _vp]),
+    "mono_table_export": (ctypes.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _u64, ctypes.POINTER(_u64), _vp]),
+    "mono_filter_export": (ctypes.c_int, [_vp, _vp, _u64, _u64, _vp]),
+    "mono_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+}
+
+_lib = None
+
+
+def load_library():
+    """Loads libmonotable.so (built in-tree by `paper_2209_07663_amd.build`); raises if it is absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libmonotable.so is not built: run `python -m paper_2209_07663_amd.build` "
+                               "(there is no CPU fallback)")
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SYMBOLS.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = lib
+    return _lib
+
+
+class MonoError(RuntimeError):
+    pass
+
+
+def _check(rc, what):
+    if rc != MONO_OK:
+        raise MonoError("%s: %s (%d)" % (what, load_library().mono_strerror(rc).decode(), rc))
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _p(t):
+    return None if t is None else t.data_ptr()
+
+
+def _dev(t, dtype):
+    assert t.is_cuda and t.dtype == dtype and t.is_contiguous(), "need a contiguous CUDA tensor of %s" % dtype
+
+
+class Table:
+    """One collisionless embedding table on the current device.  Methods carry the C-ABI names."""
+
+    def __init__(self, capacity, dim, seed, freq_threshold=1, expire_steps=0, bf16=False, max_ids=1 << 20,
+                 max_bags=None, device="cuda:0"):
+        self.lib = load_library()
+        self.capacity, self.dim, self.bf16 = int(capacity), int(dim), bool(bf16)
+        self.max_ids = int(max_ids)
+        self.max_bags = int(max_bags) if max_bags is not None else self.max_ids
+        self.device = torch.device(device)
+        flags = MONO_ROWS_BF16 if bf16 else MONO_ROWS_FP32
+        nbytes = self.lib.mono_table_bytes(self.capacity, self.dim, flags, self.max_ids, self.max_bags)
+        if nbytes == 0:
+            raise MonoError("mono_table_bytes: invalid table shape")
+        self.arena = torch.empty(nbytes, dtype=torch.uint8, device=self.device)  # torch owns the memory
+        h = _vp()
+        with torch.cuda.device(self.device):
+            _check(self.lib.mono_table_create(ctypes.byref(h), self.capacity, self.dim, seed, freq_threshold,
+                                              expire_steps, flags, self.max_ids, self.max_bags,
+                                              self.arena.data_ptr(), nbytes, _stream()), "mono_table_create")
+        self.h = h
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.mono_table_destroy(self.h)
+            self.h = None
+            self.arena = None
+
+    def __del__(self):
+        self.close()
+
+    def mono_lookup_or_insert(self, keys, step, rows_out=None):
+        _dev(keys, torch.int64)
+        if rows_out is None:
+            rows_out = torch.empty(keys.shape[0], dtype=torch.int32, device=keys.device)
+        _dev(rows_out, torch.int32)
+        _check(self.lib.mono_lookup_or_insert(self.h, _p(keys), keys.shape[0], step, _p(rows_out), _stream()),
+               "mono_lookup_or_insert")
+        return rows_out
+
+    def mono_gather_pool(self, rows, offsets, out=None):
+        _dev(rows, torch.int32)
+        _dev(offsets, torch.int64)
+        n_bags = offsets.shape[0] - 1
+        if out is None:
+            out = torch.empty((n_bags, self.dim), dtype=torch.float32, device=rows.device)
+        _dev(out, torch.float32)
+        _check(self.lib.mono_gather_pool(self.h, _p(rows), rows.shape[0], _p(offsets), n_bags, _p(out), _stream()),
+               "mono_gather_pool")
+        return out
+
+    def mono_apply_grad_adagrad(self, rows, offsets, grad, lr, eps):
+        _dev(rows, torch.int32)
+        _dev(offsets, torch.int64)
+        _dev(grad, torch.float32)
+        n_bags = offsets.shape[0] - 1
+        assert grad.numel() == n_bags * self.dim
+        _check(self.lib.mono_apply_grad_adagrad(self.h, _p(rows), rows.shape[0], _p(offsets), n_bags, _p(grad), lr,
+                                                eps, _stream()), "mono_apply_grad_adagrad")
+
+    def mono_expire_sweep(self, now, n_expired=None, expired_keys=None):
+        max_expired = 0
+        if expired_keys is not None:
+            _dev(expired_keys, torch.int64)
+            max_expired = expired_keys.shape[0]
+        if n_expired is not None:
+            _dev(n_expired, torch.int64)
+        _check(self.lib.mono_expire_sweep(self.h, now, _p(n_expired), _p(expired_keys), max_expired, _stream()),
+               "mono_expire_sweep")
+
+    def mono_table_stats(self):
+        st = mono_stats()
+        _check(self.lib.mono_table_stats(self.h, ctypes.byref(st), _stream()), "mono_table_stats")
+        return {n: int(getattr(st, n)) for n, _ in mono_stats._fields_}
+
+    def mono_table_export(self, with_values=True):
+        """Dump as host numpy arrays sorted by key (as uint64): keys, row, last_seen, slot, rows, acc."""
+        n = self.mono_table_stats()["size"]
+        dev = self.device
+        keys = torch.empty(n, dtype=torch.int64, device=dev)
+        row = torch.empty(n, dtype=torch.int32, device=dev)
+        seen = torch.empty(n, dtype=torch.int32, device=dev)
+        slot = torch.empty(n, dtype=torch.int64, device=dev)
+        vals = torch.empty((n, self.dim), dtype=torch.float32, device=dev) if with_values else None
+        acc = torch.empty(n, dtype=torch.float32, device=dev) if with_values else None
+        got = _u64()
+        _check(self.lib.mono_table_export(self.h, _p(keys), _p(row), _p(seen), _p(slot), _p(vals), _p(acc), n,
+                                          ctypes.byref(got), _stream()), "mono_table_export")
+        if got.value != n:
+            raise MonoError("mono_table_export: %d keys stored but %d rows in use" % (got.value, n))
+        k = keys.cpu().numpy()
+        order = k.view("uint64").argsort(kind="stable")
+        d = {"keys": k[order], "row": row.cpu().numpy()[order], "last_seen": seen.cpu().numpy().view("uint32")[order],
+             "slot": slot.cpu().numpy()[order]}
+        if with_values:
+            d["rows"] = vals.cpu().numpy()[order]
+            d["acc"] = acc.cpu().numpy()[order]
+        return d
+
+    def mono_filter_export(self, first=0, count=None):
+        count = 4 * self.capacity - first if count is None else count
+        words = torch.empty(count, dtype=torch.int32, device=self.device)
+        _check(self.lib.mono_filter_export(self.h, _p(words), first, count, _stream()), "mono_filter_export")
+        return words.cpu().numpy().view("uint32")

@@ -1,0 +1,119 @@
+// Device-side layout and helpers shared by the kernels of the collisionless table (gfx950).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mono {
+
+constexpr uint64_t kEmptyKey = ~0ull;       // reserved key: padding / free slot
+constexpr uint32_t kNoRow = 0xFFFFFFFFu;    // slot has no published row: free, or being written
+constexpr int kBucket = 8;                  // slots per bucket
+constexpr int kMaxKicks = 128;              // bound of an eviction chain
+constexpr uint32_t kStashCap = 4096;        // homeless elements kept aside after a failed chain
+constexpr int32_t kRowAbsent = -1;          // rows_out: key not in the table
+constexpr int32_t kRowMiss = -2;            // rows_out, between the kernels of one call: missed, undecided
+// rows_out values <= -3 between the kernels of one call: duplicate of an admitted key, encodes the
+// position of that key in the per-call dedup set
+
+// One bucket = one 128-byte line: the first 64-byte half holds the keys that a probe compares, the
+// second half the row index and last-seen step of each slot, so that a hit costs one line and a
+// miss only touches the key halves.
+struct __attribute__((aligned(128))) Bucket {
+  uint64_t key[kBucket];
+  uint32_t row[kBucket];
+  uint32_t seen[kBucket];
+};
+static_assert(sizeof(Bucket) == 128, "bucket must be one 128-byte line");
+
+struct StashEntry {
+  uint64_t key;
+  uint32_t row;
+  uint32_t seen;
+};
+
+// Counters that live on the device for the whole life of the table.
+struct Control {
+  int32_t free_n;            // rows on the free stack
+  uint32_t stash_n;          // elements pushed to the stash (may exceed kStashCap: then some were lost)
+  unsigned long long n_admitted, n_expired, n_insert_failed, n_lost, n_full, max_chain;
+  unsigned long long scratch[8];  // per-call scalars (export count, sweep count)
+};
+
+// Everything a kernel needs to know about a table; passed by value.
+struct TableView {
+  Bucket* buckets;           // [2 * n_buckets]: T0 then T1
+  unsigned long long* filter;  // [n_filter] occurrence counters: step << 32 | count
+  void* rows;                // [capacity * dim] fp32 or bf16
+  float* acc;                // [capacity]
+  uint32_t* free_rows;       // [capacity] stack of free row indices
+  Control* ctl;
+  StashEntry* stash;         // [kStashCap]
+  unsigned long long* dset;  // [dset_size] per-call dedup set: epoch << 32 | occurrence index
+  int32_t* dset_row;         // [dset_size] row of the key that owns the dedup-set position
+  uint64_t capacity;
+  uint64_t n_buckets;        // per sub-table
+  uint64_t n_filter;
+  uint64_t dset_mask;
+  uint64_t s_h0, s_h1, s_filter, s_init, s_dedup;
+  uint32_t bucket_shift;     // 64 - log2(n_buckets)   (64 means: single bucket)
+  uint32_t filter_shift;     // 64 - log2(n_filter)
+  uint32_t dim;
+  uint32_t freq_threshold;
+  uint32_t expire_steps;
+  uint32_t bf16;
+};
+
+__host__ __device__ inline uint64_t mix64(uint64_t z) {
+  z ^= z >> 30;
+  z *= 0xBF58476D1CE4E5B9ull;
+  z ^= z >> 27;
+  z *= 0x94D049BB133111EBull;
+  z ^= z >> 31;
+  return z;
+}
+
+__device__ inline uint64_t shr_or_zero(uint64_t h, uint32_t shift) { return shift >= 64 ? 0 : h >> shift; }
+
+__device__ inline uint64_t bucket_index(const TableView& t, int side, uint64_t key) {
+  uint64_t h = mix64(key ^ (side == 0 ? t.s_h0 : t.s_h1));
+  return shr_or_zero(h, t.bucket_shift) + (side == 0 ? 0 : t.n_buckets);
+}
+
+__device__ inline uint64_t filter_index(const TableView& t, uint64_t key) {
+  return shr_or_zero(mix64(key ^ t.s_filter), t.filter_shift);
+}
+
+// Initial value of element j of the row of `key`: uniform on a 2^-27 grid in [-2^-4, 2^-4).
+// `base` = mix64(key ^ s_init).  Only exact fp32 operations.
+__device__ inline float init_value(uint64_t base, uint32_t j) {
+  uint32_t u24 = (uint32_t)(mix64(base + (uint64_t)j) >> 40);
+  return ((float)u24 * (1.0f / 8388608.0f) - 1.0f) * 0.0625f;
+}
+
+// bfloat16 <-> fp32 on bit patterns; round to nearest even.
+__device__ inline uint16_t f32_to_bf16(float x) {
+  uint32_t u = __float_as_uint(x);
+  if ((u & 0x7F800000u) == 0x7F800000u) {
+    if (u & 0x007FFFFFu) u |= 0x00400000u;
+    return (uint16_t)(u >> 16);
+  }
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ inline float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+// agent-scope relaxed atomics on table words (visible across all compute units of the device)
+template <typename T>
+__device__ inline T ld_agent(const T* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T>
+__device__ inline void st_agent(T* p, T v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ inline unsigned lane_id() { return __lane_id(); }
+__device__ inline uint64_t lanes_below() { return (1ull << lane_id()) - 1ull; }
+
+}  // namespace mono

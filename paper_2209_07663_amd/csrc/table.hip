@@ -1,0 +1,262 @@
+// Host side of the C ABI declared in include/monotable.h: argument checks, arena layout, launches.
+#include <new>
+
+#include "../../include/monotable.h"
+#include "common.h"
+#include "kernels.h"
+
+using namespace mono;
+
+struct mono_table {
+  TableView view;
+  UpdateWorkspace ws;
+  void* owned_arena = nullptr;  // non-null when the library allocated the arena
+  uint64_t max_ids = 0, max_bags = 0, dset_size = 0;
+  uint32_t epoch = 0;       // per-call tag of the dedup set
+  uint32_t last_step = 0;
+  int device = 0;
+};
+
+namespace {
+
+bool is_pow2(uint64_t v) { return v && !(v & (v - 1)); }
+int log2u(uint64_t v) {
+  int lg = 0;
+  while ((1ull << lg) < v) ++lg;
+  return lg;
+}
+size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+bool valid_shape(uint64_t capacity, uint32_t dim, uint32_t flags, uint64_t max_ids, uint64_t max_bags) {
+  return is_pow2(capacity) && capacity >= 16 && capacity <= (1ull << 30) && dim >= 4 && dim <= 256 && dim % 4 == 0 &&
+         flags <= MONO_ROWS_BF16 && max_ids >= 1 && max_ids <= (1ull << 28) && max_bags >= 1 && max_bags <= max_ids + 1;
+}
+
+uint64_t dedup_size(uint64_t max_ids) {
+  uint64_t s = 64;
+  while (s < 2 * max_ids) s <<= 1;
+  return s;
+}
+
+// Carves the arena; with base == nullptr only measures.  Returns the bytes used.
+size_t layout(mono_table* t, char* base, uint64_t capacity, uint32_t dim, uint32_t flags, uint64_t max_ids,
+              uint64_t max_bags) {
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    char* p = base ? base + off : nullptr;
+    off += align_up(bytes);
+    return p;
+  };
+  const uint64_t n_buckets = capacity / 2 / kBucket, n_filter = 4 * capacity, dset = dedup_size(max_ids);
+  const size_t esize = flags == MONO_ROWS_BF16 ? 2 : 4;
+  char* buckets = take(2 * n_buckets * sizeof(Bucket));
+  char* filter = take(n_filter * sizeof(unsigned long long));
+  char* rows = take(capacity * dim * esize);
+  char* acc = take(capacity * sizeof(float));
+  char* free_rows = take(capacity * sizeof(uint32_t));
+  char* ctl = take(sizeof(Control));
+  char* stash = take(kStashCap * sizeof(StashEntry));
+  char* dset_p = take(dset * sizeof(unsigned long long));
+  char* dset_row = take(dset * sizeof(int32_t));
+  char* key_a = take(max_ids * 4);
+  char* key_b = take(max_ids * 4);
+  char* val_a = take(max_ids * 4);
+  char* val_b = take(max_ids * 4);
+  char* hist = take(((size_t)kSortMaxBins * sort_units(max_ids) + kSortMaxBins) * 4);
+  char* part = take(2 * reduce_chunks(max_ids) * dim * sizeof(float));
+  char* part_row = take(2 * reduce_chunks(max_ids) * sizeof(uint32_t));
+  (void)max_bags;
+  if (t && base) {
+    TableView& v = t->view;
+    v.buckets = (Bucket*)buckets;
+    v.filter = (unsigned long long*)filter;
+    v.rows = rows;
+    v.acc = (float*)acc;
+    v.free_rows = (uint32_t*)free_rows;
+    v.ctl = (Control*)ctl;
+    v.stash = (StashEntry*)stash;
+    v.dset = (unsigned long long*)dset_p;
+    v.dset_row = (int32_t*)dset_row;
+    t->ws.key_a = (uint32_t*)key_a;
+    t->ws.key_b = (uint32_t*)key_b;
+    t->ws.val_a = (uint32_t*)val_a;
+    t->ws.val_b = (uint32_t*)val_b;
+    t->ws.hist = (uint32_t*)hist;
+    t->ws.part = (float*)part;
+    t->ws.part_row = (uint32_t*)part_row;
+  }
+  return off;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* mono_strerror(int err) {
+  switch (err) {
+    case MONO_OK: return "ok";
+    case MONO_EINVAL: return "invalid argument";
+    case MONO_ENOMEM: return "out of device memory";
+    case MONO_EHIP: return "HIP runtime error";
+    default: return "unknown error";
+  }
+}
+
+size_t mono_table_bytes(uint64_t capacity, uint32_t dim, uint32_t flags, uint64_t max_ids, uint64_t max_bags) {
+  if (!valid_shape(capacity, dim, flags, max_ids, max_bags)) return 0;
+  return layout(nullptr, nullptr, capacity, dim, flags, max_ids, max_bags);
+}
+
+int mono_table_create(mono_table** out, uint64_t capacity, uint32_t dim, uint64_t seed, uint32_t freq_threshold,
+                      uint32_t expire_steps, uint32_t flags, uint64_t max_ids, uint64_t max_bags, void* d_arena,
+                      size_t arena_bytes, void* stream) {
+  if (!out) return MONO_EINVAL;
+  *out = nullptr;
+  if (!valid_shape(capacity, dim, flags, max_ids, max_bags) || freq_threshold > 255 || expire_steps >= (1u << 24))
+    return MONO_EINVAL;
+  const size_t need = layout(nullptr, nullptr, capacity, dim, flags, max_ids, max_bags);
+  if (d_arena && (arena_bytes < need || ((uintptr_t)d_arena & 255))) return MONO_EINVAL;
+  mono_table* t = new (std::nothrow) mono_table();
+  if (!t) return MONO_ENOMEM;
+  if (hipGetDevice(&t->device) != hipSuccess) {
+    delete t;
+    return MONO_EHIP;
+  }
+  char* base = (char*)d_arena;
+  if (!base) {
+    if (hipMalloc((void**)&base, need) != hipSuccess) {
+      (void)hipGetLastError();
+      delete t;
+      return MONO_ENOMEM;
+    }
+    t->owned_arena = base;
+  }
+  layout(t, base, capacity, dim, flags, max_ids, max_bags);
+  TableView& v = t->view;
+  v.capacity = capacity;
+  v.n_buckets = capacity / 2 / kBucket;
+  v.n_filter = 4 * capacity;
+  t->dset_size = dedup_size(max_ids);
+  v.dset_mask = t->dset_size - 1;
+  uint64_t s[5];
+  for (int i = 0; i < 5; ++i) s[i] = mix64(seed + (uint64_t)(i + 1) * 0x9E3779B97F4A7C15ull);
+  v.s_h0 = s[0];
+  v.s_h1 = s[1];
+  v.s_filter = s[2];
+  v.s_init = s[3];
+  v.s_dedup = s[4];
+  v.bucket_shift = 64u - (uint32_t)log2u(v.n_buckets);
+  v.filter_shift = 64u - (uint32_t)log2u(v.n_filter);
+  v.dim = dim;
+  v.freq_threshold = freq_threshold;
+  v.expire_steps = expire_steps;
+  v.bf16 = flags == MONO_ROWS_BF16;
+  t->max_ids = max_ids;
+  t->max_bags = max_bags;
+  if (launch_table_init(v, t->dset_size, (hipStream_t)stream) != hipSuccess) {
+    if (t->owned_arena) (void)hipFree(t->owned_arena);
+    delete t;
+    return MONO_EHIP;
+  }
+  *out = t;
+  return MONO_OK;
+}
+
+int mono_table_destroy(mono_table* t) {
+  if (!t) return MONO_EINVAL;
+  int rc = MONO_OK;
+  if (hipDeviceSynchronize() != hipSuccess) rc = MONO_EHIP;
+  if (t->owned_arena && hipFree(t->owned_arena) != hipSuccess) rc = MONO_EHIP;
+  delete t;
+  return rc;
+}
+
+int mono_lookup_or_insert(mono_table* t, const int64_t* d_keys, uint64_t n, uint32_t step, int32_t* d_rows_out,
+                          void* stream) {
+  if (!t || n > t->max_ids || step >= (1u << 24) || step < t->last_step) return MONO_EINVAL;
+  if (n == 0) return MONO_OK;
+  if (!d_keys || !d_rows_out) return MONO_EINVAL;
+  t->last_step = step;
+  if (++t->epoch == 0) {  // the 32-bit call tag wrapped: forget every old tag
+    if (hipMemsetAsync(t->view.dset, 0, t->dset_size * sizeof(unsigned long long), (hipStream_t)stream) != hipSuccess)
+      return MONO_EHIP;
+    t->epoch = 1;
+  }
+  return launch_lookup_or_insert(t->view, d_keys, n, step, t->epoch, d_rows_out, (hipStream_t)stream) == hipSuccess
+             ? MONO_OK
+             : MONO_EHIP;
+}
+
+int mono_gather_pool(mono_table* t, const int32_t* d_rows, uint64_t n, const int64_t* d_offsets, uint64_t n_bags,
+                     float* d_out, void* stream) {
+  if (!t || n > t->max_ids || n_bags > t->max_bags) return MONO_EINVAL;
+  if (n_bags == 0) return MONO_OK;
+  if (!d_offsets || !d_out || (n && !d_rows)) return MONO_EINVAL;
+  return launch_gather_pool(t->view, d_rows, d_offsets, n_bags, d_out, (hipStream_t)stream) == hipSuccess ? MONO_OK
+                                                                                                           : MONO_EHIP;
+}
+
+int mono_apply_grad_adagrad(mono_table* t, const int32_t* d_rows, uint64_t n, const int64_t* d_offsets,
+                            uint64_t n_bags, const float* d_grad, float lr, float eps, void* stream) {
+  if (!t || n > t->max_ids || n_bags > t->max_bags) return MONO_EINVAL;
+  if (n == 0 || n_bags == 0) return MONO_OK;
+  if (!d_rows || !d_offsets || !d_grad) return MONO_EINVAL;
+  return launch_apply_grad_adagrad(t->view, t->ws, d_rows, n, d_offsets, n_bags, d_grad, lr, eps,
+                                   (hipStream_t)stream) == hipSuccess
+             ? MONO_OK
+             : MONO_EHIP;
+}
+
+int mono_expire_sweep(mono_table* t, uint32_t now, uint64_t* d_n_expired, int64_t* d_expired_keys,
+                      uint64_t max_expired, void* stream) {
+  if (!t || now >= (1u << 24)) return MONO_EINVAL;
+  return launch_expire_sweep(t->view, now, d_n_expired, d_expired_keys, d_expired_keys ? max_expired : 0,
+                             (hipStream_t)stream) == hipSuccess
+             ? MONO_OK
+             : MONO_EHIP;
+}
+
+int mono_table_stats(mono_table* t, mono_stats* h_out, void* stream) {
+  if (!t || !h_out) return MONO_EINVAL;
+  Control c;
+  if (hipMemcpyAsync(&c, t->view.ctl, sizeof(Control), hipMemcpyDeviceToHost, (hipStream_t)stream) != hipSuccess ||
+      hipStreamSynchronize((hipStream_t)stream) != hipSuccess)
+    return MONO_EHIP;
+  h_out->capacity = t->view.capacity;
+  h_out->size = t->view.capacity - (uint64_t)(c.free_n < 0 ? 0 : c.free_n);
+  h_out->n_admitted = c.n_admitted;
+  h_out->n_expired = c.n_expired;
+  h_out->n_insert_failed = c.n_insert_failed;
+  h_out->n_lost = c.n_lost;
+  h_out->n_full = c.n_full;
+  h_out->stash_size = c.stash_n < kStashCap ? c.stash_n : kStashCap;
+  h_out->max_chain = c.max_chain;
+  return MONO_OK;
+}
+
+int mono_table_export(mono_table* t, int64_t* d_keys, int32_t* d_row, uint32_t* d_last_seen, int64_t* d_slot,
+                      float* d_values, float* d_acc, uint64_t max_n, uint64_t* h_n, void* stream) {
+  if (!t || !h_n) return MONO_EINVAL;
+  if ((d_values || d_acc) && !d_row) return MONO_EINVAL;  // values are gathered through the row indices
+  hipStream_t s = (hipStream_t)stream;
+  if (launch_export(t->view, d_keys, d_row, d_last_seen, d_slot, max_n, s) != hipSuccess) return MONO_EHIP;
+  unsigned long long n = 0;
+  if (hipMemcpyAsync(&n, &t->view.ctl->scratch[1], sizeof(n), hipMemcpyDeviceToHost, s) != hipSuccess ||
+      hipStreamSynchronize(s) != hipSuccess)
+    return MONO_EHIP;
+  *h_n = n;
+  const uint64_t wrote = n < max_n ? n : max_n;
+  if ((d_values || d_acc) && wrote) {
+    if (launch_export_values(t->view, d_row, wrote, d_values, d_acc, s) != hipSuccess) return MONO_EHIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return MONO_EHIP;
+  }
+  return MONO_OK;
+}
+
+int mono_filter_export(mono_table* t, uint32_t* d_words, uint64_t first, uint64_t count, void* stream) {
+  if (!t || first + count > t->view.n_filter || (count && !d_words)) return MONO_EINVAL;
+  if (launch_filter_export(t->view, d_words, first, count, (hipStream_t)stream) != hipSuccess) return MONO_EHIP;
+  return hipStreamSynchronize((hipStream_t)stream) == hipSuccess ? MONO_OK : MONO_EHIP;
+}
+
+}  // extern "C"

@@ -86,10 +86,11 @@ def check_placement(dump, capacity, bucket, seed):
 
 def rows_close(got, ref, rtol):
     """Per row: ||got - ref||_inf <= rtol * max(||ref||_inf, tiny).  Returns the worst ratio."""
+    if ref.shape[0] == 0:
+        assert np.asarray(got).size == 0
+        return 0.0
     got = np.asarray(got, dtype=np.float64).reshape(ref.shape[0], -1)
     ref = np.asarray(ref, dtype=np.float64).reshape(ref.shape[0], -1)
-    if ref.shape[0] == 0:
-        return 0.0
     scale = np.maximum(np.abs(ref).max(axis=1), 1e-30)
     err = np.abs(got - ref).max(axis=1) / scale
     worst = float(err.max())

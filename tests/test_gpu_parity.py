@@ -1,0 +1,204 @@
+"""Device library vs CPU oracle on the same seeded inputs, through the C ABI (needs an MI355X).
+
+Equality is on semantics, not layout: admitted key set, last_seen, counter words and expired sets
+bit-exact; rows bit-exact until an optimizer step touches them; pooled sums, updated rows and
+accumulators within rtol 1e-5 (fp32 rows) / 1e-2 (bf16 rows) per row in the infinity norm.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import Oracle
+from paper_2209_07663_amd import synth
+from tests import table_checks as tc
+
+pytestmark = pytest.mark.gpu
+
+RTOL_F32, RTOL_BF16 = 1e-5, 1e-2
+
+
+@pytest.fixture(scope="module")
+def dev():
+    assert torch.cuda.is_available(), "gpu tests need a GPU"
+    return torch.device("cuda:0")
+
+
+def make_table(wl, seed, max_ids, dev):
+    from paper_2209_07663_amd.binding import Table
+    return Table(wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, max_ids=max_ids,
+                 max_bags=max(wl.n_bags, 1), device=dev)
+
+
+def make_oracle(wl, seed):
+    return Oracle(wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, kind="cuckoo")
+
+
+def compare_step(tab, orc, batch, dev, rtol, exact_rows, train, lr=0.05, eps=1e-8, sweep_at=None, log=None):
+    keys_h, offs_h = batch["keys"], batch["offsets"]
+    step = batch["step"]
+    keys = torch.from_numpy(keys_h).to(dev)
+    offs = torch.from_numpy(offs_h).to(dev)
+    rows = tab.mono_lookup_or_insert(keys, step)
+    present = orc.lookup_or_insert(keys_h, step)
+    rows_h = rows.cpu().numpy()
+    assert ((rows_h >= 0) == present).all(), "presence differs at step %d" % step
+    assert (rows_h >= -1).all()
+    d = tab.mono_table_export()
+    # the key -> row map handed out is the one stored
+    pos = np.searchsorted(d["keys"].view(np.uint64), keys_h[present].view(np.uint64))
+    assert (d["row"][pos] == rows_h[present]).all()
+    st = tab.mono_table_stats()
+    assert st["n_insert_failed"] == 0 and st["n_lost"] == 0 and st["n_full"] == 0 and orc.insert_failures == 0
+    tc.check_placement(d, tab.capacity, 8, tab_seed(tab))
+    tc.assert_same_table(d, orc.dump(), exact_rows=exact_rows, rtol=rtol)
+    pooled = tab.mono_gather_pool(rows, offs).cpu().numpy()
+    worst = tc.rows_close(pooled, orc.pool(keys_h, offs_h), rtol)
+    if train:
+        grad_h = batch["grad"]
+        tab.mono_apply_grad_adagrad(rows, offs, torch.from_numpy(grad_h).to(dev), lr, eps)
+        orc.apply_grad_adagrad(keys_h, offs_h, grad_h, lr, eps)
+        tc.assert_same_table(tab.mono_table_export(), orc.dump(), exact_rows=False, rtol=rtol)
+    if sweep_at is not None:
+        n_exp = torch.zeros(1, dtype=torch.int64, device=dev)
+        out = torch.full((tab.capacity,), -7, dtype=torch.int64, device=dev)
+        tab.mono_expire_sweep(sweep_at, n_exp, out)
+        want = orc.expire_sweep(sweep_at)
+        n = int(n_exp.item())
+        got = np.sort(out[:n].cpu().numpy().view(np.uint64)).view(np.int64)
+        assert n == want.shape[0] and (got == want).all(), "expired sets differ at step %d" % step
+        tc.assert_same_table(tab.mono_table_export(), orc.dump(), exact_rows=exact_rows and not train, rtol=rtol)
+    if log is not None:
+        log.append((step, int(present.sum()), d["keys"].shape[0], worst))
+
+
+_SEEDS = {}
+
+
+def tab_seed(tab):
+    return _SEEDS[id(tab)]
+
+
+def run_stream(wl, seed, steps, dev, train=False, sweep=False, check_filter=True):
+    tab = make_table(wl, seed, max_ids=int(wl.n_bags * (wl.poisson_lam + 1) * 1.3) + 64, dev=dev)
+    _SEEDS[id(tab)] = seed
+    orc = make_oracle(wl, seed)
+    drift = synth.DriftMap(wl, seed) if wl.drift_frac > 0 else None
+    rtol = RTOL_BF16 if wl.bf16 else RTOL_F32
+    log = []
+    for step in range(steps):
+        b = synth.make_batch(wl, seed, step, with_grad=train, drift=drift)
+        compare_step(tab, orc, b, dev, rtol, exact_rows=not train, train=train, lr=wl.lr, eps=wl.eps,
+                     sweep_at=step if sweep else None, log=log)
+        if check_filter:
+            assert (tab.mono_filter_export() == orc.filter_words()).all(), "counter words differ at step %d" % step
+    tab.close()
+    return log
+
+
+def test_config1_lookup_and_gather(dev):
+    """configs[0]: 2^16 rows, dim 16, 4096 uniform IDs, threshold 1, lookup_or_insert + gather only."""
+    wl = synth.CONFIGS["cfg1"]
+    log = run_stream(wl, seed=1, steps=2, dev=dev)
+    assert log[0][1] == 4096                      # everything admitted on first sight
+
+
+def test_forward_zipf_threshold3_several_steps(dev):
+    """configs[1] shapes (26 slots, Poisson(3)+1, Zipf 1.05 over 2^32, threshold 3) at 4096 samples."""
+    wl = synth.scaled(synth.CONFIGS["cfg2"], samples=4096, capacity=1 << 18)
+    log = run_stream(wl, seed=2, steps=5, dev=dev)
+    assert log[-1][2] > log[0][2] > 0             # keys keep crossing the threshold
+
+
+def test_train_step_fp32(dev):
+    """configs[2] shapes (40 slots, Poisson(4)+1, Zipf 1.1, dim 64, Adagrad) at 2048 samples."""
+    wl = synth.scaled(synth.CONFIGS["cfg3"], samples=2048, capacity=1 << 19)
+    run_stream(wl, seed=3, steps=4, dev=dev, train=True)
+
+
+def test_streaming_drift_with_expiry(dev):
+    """configs[3] shapes: threshold 5, expiry, rotating hot set, sweep every step (short expiry here)."""
+    from dataclasses import replace
+    wl = replace(synth.scaled(synth.CONFIGS["cfg4"], samples=2048, capacity=1 << 17, drift_ranks=1 << 15),
+                 expire_steps=3, freq_threshold=3, drift_frac=0.3)
+    log = run_stream(wl, seed=4, steps=12, dev=dev, train=True, sweep=True)
+    assert log[-1][2] > 0
+
+
+def test_train_step_bf16_rows(dev):
+    """configs[4] shapes: bf16 rows, dim 64, one ID per bag, Zipf 1.2 over 2^63, threshold 2, expiry."""
+    wl = synth.scaled(synth.CONFIGS["cfg5"], samples=16384, capacity=1 << 18)
+    run_stream(wl, seed=5, steps=4, dev=dev, train=True, sweep=True)
+
+
+@pytest.mark.parametrize("dim", [4, 24, 128, 256])
+def test_other_dims(dev, dim):
+    from dataclasses import replace
+    wl = replace(synth.scaled(synth.CONFIGS["cfg3"], samples=512, capacity=1 << 16), dim=dim, slots=8)
+    run_stream(wl, seed=6 + dim, steps=3, dev=dev, train=True)
+
+
+def test_edge_cases(dev):
+    from paper_2209_07663_amd.binding import Table, MonoError
+    seed = 77
+    tab = Table(1 << 10, 8, seed, freq_threshold=2, expire_steps=2, max_ids=1 << 12, max_bags=1 << 12, device=dev)
+    _SEEDS[id(tab)] = seed
+    orc = Oracle(1 << 10, 8, seed, 2, 2, False, kind="cuckoo")
+    # empty batch
+    empty = torch.empty(0, dtype=torch.int64, device=dev)
+    assert tab.mono_lookup_or_insert(empty, 0).shape[0] == 0
+    # empty bags, padding keys, one key repeated across a whole batch (several waves of duplicates)
+    keys_h = np.concatenate([np.full(1000, 42), [-1, -1, 7, 7, 9], np.full(37, 1 << 62)]).astype(np.int64)
+    offs_h = np.array([0, 0, 1000, 1000, 1003, 1005, 1042, 1042], dtype=np.int64)
+    grad_h = np.random.default_rng(0).standard_normal((7, 8)).astype(np.float32)
+    for step in range(4):
+        compare_step(tab, orc, {"keys": keys_h, "offsets": offs_h, "grad": grad_h, "step": step}, dev, RTOL_F32,
+                     exact_rows=False, train=True, sweep_at=step)
+    # nothing seen for 2 steps: everything expires
+    compare_step(tab, orc, {"keys": np.array([5], dtype=np.int64), "offsets": np.array([0, 1], dtype=np.int64),
+                            "step": 6}, dev, RTOL_F32, exact_rows=False, train=False, sweep_at=6)
+    assert tab.mono_table_stats()["size"] == 0
+    # argument errors are reported, not executed
+    big = torch.zeros((1 << 12) + 1, dtype=torch.int64, device=dev)
+    with pytest.raises(MonoError):
+        tab.mono_lookup_or_insert(big, 7)
+    with pytest.raises(MonoError):
+        tab.mono_lookup_or_insert(big[:4], 5)      # step went backwards
+    with pytest.raises(MonoError):
+        Table(1000, 8, seed, device=dev)           # capacity not a power of two
+    tab.close()
+
+
+def test_high_load_without_failed_chains(dev):
+    """Drive a table to load 0.9 (configs[3] asks for it) and check every invariant."""
+    from paper_2209_07663_amd.binding import Table
+    seed, cap = 9, 1 << 16
+    tab = Table(cap, 4, seed, freq_threshold=1, max_ids=1 << 16, device=dev)
+    _SEEDS[id(tab)] = seed
+    orc = Oracle(cap, 4, seed, 1, 0, False, kind="cuckoo")
+    rng = np.random.default_rng(1)
+    all_keys = rng.permutation(1 << 24)[: int(0.9 * cap)].astype(np.int64) * 1000003
+    for step, chunk in enumerate(np.array_split(all_keys, 6)):
+        offs = np.arange(chunk.shape[0] + 1, dtype=np.int64)
+        compare_step(tab, orc, {"keys": chunk, "offsets": offs, "step": step}, dev, RTOL_F32, exact_rows=True,
+                     train=False)
+    st = tab.mono_table_stats()
+    assert st["size"] == all_keys.shape[0] and st["size"] >= 0.9 * cap - 1
+    tab.close()
+
+
+def test_hot_key_gradient_reduction_is_pairwise(dev):
+    """One key holding half of a 400k-occurrence batch: its gradient sum must still meet 1e-5."""
+    from paper_2209_07663_amd.binding import Table
+    seed, dim, n_bags = 10, 32, 100000
+    tab = Table(1 << 16, dim, seed, freq_threshold=1, max_ids=1 << 19, max_bags=n_bags, device=dev)
+    _SEEDS[id(tab)] = seed
+    orc = Oracle(1 << 16, dim, seed, 1, 0, False, kind="cuckoo")
+    rng = np.random.default_rng(2)
+    offs_h = np.arange(0, 4 * n_bags + 1, 4, dtype=np.int64)
+    keys_h = rng.integers(0, 5000, size=4 * n_bags).astype(np.int64)
+    keys_h[rng.random(4 * n_bags) < 0.5] = 123456789
+    grad_h = (rng.standard_normal((n_bags, dim)) * 0.1).astype(np.float32)
+    for step in range(2):
+        compare_step(tab, orc, {"keys": keys_h, "offsets": offs_h, "grad": grad_h, "step": step}, dev, RTOL_F32,
+                     exact_rows=False, train=True)
+    tab.close()
