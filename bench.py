@@ -1,0 +1,238 @@
+#!/usr/bin/env python3
+"""Benchmark of the collisionless-table hot path on one MI355X.
+
+A step = one pass of the whole path over one fresh synthetic batch:
+lookup_or_insert -> gather_pool -> apply_grad_adagrad -> expire_sweep.
+Default workload: configs[1] of the benchmark spec (capacity 2^24, dim 32 fp32, 65536 samples x 26 slots,
+Poisson(3)+1 IDs per bag, Zipf(1.05) over 2^32, threshold 3).  Prints ONE JSON line.
+
+    python bench.py --gpus 1 --steps 10 --warmup 3
+"""
+import argparse
+import json
+import multiprocessing as mp
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2209_07663_amd import synth  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
+SECTOR = 32             # bytes: smallest HBM access counted for a random 4/8-byte word
+
+
+def _gen(args):
+    wl_name, seed, step = args
+    wl = synth.CONFIGS[wl_name]
+    return synth.make_batch(wl, seed, step, with_grad=True)
+
+
+def generate_batches(wl_name, seed, steps, workers):
+    wl = synth.CONFIGS[wl_name]
+    if wl.drift_frac > 0:  # the rotating rank->ID map is sequential state
+        drift = synth.DriftMap(wl, seed)
+        return [synth.make_batch(wl, seed, s, with_grad=True, drift=drift) for s in steps]
+    with mp.get_context("fork").Pool(workers) as pool:
+        return pool.map(_gen, [(wl_name, seed, s) for s in steps], chunksize=1)
+
+
+def cpu_baseline(wl, seed, batches, budget_s):
+    """The oracle as it stands (single thread), full step on the first batches from an empty table."""
+    from oracle import Oracle
+    o = Oracle(wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, kind="cuckoo")
+    ids, t0, used = 0, time.perf_counter(), 0
+    for b in batches:
+        o.lookup_or_insert(b["keys"], b["step"])
+        o.pool(b["keys"], b["offsets"])
+        o.apply_grad_adagrad(b["keys"], b["offsets"], b["grad"], wl.lr, wl.eps)
+        o.expire_sweep(b["step"])
+        ids += b["keys"].shape[0]
+        used += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    return {"value": ids / dt, "unit": "IDs/s", "cores": 1, "kind": "oracle",
+            "sample": "full step (lookup_or_insert+pool+adagrad+sweep) on the first %d batches of the same workload, "
+                      "from an empty table, %.1f s" % (used, dt),
+            "host_cpus_present": os.cpu_count()}
+
+
+def algorithmic_bytes(kernel, s, wl):
+    """Compulsory bytes of ONE launch of `kernel` for a batch with statistics `s`."""
+    e = 2 if wl.bf16 else 4
+    row = wl.dim * e
+    n, nb = s["n"], s["n_bags"]
+    if kernel == "probe_count":
+        return 8 * n + 4 * n + 128 * s["u_hit"] + SECTOR * s["u_hit"] + 128 * s["u_miss"] + 2 * SECTOR * s["u_miss"]
+    if kernel == "admit_elect":
+        return 4 * n + 8 * s["n_miss"] + SECTOR * s["u_miss"] + 16 * s["u_new"]
+    if kernel == "insert":
+        return s["u_new"] * (row + 128 + 4 + 8 + 8 + 4)
+    if kernel == "resolve":
+        return 4 * n
+    if kernel == "gather_pool":
+        return 4 * n + 8 * (nb + 1) + row * s["u_present"] + 4 * wl.dim * nb
+    if kernel == "expand_bags":
+        return 8 * (nb + 1) + 4 * n
+    if kernel == "sort_hist":
+        return 4 * n
+    if kernel == "sort_scatter":
+        return 16 * n
+    if kernel == "seg_reduce":
+        return 8 * n + 4 * wl.dim * nb + 2 * row * s["u_present"] + 8 * s["u_present"]
+    if kernel == "sweep_find":
+        return 8 * wl.capacity
+    return 0
+
+
+def step_bytes(s, wl):
+    """Compulsory bytes of a whole step (forward + backward; sweep when the table expires keys)."""
+    e = 2 if wl.bf16 else 4
+    row = wl.dim * e
+    n, nb = s["n"], s["n_bags"]
+    fwd = (8 * n + 8 * (nb + 1) + 128 * (s["u_hit"] + s["u_miss"]) + 2 * SECTOR * s["u_miss"] + 4 * s["u_present"]
+           + row * s["u_present"] + row * s["u_new"] + 4 * wl.dim * nb)
+    bwd = 4 * wl.dim * nb + 2 * row * s["u_present"] + 8 * s["u_present"]
+    sweep = 8 * wl.capacity if wl.expire_steps else 0
+    return fwd + bwd + sweep
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg2", choices=sorted(synth.CONFIGS))
+    ap.add_argument("--prefill", type=int, default=8, help="untimed steps that bring the table to a steady state")
+    ap.add_argument("--profile-steps", type=int, default=4, help="extra steps run with per-kernel HIP events")
+    ap.add_argument("--seed", type=int, default=1)
+    ap.add_argument("--cpu-budget", type=float, default=12.0, help="seconds of oracle time; 0 = skip")
+    ap.add_argument("--workers", type=int, default=min(16, os.cpu_count() or 8))
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives are part of it); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    wl = synth.CONFIGS[args.workload]
+    n_steps = args.prefill + args.warmup + args.steps + args.profile_steps
+    t_gen = time.perf_counter()
+    batches = generate_batches(args.workload, args.seed, list(range(n_steps)), args.workers)
+    t_gen = time.perf_counter() - t_gen
+    print("[bench] generated %d batches of %s in %.1f s" % (n_steps, wl.name, t_gen), file=sys.stderr, flush=True)
+
+    cpu = None
+    if args.cpu_budget > 0:
+        cpu = cpu_baseline(wl, args.seed, batches, args.cpu_budget)
+        print("[bench] oracle: %.3g IDs/s" % cpu["value"], file=sys.stderr, flush=True)
+
+    import torch
+    from paper_2209_07663_amd.binding import Table
+    dev = torch.device("cuda:0")
+    max_ids = max(b["keys"].shape[0] for b in batches)
+    tab = Table(wl.capacity, wl.dim, args.seed, wl.freq_threshold, wl.expire_steps, wl.bf16, max_ids=max_ids,
+                max_bags=wl.n_bags, device=dev)
+    dbatches = []
+    for b in batches:  # inputs resident in HBM before anything is timed
+        dbatches.append({"keys": torch.from_numpy(b["keys"]).to(dev), "offsets": torch.from_numpy(b["offsets"]).to(dev),
+                         "grad": torch.from_numpy(b["grad"]).to(dev), "step": b["step"], "n": b["keys"].shape[0]})
+    rows = torch.empty(max_ids, dtype=torch.int32, device=dev)
+    pooled = torch.empty((wl.n_bags, wl.dim), dtype=torch.float32, device=dev)
+    n_exp = torch.zeros(1, dtype=torch.int64, device=dev)
+
+    def run_step(b):
+        r = rows[: b["n"]]
+        tab.mono_lookup_or_insert(b["keys"], b["step"], r)
+        tab.mono_gather_pool(r, b["offsets"], pooled)
+        tab.mono_apply_grad_adagrad(r, b["offsets"], b["grad"], wl.lr, wl.eps)
+        tab.mono_expire_sweep(b["step"], n_exp, None)
+
+    it = iter(dbatches)
+    for _ in range(args.prefill + args.warmup):
+        run_step(next(it))
+    torch.cuda.synchronize()
+    load_before = tab.mono_table_stats()["size"] / wl.capacity
+
+    timed = [next(it) for _ in range(args.steps)]
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in timed]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for b, (e0, e1) in zip(timed, ev):
+        e0.record()
+        run_step(b)
+        e1.record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ids = sum(b["n"] for b in timed)
+    step_ms = [e0.elapsed_time(e1) for e0, e1 in ev]
+    st = tab.mono_table_stats()
+    assert st["n_insert_failed"] == 0 and st["n_lost"] == 0 and st["n_full"] == 0, st
+
+    # per-kernel pass (HIP events inside the library, on the stream the kernels run on) + batch statistics
+    stats, prof = [], {}
+    tab.mono_profile_enable(True)
+    for _ in range(args.profile_steps):
+        b = next(it)
+        adm0 = tab.mono_table_stats()["n_admitted"]
+        r = rows[: b["n"]]
+        tab.mono_lookup_or_insert(b["keys"], b["step"], r)
+        torch.cuda.synchronize()
+        u_all = torch.unique(b["keys"]).numel()
+        present = r >= 0
+        u_present = torch.unique(b["keys"][present]).numel()
+        u_new = tab.mono_table_stats()["n_admitted"] - adm0
+        # miss occurrences = occurrences of keys absent before the call: absent now, or admitted in this call
+        u_hit = u_present - u_new
+        stats.append({"n": b["n"], "n_bags": wl.n_bags, "u": u_all, "u_present": u_present, "u_new": u_new,
+                      "u_hit": u_hit, "u_miss": u_all - u_hit, "n_miss": int((~present).sum().item())})
+        tab.mono_gather_pool(r, b["offsets"], pooled)
+        tab.mono_apply_grad_adagrad(r, b["offsets"], b["grad"], wl.lr, wl.eps)
+        tab.mono_expire_sweep(b["step"], n_exp, None)
+    prof = tab.mono_profile_read()
+    tab.mono_profile_enable(False)
+
+    roofline, kernels = None, {}
+    if prof and stats:
+        mean = {k: float(np.mean([s[k] for s in stats])) for k in stats[0]}
+        for name, (ms, launches) in prof.items():
+            avg_ms = ms / launches
+            ab = algorithmic_bytes(name, mean, wl)
+            kernels[name] = {"avg_ms": round(avg_ms, 4), "launches_per_step": launches / len(stats),
+                             "ms_per_step": round(ms / len(stats), 4),
+                             "algo_GBps": round(ab / avg_ms / 1e6, 1) if ab else None}
+        dom = max(prof, key=lambda k: prof[k][0])
+        achieved = algorithmic_bytes(dom, mean, wl) / (prof[dom][0] / prof[dom][1]) / 1e6
+        roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None}
+        sb = step_bytes(mean, wl)
+        step_roof = {"algorithmic_bytes_per_step": int(sb),
+                     "achieved_GBps": round(sb / (np.median(step_ms) * 1e-3) / 1e9, 1),
+                     "frac_of_hbm_peak": round(sb / (np.median(step_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                     "batch_stats": {k: int(v) for k, v in mean.items()}}
+    else:
+        step_roof = None
+
+    out = {
+        "metric": "sparse IDs/sec per training step (lookup+pool+update)",
+        "value": ids / elapsed, "unit": "IDs/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if wl.bf16 else "f32", "data": "synthetic",
+        "config": {"workload": "%s: capacity 2^%d, dim %d, %d samples x %d slots, %s IDs, threshold %d, expire %d"
+                               % (wl.name, wl.capacity.bit_length() - 1, wl.dim, wl.samples, wl.slots,
+                                  "Zipf(%.2f)" % wl.alpha if wl.dist == "zipf" else "uniform", wl.freq_threshold,
+                                  wl.expire_steps),
+                   "ids_per_step": ids // args.steps, "prefill_steps": args.prefill,
+                   "load_factor": round(load_before, 4), "step": "lookup_or_insert+gather_pool+apply_grad_adagrad+expire_sweep"},
+        "median_step_ms_events": float(np.median(step_ms)), "min_step_ms_events": float(np.min(step_ms)),
+        "roofline": roofline, "step_roofline": step_roof, "kernels": kernels, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

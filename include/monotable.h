@@ -128,6 +128,15 @@ int mono_table_export(mono_table* t, int64_t* d_keys, int32_t* d_row, uint32_t* 
  * There are 4 * capacity counters. */
 int mono_filter_export(mono_table* t, uint32_t* d_words, uint64_t first, uint64_t count, void* stream);
 
+/* Benchmark instrumentation.  While enabled, every kernel launched for this table is bracketed by
+ * two HIP events on its stream (this costs a little, so throughput is measured with it off).
+ * mono_profile_read synchronises the device, then reports, for each kernel launched since the last
+ * read, its name (static string), the sum of its durations in milliseconds and its launch count;
+ * at most max_kernels entries are written, *h_n receives how many. */
+int mono_profile_enable(mono_table* t, int on);
+int mono_profile_read(mono_table* t, const char** h_names, double* h_ms, uint64_t* h_launches, uint32_t max_kernels,
+                      uint32_t* h_n);
+
 /* Static description of an error code. */
 const char* mono_strerror(int err);
 

@@ -35,6 +35,9 @@ SYMBOLS = {
     "mono_table_stats": (ctypes.c_int, [_vp, ctypes.POINTER(mono_stats), _vp]),
     "mono_table_export": (ctypes.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _u64, ctypes.POINTER(_u64), _vp]),
     "mono_filter_export": (ctypes.c_int, [_vp, _vp, _u64, _u64, _vp]),
+    "mono_profile_enable": (ctypes.c_int, [_vp, ctypes.c_int]),
+    "mono_profile_read": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_double),
+                                         ctypes.POINTER(_u64), _u32, ctypes.POINTER(_u32)]),
     "mono_strerror": (ctypes.c_char_p, [ctypes.c_int]),
 }
 
@@ -175,6 +178,16 @@ class Table:
             d["rows"] = vals.cpu().numpy()[order]
             d["acc"] = acc.cpu().numpy()[order]
         return d
+
+    def mono_profile_enable(self, on):
+        _check(self.lib.mono_profile_enable(self.h, int(on)), "mono_profile_enable")
+
+    def mono_profile_read(self):
+        """{kernel name: (total ms, launches)} since the last read."""
+        cap = 32
+        names, ms, cnt, n = (ctypes.c_char_p * cap)(), (ctypes.c_double * cap)(), (_u64 * cap)(), _u32()
+        _check(self.lib.mono_profile_read(self.h, names, ms, cnt, cap, ctypes.byref(n)), "mono_profile_read")
+        return {names[i].decode(): (ms[i], int(cnt[i])) for i in range(n.value)}
 
     def mono_filter_export(self, first=0, count=None):
         count = 4 * self.capacity - first if count is None else count

@@ -16,15 +16,22 @@ constexpr int32_t kRowMiss = -2;            // rows_out, between the kernels of 
 // rows_out values <= -3 between the kernels of one call: duplicate of an admitted key, encodes the
 // position of that key in the per-call dedup set
 
-// One bucket = one 128-byte line: the first 64-byte half holds the keys that a probe compares, the
-// second half the row index and last-seen step of each slot, so that a hit costs one line and a
-// miss only touches the key halves.
+// One bucket = one 128-byte line (the unit the memory system fetches): eight keys, then eight
+// `meta` words = last-seen step << 32 | row index.  A probe costs one line per bucket; the row and
+// the stamp of a hit sit in the line already fetched.  meta == kNoMeta: slot free or being written.
 struct __attribute__((aligned(128))) Bucket {
   uint64_t key[kBucket];
-  uint32_t row[kBucket];
-  uint32_t seen[kBucket];
+  unsigned long long meta[kBucket];
 };
 static_assert(sizeof(Bucket) == 128, "bucket must be one 128-byte line");
+constexpr unsigned long long kNoMeta = ~0ull;
+__host__ __device__ inline uint32_t meta_row(unsigned long long m) { return (uint32_t)m; }
+__host__ __device__ inline uint32_t meta_seen(unsigned long long m) { return (uint32_t)(m >> 32); }
+__host__ __device__ inline unsigned long long make_meta(uint32_t row, uint32_t seen) {
+  return ((unsigned long long)seen << 32) | row;
+}
+constexpr int kWinLists = 64;               // sub-lists of elected occurrences (spreads the append counter)
+constexpr int kWinStride = 32;              // u32 words between two sub-list counters (one 128-byte line each)
 
 struct StashEntry {
   uint64_t key;
@@ -51,6 +58,12 @@ struct TableView {
   StashEntry* stash;         // [kStashCap]
   unsigned long long* dset;  // [dset_size] per-call dedup set: epoch << 32 | occurrence index
   int32_t* dset_row;         // [dset_size] row of the key that owns the dedup-set position
+  uint2* win_list;           // [kWinLists * win_cap] (occurrence, dedup-set position) of elected occurrences
+  uint32_t* win_cnt;         // [kWinLists * kWinStride] fill of each sub-list (zero between calls)
+  uint64_t win_cap;
+  uint32_t* sweep_list;      // [kWinLists * sweep_cap] slots found expired by the running sweep
+  uint32_t* sweep_cnt;       // [kWinLists * kWinStride]
+  uint64_t sweep_cap;
   uint64_t capacity;
   uint64_t n_buckets;        // per sub-table
   uint64_t n_filter;

@@ -63,17 +63,17 @@ __global__ __launch_bounds__(256) void gather_pool_kernel(const E* __restrict__ 
 }
 
 hipError_t launch_gather_pool(const TableView& t, const int32_t* d_rows, const int64_t* d_offsets, uint64_t n_bags,
-                              float* d_out, hipStream_t stream) {
+                              float* d_out, hipStream_t stream, Profiler* prof) {
   if (n_bags == 0) return hipSuccess;
   uint32_t group_log2 = 0;
   while ((4u << group_log2) < t.dim) ++group_log2;
   uint64_t threads = n_bags << group_log2;
   dim3 block(256), grid((unsigned)((threads + 255) / 256));
   if (t.bf16)
-    hipLaunchKernelGGL(gather_pool_kernel<uint16_t>, grid, block, 0, stream, (const uint16_t*)t.rows, d_rows, d_offsets,
+    MONO_LAUNCH(prof, K_GATHER_POOL, stream, gather_pool_kernel<uint16_t>, grid, block, (const uint16_t*)t.rows, d_rows, d_offsets,
                        n_bags, t.dim, group_log2, d_out);
   else
-    hipLaunchKernelGGL(gather_pool_kernel<float>, grid, block, 0, stream, (const float*)t.rows, d_rows, d_offsets,
+    MONO_LAUNCH(prof, K_GATHER_POOL, stream, gather_pool_kernel<float>, grid, block, (const float*)t.rows, d_rows, d_offsets,
                        n_bags, t.dim, group_log2, d_out);
   return hipGetLastError();
 }

@@ -2,6 +2,7 @@
 #pragma once
 
 #include "common.h"
+#include "profile.h"
 
 namespace mono {
 
@@ -25,23 +26,23 @@ inline uint64_t sort_units(uint64_t n) { return (n + kSortItemsPerWave - 1) / kS
 inline uint64_t reduce_chunks(uint64_t n) { return (n + kChunk - 1) / kChunk; }
 
 hipError_t launch_lookup_or_insert(const TableView& t, const int64_t* d_keys, uint64_t n, uint32_t step, uint32_t epoch,
-                                   int32_t* d_rows_out, hipStream_t stream);
+                                   int32_t* d_rows_out, hipStream_t stream, Profiler* prof);
 
 hipError_t launch_gather_pool(const TableView& t, const int32_t* d_rows, const int64_t* d_offsets, uint64_t n_bags,
-                              float* d_out, hipStream_t stream);
+                              float* d_out, hipStream_t stream, Profiler* prof);
 
 hipError_t launch_apply_grad_adagrad(const TableView& t, const UpdateWorkspace& ws, const int32_t* d_rows, uint64_t n,
                                      const int64_t* d_offsets, uint64_t n_bags, const float* d_grad, float lr, float eps,
-                                     hipStream_t stream);
+                                     hipStream_t stream, Profiler* prof);
 
 // Stable LSD radix sort of (key, value) pairs on the low `bits` bits of the key.  Input in
 // (key_a, val_a) unless `keys_in` is given (first pass then reads keys from there, transformed by
 // min(key, clamp) on unsigned values); returns which buffer pair holds the result (0 = a, 1 = b).
 hipError_t launch_sort_pairs(const UpdateWorkspace& ws, const uint32_t* keys_in, uint32_t clamp, uint64_t n,
-                             uint32_t bits, int* result_in_b, hipStream_t stream);
+                             uint32_t bits, int* result_in_b, hipStream_t stream, Profiler* prof);
 
 hipError_t launch_expire_sweep(const TableView& t, uint32_t now, uint64_t* d_n_expired, int64_t* d_expired_keys,
-                               uint64_t max_expired, hipStream_t stream);
+                               uint64_t max_expired, hipStream_t stream, Profiler* prof);
 
 hipError_t launch_export(const TableView& t, int64_t* d_keys, int32_t* d_row, uint32_t* d_last_seen, int64_t* d_slot,
                          uint64_t max_n, hipStream_t stream);

@@ -1,21 +1,28 @@
 // lookup_or_insert: cuckoo probe, count-before-admit, insertion with bounded eviction chain,
 // resolve (paper section 2.1; batch semantics of the build's contract).
 //
-// Three kernels per call, each one thread per occurrence:
-//   probe_count   hit -> row index + last-seen stamp; miss -> touch the key's occurrence counter
-//   admit_insert  (after ALL counts) miss with counter >= threshold -> elect one occurrence per
-//                 distinct key through the per-call dedup set; the elected one takes a row from the
-//                 free stack, inserts the key (CAS on 64-bit key slots, eviction chain), and its
-//                 wave initialises the row cooperatively
-//   resolve       duplicates of an admitted key pick up the row of the elected occurrence
+// Four kernels per call:
+//   probe_count   (thread per occurrence) hit -> row index + last-seen stamp; miss -> touch the
+//                 key's occurrence counter
+//   admit_elect   (thread per occurrence, after ALL counts) miss with counter >= threshold -> one
+//                 occurrence per distinct key is elected through the per-call dedup set and appended
+//                 to one of kWinLists lists (one atomic per block, spread over the lists: a single
+//                 append counter would serialise at ~12 ns per atomic on this machine)
+//   insert        (dense, grid-stride over the elected occurrences) take a row from the free stack
+//                 by rank (no atomics), insert the key (CAS on 64-bit key slots, eviction chain),
+//                 initialise the row with the whole wave
+//   resolve       duplicates of an admitted key pick up the row of the elected occurrence; one
+//                 thread settles the counters
 //
-// Slot protocol (no 128-bit atomics needed): a slot's `row` word doubles as its lock.
-//   free slot:      key == EMPTY, row == kNoRow
-//   claim:          CAS key EMPTY -> k; then seen, fence, row (publishing)
-//   evict:          old = exch(row, kNoRow); old == kNoRow -> slot is free or mid-write, try another;
-//                   else the caller owns the slot: read the victim's key/seen, write its own, fence,
-//                   publish row.  The victim continues in its other sub-table.
-// No thread ever waits for another one; every loop is bounded.
+// Slot protocol (no 128-bit atomics, no fences): a slot's `meta` word doubles as its lock.
+//   free slot:   key == EMPTY, meta == kNoMeta
+//   claim:       CAS key EMPTY -> k (wait for the result); then store meta (publishes row + stamp)
+//   evict:       old = exch(meta, kNoMeta); row(old) == kNoRow -> slot is free or mid-write, try
+//                another; else the caller owns the slot: vk = exch(key, k) (wait), then store meta.
+//                The victim (vk, old) continues in its other sub-table.
+// Every access in the protocol is an agent-scope atomic performed at the coherence point, and each
+// step consumes the result of the previous one, so no ordering fence is needed.  No thread ever
+// waits for another one; every loop is bounded.
 #include "common.h"
 #include "kernels.h"
 
@@ -67,8 +74,9 @@ __global__ __launch_bounds__(256) void probe_count_kernel(TableView t, const int
     j = find_in_bucket(b, k);
   }
   if (j >= 0) {
-    rows_out[i] = (int32_t)b->row[j];
-    if (b->seen[j] != step) b->seen[j] = step;
+    const unsigned long long m = b->meta[j];
+    rows_out[i] = (int32_t)meta_row(m);
+    if (meta_seen(m) != step) reinterpret_cast<uint32_t*>(&b->meta[j])[1] = step;  // high half = stamp
     return;
   }
   uint32_t sn = t.ctl->stash_n;
@@ -85,61 +93,124 @@ __global__ __launch_bounds__(256) void probe_count_kernel(TableView t, const int
   rows_out[i] = kRowMiss;
 }
 
+// ---- election ------------------------------------------------------------------------------------
+
+__global__ __launch_bounds__(256) void admit_elect_kernel(TableView t, const int64_t* __restrict__ keys, uint64_t n,
+                                                          uint32_t epoch, int32_t* rows_out) {
+  __shared__ uint32_t wave_cnt[4];
+  __shared__ uint32_t block_base;
+  const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const bool miss = i < n && rows_out[i] == kRowMiss;
+  bool winner = false;
+  uint64_t pos = 0;
+  if (miss) {
+    const uint64_t k = (uint64_t)keys[i];
+    unsigned long long* w = &t.filter[filter_index(t, k)];
+    const unsigned long long word = *w;
+    uint32_t cnt = (uint32_t)word;
+    if (cnt > 255u) {  // keep the unsaturated count from ever wrapping
+      atomicMin(w, (word & 0xFFFFFFFF00000000ull) | 255ull);
+      cnt = 255u;
+    }
+    if (cnt < t.freq_threshold) {
+      rows_out[i] = kRowAbsent;
+    } else {
+      // one occurrence per distinct key wins its position of the per-call dedup set
+      pos = mix64(k ^ t.s_dedup) & t.dset_mask;
+      const unsigned long long mine = ((unsigned long long)epoch << 32) | (unsigned long long)i;
+      for (;;) {
+        unsigned long long e = ld_agent(&t.dset[pos]);
+        if ((uint32_t)(e >> 32) != epoch) {
+          const unsigned long long old = atomicCAS(&t.dset[pos], e, mine);
+          if (old == e) {
+            winner = true;
+            break;
+          }
+          e = old;  // someone wrote this position in this call
+          if ((uint32_t)(e >> 32) != epoch) continue;
+        }
+        if ((uint64_t)keys[(uint32_t)e] == k) break;  // duplicate of the owner
+        pos = (pos + 1) & t.dset_mask;
+      }
+      if (!winner) rows_out[i] = -(int32_t)pos - 3;
+    }
+  }
+  // block-aggregated append to sub-list (blockIdx mod kWinLists)
+  const uint32_t wave = threadIdx.x >> 6;
+  const uint64_t wmask = __ballot(winner);
+  if (lane_id() == 0) wave_cnt[wave] = (uint32_t)__popcll(wmask);
+  __syncthreads();
+  const uint32_t list = blockIdx.x & (kWinLists - 1);
+  if (threadIdx.x == 0) {
+    const uint32_t total = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+    block_base = total ? atomicAdd(&t.win_cnt[list * kWinStride], total) : 0u;
+  }
+  __syncthreads();
+  if (winner) {
+    uint32_t p = block_base + (uint32_t)__popcll(wmask & lanes_below());
+    for (uint32_t w = 0; w < wave; ++w) p += wave_cnt[w];
+    t.win_list[(uint64_t)list * t.win_cap + p] = make_uint2((uint32_t)i, (uint32_t)pos);
+  }
+}
+
 // ---- insertion ---------------------------------------------------------------------------------
 
-__device__ inline bool try_claim(Bucket* b, uint64_t k, uint32_t row, uint32_t seen) {
-#pragma unroll 1
+__device__ inline void wait_all_memory_ops() {
+  __asm__ volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0);  // every load, store and atomic of this wave has been performed
+  __asm__ volatile("" ::: "memory");
+}
+
+__device__ inline bool try_claim(Bucket* b, uint64_t k, unsigned long long meta) {
+  // snapshot of the eight keys (may be stale: a slot seen free may be taken by now; the CAS decides)
+  const ulonglong2* kp = reinterpret_cast<const ulonglong2*>(b->key);
+  const ulonglong2 a0 = kp[0], a1 = kp[1], a2 = kp[2], a3 = kp[3];
+  const uint64_t snap[kBucket] = {a0.x, a0.y, a1.x, a1.y, a2.x, a2.y, a3.x, a3.y};
+#pragma unroll
   for (int l = 0; l < kBucket; ++l) {
-    if (ld_agent(&b->key[l]) != kEmptyKey) continue;
+    if (snap[l] != kEmptyKey) continue;
     if (atomicCAS((unsigned long long*)&b->key[l], (unsigned long long)kEmptyKey, (unsigned long long)k) ==
         (unsigned long long)kEmptyKey) {
-      st_agent(&b->seen[l], seen);
-      __threadfence();
-      st_agent(&b->row[l], row);
+      st_agent(&b->meta[l], meta);  // issued after the CAS has returned: publishes the slot
       return true;
     }
   }
   return false;
 }
 
-// Inserts (k, row, seen); k is not in the table and no other thread inserts the same key.
-__device__ void cuckoo_insert(const TableView& t, uint64_t k, uint32_t row, uint32_t seen) {
+// Inserts (k, meta); k is not in the table and no other thread inserts the same key.
+__device__ void cuckoo_insert(const TableView& t, uint64_t k, unsigned long long meta) {
   int side = 0;
   uint32_t chain = 0;
 #pragma unroll 1
   for (int kick = 0; kick < kMaxKicks; ++kick) {
     Bucket* b = &t.buckets[bucket_index(t, side, k)];
-    if (try_claim(b, k, row, seen)) goto done;
-    if (kick == 0 && try_claim(&t.buckets[bucket_index(t, 1, k)], k, row, seen)) goto done;
+    if (try_claim(b, k, meta)) goto done;
+    if (kick == 0 && try_claim(&t.buckets[bucket_index(t, 1, k)], k, meta)) goto done;
     // evict: take the lock of a published slot
-    uint32_t v0 = (uint32_t)(mix64(k + (uint64_t)kick) >> 61);
+    const uint32_t v0 = (uint32_t)(mix64(k + (uint64_t)kick) >> 61);
 #pragma unroll 1
     for (int tries = 0; tries < kBucket; ++tries) {
-      int l = (int)((v0 + (uint32_t)tries) & (kBucket - 1));
-      uint32_t old = atomicExch(&b->row[l], kNoRow);
-      if (old == kNoRow) continue;  // free or mid-write: not ours
-      __threadfence();
-      uint64_t vk = ld_agent(&b->key[l]);
-      uint32_t vs = ld_agent(&b->seen[l]);
-      st_agent(&b->key[l], k);
-      st_agent(&b->seen[l], seen);
-      __threadfence();
-      st_agent(&b->row[l], row);
+      const int l = (int)((v0 + (uint32_t)tries) & (kBucket - 1));
+      const unsigned long long old = atomicExch(&b->meta[l], kNoMeta);
+      if (meta_row(old) == kNoRow) continue;  // free or mid-write: not ours
+      const uint64_t vk = atomicExch((unsigned long long*)&b->key[l], (unsigned long long)k);
+      wait_all_memory_ops();  // the key exchange is performed before the slot is published again
+      st_agent(&b->meta[l], meta);
       k = vk;
-      row = old;
-      seen = vs;
+      meta = old;
       side = 1 - side;  // the victim continues in its other sub-table
       ++chain;
       break;
     }
   }
   {  // chain bound hit: keep the homeless element aside
-    uint32_t s = atomicAdd(&t.ctl->stash_n, 1u);
+    const uint32_t s = atomicAdd(&t.ctl->stash_n, 1u);
     atomicAdd(&t.ctl->n_insert_failed, 1ull);
     if (s < kStashCap) {
       t.stash[s].key = k;
-      t.stash[s].row = row;
-      t.stash[s].seen = seen;
+      t.stash[s].row = meta_row(meta);
+      t.stash[s].seen = meta_seen(meta);
     } else {
       atomicAdd(&t.ctl->n_lost, 1ull);
     }
@@ -155,102 +226,93 @@ __device__ inline void store_init<float>(float* rows, uint64_t idx, float v) { r
 template <>
 __device__ inline void store_init<uint16_t>(uint16_t* rows, uint64_t idx, float v) { rows[idx] = f32_to_bf16(v); }
 
+// Dense over the elected occurrences: winner number w of the call takes free_rows[free_n - 1 - w].
 template <typename E>
-__global__ __launch_bounds__(256) void admit_insert_kernel(TableView t, const int64_t* __restrict__ keys, uint64_t n,
-                                                           uint32_t step, uint32_t epoch, int32_t* rows_out) {
-  uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  bool miss = i < n && rows_out[i] == kRowMiss;
-  bool winner = false;
-  uint64_t k = 0, pos = 0;
-  if (miss) {
-    k = (uint64_t)keys[i];
-    unsigned long long* w = &t.filter[filter_index(t, k)];
-    unsigned long long word = *w;
-    uint32_t cnt = (uint32_t)word;
-    if (cnt > 255u) {  // keep the unsaturated count from ever wrapping
-      atomicMin(w, (word & 0xFFFFFFFF00000000ull) | 255ull);
-      cnt = 255u;
-    }
-    if (cnt < t.freq_threshold) {
-      rows_out[i] = kRowAbsent;
-    } else {
-      // one occurrence per distinct key wins its position of the per-call dedup set
-      pos = mix64(k ^ t.s_dedup) & t.dset_mask;
-      const unsigned long long mine = ((unsigned long long)epoch << 32) | (unsigned long long)i;
-      for (;;) {
-        unsigned long long e = ld_agent(&t.dset[pos]);
-        if ((uint32_t)(e >> 32) != epoch) {
-          unsigned long long old = atomicCAS(&t.dset[pos], e, mine);
-          if (old == e) {
-            winner = true;
-            break;
-          }
-          e = old;  // someone wrote this position in this call
-          if ((uint32_t)(e >> 32) != epoch) continue;
-        }
-        if ((uint64_t)keys[(uint32_t)e] == k) break;  // duplicate of the owner
-        pos = (pos + 1) & t.dset_mask;
-      }
-      if (!winner) rows_out[i] = -(int32_t)pos - 3;
-    }
+__global__ __launch_bounds__(256) void insert_kernel(TableView t, const int64_t* __restrict__ keys, uint32_t step,
+                                                     int32_t* rows_out) {
+  const uint32_t lane = lane_id();
+  // inclusive prefix of the sub-list fills, one list per lane
+  uint32_t inc = t.win_cnt[lane * kWinStride];
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t y = __shfl_up(inc, d);
+    if ((int)lane >= d) inc += y;
   }
-  // winners take rows from the free stack, one atomic per wave
-  const uint64_t wmask = __ballot(winner);
-  if (wmask == 0) return;
-  const int cnt = __popcll(wmask);
-  const int leader = __ffsll((unsigned long long)wmask) - 1;
-  int base = 0;
-  if ((int)lane_id() == leader) base = atomicSub(&t.ctl->free_n, cnt);
-  base = __shfl(base, leader);
-  uint32_t row = kNoRow;
-  if (winner) {
-    int idx = base - 1 - __popcll(wmask & lanes_below());
-    if (idx >= 0) row = t.free_rows[idx];
-  }
-  if ((int)lane_id() == leader) {
-    int got = base < 0 ? 0 : (base < cnt ? base : cnt);
-    if (got < cnt) {
-      atomicAdd(&t.ctl->free_n, cnt - got);
-      atomicAdd(&t.ctl->n_full, (unsigned long long)(cnt - got));
-    }
-    if (got) atomicAdd(&t.ctl->n_admitted, (unsigned long long)got);
-  }
-  if (winner) {
-    t.dset_row[pos] = row == kNoRow ? kRowAbsent : (int32_t)row;
-    rows_out[i] = row == kNoRow ? kRowAbsent : (int32_t)row;
-    if (row != kNoRow) cuckoo_insert(t, k, row, step);
-  }
-  // the wave initialises the new rows together: coalesced stores, one mixer call per lane
-  uint64_t imask = __ballot(winner && row != kNoRow);
+  const uint32_t total = __shfl(inc, 63);
+  const int32_t free0 = t.ctl->free_n;  // settled by the resolve kernel, constant here
   E* rows = reinterpret_cast<E*>(t.rows);
-  while (imask) {
-    int l = __ffsll((unsigned long long)imask) - 1;
-    imask &= imask - 1;
-    uint64_t kk = __shfl(k, l);
-    uint32_t rr = __shfl(row, l);
-    uint64_t base_h = mix64(kk ^ t.s_init);
-    for (uint32_t j = lane_id(); j < t.dim; j += 64) store_init<E>(rows, (uint64_t)rr * t.dim + j, init_value(base_h, j));
-    if (lane_id() == 0) t.acc[rr] = 0.0f;
+  const uint32_t stride = gridDim.x * blockDim.x;
+  for (uint32_t w0 = blockIdx.x * blockDim.x + (threadIdx.x & ~63u); w0 < total; w0 += stride) {
+    const uint32_t w = w0 + lane;
+    const bool valid = w < total;
+    // sub-list of w: the first list whose inclusive prefix exceeds w
+    uint32_t lo = 0, hi = 64;
+#pragma unroll
+    for (int it = 0; it < 7; ++it) {  // 65 possible answers: seven halvings
+      const uint32_t mid = (lo + hi) >> 1 < 63u ? (lo + hi) >> 1 : 63u;
+      const uint32_t v = __shfl(inc, (int)mid);
+      if (lo < hi) {
+        if (v <= w) lo = mid + 1; else hi = mid;
+      }
+    }
+    const uint32_t before = __shfl(inc, (int)(lo > 0 ? lo - 1 : 0));
+    uint64_t k = 0;
+    uint32_t row = kNoRow;
+    if (valid) {
+      const uint32_t p = w - (lo > 0 ? before : 0u);
+      const uint2 e = t.win_list[(uint64_t)lo * t.win_cap + p];
+      k = (uint64_t)keys[e.x];
+      if ((int64_t)w < (int64_t)free0) row = t.free_rows[free0 - 1 - (int32_t)w];
+      t.dset_row[e.y] = row == kNoRow ? kRowAbsent : (int32_t)row;
+      rows_out[e.x] = row == kNoRow ? kRowAbsent : (int32_t)row;
+      if (row != kNoRow) cuckoo_insert(t, k, make_meta(row, step));
+    }
+    // the wave initialises its new rows together: coalesced stores, one mixer call per lane
+    uint64_t imask = __ballot(valid && row != kNoRow);
+    while (imask) {
+      const int l = __ffsll((unsigned long long)imask) - 1;
+      imask &= imask - 1;
+      const uint64_t kk = __shfl(k, l);
+      const uint32_t rr = __shfl(row, l);
+      const uint64_t base_h = mix64(kk ^ t.s_init);
+      for (uint32_t j = lane; j < t.dim; j += 64) store_init<E>(rows, (uint64_t)rr * t.dim + j, init_value(base_h, j));
+      if (lane == 0) t.acc[rr] = 0.0f;
+    }
   }
 }
 
 __global__ __launch_bounds__(256) void resolve_kernel(TableView t, uint64_t n, int32_t* rows_out) {
-  uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n) return;
-  int32_t v = rows_out[i];
-  if (v <= -3) rows_out[i] = t.dset_row[(uint64_t)(-(v + 3))];
+  const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) {
+    const int32_t v = rows_out[i];
+    if (v <= -3) rows_out[i] = t.dset_row[(uint64_t)(-(v + 3))];
+  }
+  if (i == 0) {  // settle the counters of this call (the insert kernel has finished)
+    uint32_t total = 0;
+    for (int l = 0; l < kWinLists; ++l) {
+      total += t.win_cnt[l * kWinStride];
+      t.win_cnt[l * kWinStride] = 0;
+    }
+    const int32_t free0 = t.ctl->free_n;
+    const uint32_t got = total < (uint32_t)free0 ? total : (uint32_t)free0;
+    t.ctl->free_n = free0 - (int32_t)got;
+    t.ctl->n_admitted += got;
+    t.ctl->n_full += total - got;
+  }
 }
 
 hipError_t launch_lookup_or_insert(const TableView& t, const int64_t* d_keys, uint64_t n, uint32_t step, uint32_t epoch,
-                                   int32_t* d_rows_out, hipStream_t stream) {
+                                   int32_t* d_rows_out, hipStream_t stream, Profiler* prof) {
   if (n == 0) return hipSuccess;
-  dim3 block(256), grid((unsigned)((n + 255) / 256));
-  hipLaunchKernelGGL(probe_count_kernel, grid, block, 0, stream, t, d_keys, n, step, d_rows_out);
+  const dim3 block(256), grid((unsigned)((n + 255) / 256));
+  const dim3 igrid(grid.x < 2048u ? grid.x : 2048u);
+  MONO_LAUNCH(prof, K_PROBE_COUNT, stream, probe_count_kernel, grid, block, t, d_keys, n, step, d_rows_out);
+  MONO_LAUNCH(prof, K_ADMIT_ELECT, stream, admit_elect_kernel, grid, block, t, d_keys, n, epoch, d_rows_out);
   if (t.bf16)
-    hipLaunchKernelGGL(admit_insert_kernel<uint16_t>, grid, block, 0, stream, t, d_keys, n, step, epoch, d_rows_out);
+    MONO_LAUNCH(prof, K_INSERT, stream, insert_kernel<uint16_t>, igrid, block, t, d_keys, step, d_rows_out);
   else
-    hipLaunchKernelGGL(admit_insert_kernel<float>, grid, block, 0, stream, t, d_keys, n, step, epoch, d_rows_out);
-  hipLaunchKernelGGL(resolve_kernel, grid, block, 0, stream, t, n, d_rows_out);
+    MONO_LAUNCH(prof, K_INSERT, stream, insert_kernel<float>, igrid, block, t, d_keys, step, d_rows_out);
+  MONO_LAUNCH(prof, K_RESOLVE, stream, resolve_kernel, grid, block, t, n, d_rows_out);
   return hipGetLastError();
 }
 

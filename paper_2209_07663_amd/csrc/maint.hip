@@ -9,7 +9,12 @@ __device__ inline bool is_expired(const TableView& t, uint32_t now, uint32_t see
   return t.expire_steps > 0 && now >= seen && now - seen >= t.expire_steps;
 }
 
-// scratch[0] = keys removed by this call.  One thread also walks the (normally empty) stash.
+// Sweep in three kernels:
+//   sweep_begin  one thread: walks the (normally empty) stash; scratch[0] = keys removed so far
+//   sweep_find   one thread per slot, read-only: slots whose stamp is too old are appended to one of
+//                kWinLists lists (one atomic per block, spread over the lists)
+//   sweep_remove dense over the found slots: pushes the row on the free stack by rank, reports the
+//                key, clears the slot; one thread settles the counters
 __global__ void sweep_begin_kernel(TableView t, uint32_t now, int64_t* expired_keys, uint64_t max_expired) {
   if (blockIdx.x != 0 || threadIdx.x != 0) return;
   Control* c = t.ctl;
@@ -31,55 +36,95 @@ __global__ void sweep_begin_kernel(TableView t, uint32_t now, int64_t* expired_k
   c->scratch[0] = removed;
 }
 
-// One thread per slot.  Only the second half of each bucket line (row, seen) is read; the key is
-// read only for slots that expire.
-__global__ __launch_bounds__(256) void sweep_kernel(TableView t, uint32_t now, int64_t* expired_keys,
-                                                    uint64_t max_expired) {
+__global__ __launch_bounds__(256) void sweep_find_kernel(TableView t, uint32_t now) {
+  __shared__ uint32_t wave_cnt[4];
+  __shared__ uint32_t block_base;
   const uint64_t g = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
   bool expired = false;
-  uint32_t row = kNoRow;
-  Bucket* b = nullptr;
-  int l = 0;
   if (g < t.capacity) {
-    b = &t.buckets[g >> 3];
-    l = (int)(g & 7);
-    row = b->row[l];
-    expired = row != kNoRow && is_expired(t, now, b->seen[l]);
+    const unsigned long long m = t.buckets[g >> 3].meta[g & 7];
+    expired = meta_row(m) != kNoRow && is_expired(t, now, meta_seen(m));
   }
-  const uint64_t m = __ballot(expired);
-  if (m == 0) return;
-  const int cnt = __popcll(m), leader = __ffsll((unsigned long long)m) - 1;
-  int base = 0;
-  unsigned long long obase = 0;
-  if ((int)lane_id() == leader) {
-    base = atomicAdd(&t.ctl->free_n, cnt);
-    obase = atomicAdd(&t.ctl->scratch[0], (unsigned long long)cnt);
+  const uint32_t wave = threadIdx.x >> 6;
+  const uint64_t mask = __ballot(expired);
+  if (lane_id() == 0) wave_cnt[wave] = (uint32_t)__popcll(mask);
+  __syncthreads();
+  const uint32_t list = blockIdx.x & (kWinLists - 1);
+  if (threadIdx.x == 0) {
+    const uint32_t total = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+    block_base = total ? atomicAdd(&t.sweep_cnt[list * kWinStride], total) : 0u;
   }
-  base = __shfl(base, leader);
-  obase = __shfl(obase, leader);
+  __syncthreads();
   if (expired) {
-    const int rank = __popcll(m & lanes_below());
-    t.free_rows[base + rank] = row;
-    if (expired_keys && obase + rank < max_expired) expired_keys[obase + rank] = (int64_t)b->key[l];
-    b->row[l] = kNoRow;
-    b->key[l] = kEmptyKey;
+    uint32_t p = block_base + (uint32_t)__popcll(mask & lanes_below());
+    for (uint32_t w = 0; w < wave; ++w) p += wave_cnt[w];
+    t.sweep_list[(uint64_t)list * t.sweep_cap + p] = (uint32_t)g;
   }
+}
+
+__global__ __launch_bounds__(256) void sweep_remove_kernel(TableView t, int64_t* expired_keys, uint64_t max_expired,
+                                                           uint64_t* n_expired) {
+  const uint32_t lane = lane_id();
+  uint32_t inc = t.sweep_cnt[lane * kWinStride];
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t y = __shfl_up(inc, d);
+    if ((int)lane >= d) inc += y;
+  }
+  const uint32_t total = __shfl(inc, 63);
+  const int32_t free0 = t.ctl->free_n;                     // constant during this kernel
+  const unsigned long long out0 = t.ctl->scratch[0];       // keys already reported from the stash
+  const uint32_t stride = gridDim.x * blockDim.x;
+  for (uint32_t w0 = blockIdx.x * blockDim.x + (threadIdx.x & ~63u); w0 < total; w0 += stride) {
+    const uint32_t w = w0 + lane;
+    uint32_t lo = 0, hi = 64;
+#pragma unroll
+    for (int it = 0; it < 7; ++it) {  // 65 possible answers: seven halvings
+      const uint32_t mid = (lo + hi) >> 1 < 63u ? (lo + hi) >> 1 : 63u;
+      const uint32_t v = __shfl(inc, (int)mid);
+      if (lo < hi) {
+        if (v <= w) lo = mid + 1; else hi = mid;
+      }
+    }
+    const uint32_t before = __shfl(inc, (int)(lo > 0 ? lo - 1 : 0));
+    if (w < total) {
+      const uint32_t p = w - (lo > 0 ? before : 0u);
+      const uint32_t g = t.sweep_list[(uint64_t)lo * t.sweep_cap + p];
+      Bucket* b = &t.buckets[g >> 3];
+      const int l = (int)(g & 7);
+      t.free_rows[free0 + (int32_t)w] = meta_row(b->meta[l]);
+      if (expired_keys && out0 + w < max_expired) expired_keys[out0 + w] = (int64_t)b->key[l];
+      b->meta[l] = kNoMeta;
+      b->key[l] = kEmptyKey;
+    }
+  }
+  // the last block to get here cannot be known cheaply; the counters are settled by sweep_end
+  (void)n_expired;
 }
 
 __global__ void sweep_end_kernel(TableView t, uint64_t* n_expired) {
   if (blockIdx.x != 0 || threadIdx.x != 0) return;
-  t.ctl->n_expired += t.ctl->scratch[0];
-  if (n_expired) *n_expired = t.ctl->scratch[0];
+  uint32_t total = 0;
+  for (int l = 0; l < kWinLists; ++l) {
+    total += t.sweep_cnt[l * kWinStride];
+    t.sweep_cnt[l * kWinStride] = 0;
+  }
+  t.ctl->free_n += (int32_t)total;
+  const unsigned long long removed = t.ctl->scratch[0] + total;
+  t.ctl->n_expired += removed;
+  if (n_expired) *n_expired = removed;
 }
 
 hipError_t launch_expire_sweep(const TableView& t, uint32_t now, uint64_t* d_n_expired, int64_t* d_expired_keys,
-                               uint64_t max_expired, hipStream_t stream) {
-  hipLaunchKernelGGL(sweep_begin_kernel, dim3(1), dim3(64), 0, stream, t, now, d_expired_keys, max_expired);
+                               uint64_t max_expired, hipStream_t stream, Profiler* prof) {
+  MONO_LAUNCH(prof, K_SWEEP_BEGIN, stream, sweep_begin_kernel, dim3(1), dim3(64), t, now, d_expired_keys, max_expired);
   if (t.expire_steps > 0) {
-    dim3 block(256), grid((unsigned)((t.capacity + 255) / 256));
-    hipLaunchKernelGGL(sweep_kernel, grid, block, 0, stream, t, now, d_expired_keys, max_expired);
+    const dim3 block(256), grid((unsigned)((t.capacity + 255) / 256));
+    MONO_LAUNCH(prof, K_SWEEP, stream, sweep_find_kernel, grid, block, t, now);
+    MONO_LAUNCH(prof, K_SWEEP_REMOVE, stream, sweep_remove_kernel, dim3(grid.x < 2048u ? grid.x : 2048u), block, t,
+                d_expired_keys, max_expired, d_n_expired);
   }
-  hipLaunchKernelGGL(sweep_end_kernel, dim3(1), dim3(64), 0, stream, t, d_n_expired);
+  MONO_LAUNCH(prof, K_SWEEP_END, stream, sweep_end_kernel, dim3(1), dim3(64), t, d_n_expired);
   return hipGetLastError();
 }
 
@@ -100,10 +145,11 @@ __global__ __launch_bounds__(256) void export_kernel(TableView t, int64_t* keys,
   if (g < t.capacity) {
     const Bucket* b = &t.buckets[g >> 3];
     const int l = (int)(g & 7);
-    row = b->row[l];
+    const unsigned long long m = b->meta[l];
+    row = meta_row(m);
     live = row != kNoRow;
     key = b->key[l];
-    seen = b->seen[l];
+    seen = meta_seen(m);
     where = (int64_t)g;
   } else if (g < total) {
     const uint32_t s = (uint32_t)(g - t.capacity);
@@ -203,6 +249,8 @@ hipError_t launch_table_init(const TableView& t, uint64_t dset_size, hipStream_t
   if ((e = hipMemsetAsync(t.buckets, 0xFF, 2 * t.n_buckets * sizeof(Bucket), stream)) != hipSuccess) return e;
   if ((e = hipMemsetAsync(t.filter, 0, t.n_filter * sizeof(unsigned long long), stream)) != hipSuccess) return e;
   if ((e = hipMemsetAsync(t.ctl, 0, sizeof(Control), stream)) != hipSuccess) return e;
+  if ((e = hipMemsetAsync(t.win_cnt, 0, kWinLists * kWinStride * sizeof(uint32_t), stream)) != hipSuccess) return e;
+  if ((e = hipMemsetAsync(t.sweep_cnt, 0, kWinLists * kWinStride * sizeof(uint32_t), stream)) != hipSuccess) return e;
   if ((e = hipMemsetAsync(t.dset, 0, dset_size * sizeof(unsigned long long), stream)) != hipSuccess) return e;
   hipLaunchKernelGGL(init_free_rows_kernel, dim3((unsigned)((t.capacity + 255) / 256)), dim3(256), 0, stream, t);
   return hipGetLastError();

@@ -143,7 +143,7 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(
 }
 
 hipError_t launch_sort_pairs(const UpdateWorkspace& ws, const uint32_t* keys_in, uint32_t clamp, uint64_t n,
-                             uint32_t bits, int* result_in_b, hipStream_t stream) {
+                             uint32_t bits, int* result_in_b, hipStream_t stream, Profiler* prof) {
   *result_in_b = 0;
   if (n == 0 || bits == 0) return hipSuccess;
   const uint64_t units = sort_units(n);
@@ -159,9 +159,9 @@ hipError_t launch_sort_pairs(const UpdateWorkspace& ws, const uint32_t* keys_in,
   for (uint32_t p = 0; p < passes; ++p) {
     const uint32_t b = bits - shift < per ? bits - shift : per;
     const uint32_t cl = p == 0 ? clamp : 0xFFFFFFFFu;
-    hipLaunchKernelGGL(sort_hist_kernel, grid, block, 0, stream, src_k, cl, n, units, shift, b, ws.hist);
-    hipLaunchKernelGGL(sort_scan_kernel, dim3(1u << b), dim3(256), 0, stream, ws.hist, units, totals);
-    hipLaunchKernelGGL(sort_scatter_kernel, grid, block, 0, stream, src_k, src_v, cl, n, units, shift, b, ws.hist,
+    MONO_LAUNCH(prof, K_SORT_HIST, stream, sort_hist_kernel, grid, block, src_k, cl, n, units, shift, b, ws.hist);
+    MONO_LAUNCH(prof, K_SORT_SCAN, stream, sort_scan_kernel, dim3(1u << b), dim3(256), ws.hist, units, totals);
+    MONO_LAUNCH(prof, K_SORT_SCATTER, stream, sort_scatter_kernel, grid, block, src_k, src_v, cl, n, units, shift, b, ws.hist,
                        totals, dst_k, dst_v);
     shift += b;
     // ping-pong; after the first pass the source is always one of the workspace pairs

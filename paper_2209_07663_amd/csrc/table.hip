@@ -15,6 +15,7 @@ struct mono_table {
   uint32_t epoch = 0;       // per-call tag of the dedup set
   uint32_t last_step = 0;
   int device = 0;
+  Profiler prof;
 };
 
 namespace {
@@ -58,6 +59,12 @@ size_t layout(mono_table* t, char* base, uint64_t capacity, uint32_t dim, uint32
   char* stash = take(kStashCap * sizeof(StashEntry));
   char* dset_p = take(dset * sizeof(unsigned long long));
   char* dset_row = take(dset * sizeof(int32_t));
+  const uint64_t win_cap = ((max_ids + 255) / 256 + kWinLists - 1) / kWinLists * 256;
+  const uint64_t sweep_cap = ((capacity + 255) / 256 + kWinLists - 1) / kWinLists * 256;
+  char* win_list = take(kWinLists * win_cap * sizeof(uint2));
+  char* win_cnt = take(kWinLists * kWinStride * sizeof(uint32_t));
+  char* sweep_list = take(kWinLists * sweep_cap * sizeof(uint32_t));
+  char* sweep_cnt = take(kWinLists * kWinStride * sizeof(uint32_t));
   char* key_a = take(max_ids * 4);
   char* key_b = take(max_ids * 4);
   char* val_a = take(max_ids * 4);
@@ -77,6 +84,12 @@ size_t layout(mono_table* t, char* base, uint64_t capacity, uint32_t dim, uint32
     v.stash = (StashEntry*)stash;
     v.dset = (unsigned long long*)dset_p;
     v.dset_row = (int32_t*)dset_row;
+    v.win_list = (uint2*)win_list;
+    v.win_cnt = (uint32_t*)win_cnt;
+    v.win_cap = win_cap;
+    v.sweep_list = (uint32_t*)sweep_list;
+    v.sweep_cnt = (uint32_t*)sweep_cnt;
+    v.sweep_cap = sweep_cap;
     t->ws.key_a = (uint32_t*)key_a;
     t->ws.key_b = (uint32_t*)key_b;
     t->ws.val_a = (uint32_t*)val_a;
@@ -182,7 +195,7 @@ int mono_lookup_or_insert(mono_table* t, const int64_t* d_keys, uint64_t n, uint
       return MONO_EHIP;
     t->epoch = 1;
   }
-  return launch_lookup_or_insert(t->view, d_keys, n, step, t->epoch, d_rows_out, (hipStream_t)stream) == hipSuccess
+  return launch_lookup_or_insert(t->view, d_keys, n, step, t->epoch, d_rows_out, (hipStream_t)stream, &t->prof) == hipSuccess
              ? MONO_OK
              : MONO_EHIP;
 }
@@ -192,7 +205,7 @@ int mono_gather_pool(mono_table* t, const int32_t* d_rows, uint64_t n, const int
   if (!t || n > t->max_ids || n_bags > t->max_bags) return MONO_EINVAL;
   if (n_bags == 0) return MONO_OK;
   if (!d_offsets || !d_out || (n && !d_rows)) return MONO_EINVAL;
-  return launch_gather_pool(t->view, d_rows, d_offsets, n_bags, d_out, (hipStream_t)stream) == hipSuccess ? MONO_OK
+  return launch_gather_pool(t->view, d_rows, d_offsets, n_bags, d_out, (hipStream_t)stream, &t->prof) == hipSuccess ? MONO_OK
                                                                                                            : MONO_EHIP;
 }
 
@@ -202,7 +215,7 @@ int mono_apply_grad_adagrad(mono_table* t, const int32_t* d_rows, uint64_t n, co
   if (n == 0 || n_bags == 0) return MONO_OK;
   if (!d_rows || !d_offsets || !d_grad) return MONO_EINVAL;
   return launch_apply_grad_adagrad(t->view, t->ws, d_rows, n, d_offsets, n_bags, d_grad, lr, eps,
-                                   (hipStream_t)stream) == hipSuccess
+                                   (hipStream_t)stream, &t->prof) == hipSuccess
              ? MONO_OK
              : MONO_EHIP;
 }
@@ -211,7 +224,7 @@ int mono_expire_sweep(mono_table* t, uint32_t now, uint64_t* d_n_expired, int64_
                       uint64_t max_expired, void* stream) {
   if (!t || now >= (1u << 24)) return MONO_EINVAL;
   return launch_expire_sweep(t->view, now, d_n_expired, d_expired_keys, d_expired_keys ? max_expired : 0,
-                             (hipStream_t)stream) == hipSuccess
+                             (hipStream_t)stream, &t->prof) == hipSuccess
              ? MONO_OK
              : MONO_EHIP;
 }
@@ -257,6 +270,40 @@ int mono_filter_export(mono_table* t, uint32_t* d_words, uint64_t first, uint64_
   if (!t || first + count > t->view.n_filter || (count && !d_words)) return MONO_EINVAL;
   if (launch_filter_export(t->view, d_words, first, count, (hipStream_t)stream) != hipSuccess) return MONO_EHIP;
   return hipStreamSynchronize((hipStream_t)stream) == hipSuccess ? MONO_OK : MONO_EHIP;
+}
+
+int mono_profile_enable(mono_table* t, int on) {
+  if (!t) return MONO_EINVAL;
+  t->prof.on = on != 0;
+  return MONO_OK;
+}
+
+int mono_profile_read(mono_table* t, const char** h_names, double* h_ms, uint64_t* h_launches, uint32_t max_kernels,
+                      uint32_t* h_n) {
+  if (!t || !h_n) return MONO_EINVAL;
+  if (hipDeviceSynchronize() != hipSuccess) return MONO_EHIP;
+  double ms[K_COUNT] = {0};
+  uint64_t cnt[K_COUNT] = {0};
+  for (auto& r : t->prof.recs) {
+    float e = 0.f;
+    if (hipEventElapsedTime(&e, r.start, r.stop) == hipSuccess) {
+      ms[r.id] += e;
+      cnt[r.id] += 1;
+    }
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
+  }
+  t->prof.recs.clear();
+  uint32_t k = 0;
+  for (int id = 0; id < K_COUNT && k < max_kernels; ++id) {
+    if (!cnt[id]) continue;
+    if (h_names) h_names[k] = kernel_name(id);
+    if (h_ms) h_ms[k] = ms[id];
+    if (h_launches) h_launches[k] = cnt[id];
+    ++k;
+  }
+  *h_n = k;
+  return MONO_OK;
 }
 
 }  // extern "C"

@@ -194,15 +194,15 @@ __global__ __launch_bounds__(256) void combine_kernel(TableView t, uint64_t n_ch
 
 hipError_t launch_apply_grad_adagrad(const TableView& t, const UpdateWorkspace& ws, const int32_t* d_rows, uint64_t n,
                                      const int64_t* d_offsets, uint64_t n_bags, const float* d_grad, float lr, float eps,
-                                     hipStream_t stream) {
+                                     hipStream_t stream, Profiler* prof) {
   if (n == 0 || n_bags == 0) return hipSuccess;
-  hipLaunchKernelGGL(expand_bags_kernel, dim3((unsigned)((n_bags + 255) / 256)), dim3(256), 0, stream, d_offsets, n_bags,
+  MONO_LAUNCH(prof, K_EXPAND_BAGS, stream, expand_bags_kernel, dim3((unsigned)((n_bags + 255) / 256)), dim3(256), d_offsets, n_bags,
                      ws.val_a);
   uint32_t bits = 1;  // keys are rows in [0, capacity) plus `capacity` itself for dropped occurrences
   while ((1ull << bits) <= t.capacity) ++bits;
   int in_b = 0;
   hipError_t e = launch_sort_pairs(ws, reinterpret_cast<const uint32_t*>(d_rows), (uint32_t)t.capacity, n, bits, &in_b,
-                                   stream);
+                                   stream, prof);
   if (e != hipSuccess) return e;
   const uint32_t* sk = in_b ? ws.key_b : ws.key_a;
   const uint32_t* sv = in_b ? ws.val_b : ws.val_a;
@@ -212,14 +212,14 @@ hipError_t launch_apply_grad_adagrad(const TableView& t, const UpdateWorkspace& 
   const uint64_t threads = n_chunks << group_log2;
   const dim3 block(256), grid((unsigned)((threads + 255) / 256)), cgrid((unsigned)((n_chunks + 3) / 4));
   if (t.bf16) {
-    hipLaunchKernelGGL(seg_reduce_kernel<uint16_t>, grid, block, 0, stream, t, sk, sv, n, d_grad, lr, eps, ws.part,
+    MONO_LAUNCH(prof, K_SEG_REDUCE, stream, seg_reduce_kernel<uint16_t>, grid, block, t, sk, sv, n, d_grad, lr, eps, ws.part,
                        ws.part_row, group_log2);
-    hipLaunchKernelGGL(combine_kernel<uint16_t>, cgrid, block, 0, stream, t, n_chunks, ws.part, ws.part_row, lr, eps,
+    MONO_LAUNCH(prof, K_COMBINE, stream, combine_kernel<uint16_t>, cgrid, block, t, n_chunks, ws.part, ws.part_row, lr, eps,
                        group_log2);
   } else {
-    hipLaunchKernelGGL(seg_reduce_kernel<float>, grid, block, 0, stream, t, sk, sv, n, d_grad, lr, eps, ws.part,
+    MONO_LAUNCH(prof, K_SEG_REDUCE, stream, seg_reduce_kernel<float>, grid, block, t, sk, sv, n, d_grad, lr, eps, ws.part,
                        ws.part_row, group_log2);
-    hipLaunchKernelGGL(combine_kernel<float>, cgrid, block, 0, stream, t, n_chunks, ws.part, ws.part_row, lr, eps,
+    MONO_LAUNCH(prof, K_COMBINE, stream, combine_kernel<float>, cgrid, block, t, n_chunks, ws.part, ws.part_row, lr, eps,
                        group_log2);
   }
   return hipGetLastError();
