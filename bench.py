@@ -37,6 +37,8 @@ def generate_batches(wl_name, seed, steps, workers):
     if wl.drift_frac > 0:  # the rotating rank->ID map is sequential state
         drift = synth.DriftMap(wl, seed)
         return [synth.make_batch(wl, seed, s, with_grad=True, drift=drift) for s in steps]
+    if workers <= 0:  # in-process (used under profilers, which have initialised the GPU already)
+        return [_gen((wl_name, seed, s)) for s in steps]
     with mp.get_context("fork").Pool(workers) as pool:
         return pool.map(_gen, [(wl_name, seed, s) for s in steps], chunksize=1)
 

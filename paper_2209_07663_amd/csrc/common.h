@@ -43,6 +43,8 @@ struct StashEntry {
 struct Control {
   int32_t free_n;            // rows on the free stack
   uint32_t stash_n;          // elements pushed to the stash (may exceed kStashCap: then some were lost)
+  uint32_t hwm;              // every row index ever handed out is below this high-water mark
+  uint32_t pad_;
   unsigned long long n_admitted, n_expired, n_insert_failed, n_lost, n_full, max_chain;
   unsigned long long scratch[8];  // per-call scalars (export count, sweep count)
 };

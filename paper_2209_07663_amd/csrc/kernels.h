@@ -8,22 +8,37 @@ namespace mono {
 
 // Per-call scratch for the update path, carved out of the table's arena.
 struct UpdateWorkspace {
-  uint32_t* key_a;      // [max_ids] sort keys (row index, or `capacity` for dropped occurrences)
-  uint32_t* key_b;      // [max_ids]
-  uint32_t* val_a;      // [max_ids] bag of each occurrence
-  uint32_t* val_b;      // [max_ids]
-  uint32_t* hist;       // [kSortMaxBins * sort_units(max_ids)]
-  float* part;          // [2 * n_chunks(max_ids) * dim] partial gradient sums of runs that cross chunks
-  uint32_t* part_row;   // [2 * n_chunks(max_ids)] row of each partial, kNoRow if unused
+  uint32_t* bag_of;     // [max_ids] bag of each occurrence
+  uint2* pair_a;        // [max_ids] (row, bag) pairs, ping
+  uint2* pair_b;        // [max_ids] pong
+  uint32_t* hist;       // [kSortMaxBins * sort_units(max_ids) + kSortMaxBins]
+  float* part;          // [2 * tiles * dim] partial gradient sums of runs that cross tile borders
+  uint32_t* part_row;   // [2 * tiles] row (+ head flag) of each partial, kNoRow if unused
 };
 
-constexpr uint32_t kSortMaxBits = 10;              // widest radix digit
+constexpr uint32_t kSortMaxBits = 11;              // widest radix digit
 constexpr uint32_t kSortMaxBins = 1u << kSortMaxBits;
-constexpr uint32_t kSortItemsPerWave = 2048;       // consecutive elements ranked by one wave
+constexpr uint32_t kSortItemsPerBlock = 8192;      // consecutive elements owned by one block of the sort
 constexpr uint32_t kChunk = 128;                   // sorted occurrences reduced by one lane group
 
-inline uint64_t sort_units(uint64_t n) { return (n + kSortItemsPerWave - 1) / kSortItemsPerWave; }
+inline uint64_t sort_units(uint64_t n) { return (n + kSortItemsPerBlock - 1) / kSortItemsPerBlock; }
 inline uint64_t reduce_chunks(uint64_t n) { return (n + kChunk - 1) / kChunk; }
+
+// How many bits of the row index are sorted, in how many passes (computed alike on host and device).
+struct SortPlan {
+  uint32_t hwm, bits, passes, per;
+  __host__ __device__ uint32_t shift(uint32_t p) const { return p * per; }
+  __host__ __device__ uint32_t width(uint32_t p) const { return bits - p * per < per ? bits - p * per : per; }
+};
+__host__ __device__ inline SortPlan make_sort_plan(uint32_t hwm) {
+  SortPlan s;
+  s.hwm = hwm;
+  s.bits = 1;
+  while (s.bits < 32 && (hwm >> s.bits) != 0) ++s.bits;  // keys lie in [0, hwm]
+  s.passes = (s.bits + kSortMaxBits - 1) / kSortMaxBits;
+  s.per = (s.bits + s.passes - 1) / s.passes;
+  return s;
+}
 
 hipError_t launch_lookup_or_insert(const TableView& t, const int64_t* d_keys, uint64_t n, uint32_t step, uint32_t epoch,
                                    int32_t* d_rows_out, hipStream_t stream, Profiler* prof);
@@ -35,11 +50,10 @@ hipError_t launch_apply_grad_adagrad(const TableView& t, const UpdateWorkspace& 
                                      const int64_t* d_offsets, uint64_t n_bags, const float* d_grad, float lr, float eps,
                                      hipStream_t stream, Profiler* prof);
 
-// Stable LSD radix sort of (key, value) pairs on the low `bits` bits of the key.  Input in
-// (key_a, val_a) unless `keys_in` is given (first pass then reads keys from there, transformed by
-// min(key, clamp) on unsigned values); returns which buffer pair holds the result (0 = a, 1 = b).
-hipError_t launch_sort_pairs(const UpdateWorkspace& ws, const uint32_t* keys_in, uint32_t clamp, uint64_t n,
-                             uint32_t bits, int* result_in_b, hipStream_t stream, Profiler* prof);
+// Stable LSD radix sort of the (row, bag) pairs of a batch; the result is in pair_b if the plan for
+// the device's high-water mark has an odd number of passes, else in pair_a.
+hipError_t launch_sort_pairs(const TableView& t, const UpdateWorkspace& ws, const int32_t* d_rows, uint64_t n,
+                             hipStream_t stream, Profiler* prof);
 
 hipError_t launch_expire_sweep(const TableView& t, uint32_t now, uint64_t* d_n_expired, int64_t* d_expired_keys,
                                uint64_t max_expired, hipStream_t stream, Profiler* prof);

@@ -296,6 +296,8 @@ __global__ __launch_bounds__(256) void resolve_kernel(TableView t, uint64_t n, i
     const int32_t free0 = t.ctl->free_n;
     const uint32_t got = total < (uint32_t)free0 ? total : (uint32_t)free0;
     t.ctl->free_n = free0 - (int32_t)got;
+    const uint32_t in_use = (uint32_t)t.capacity - (uint32_t)(free0 - (int32_t)got);
+    if (in_use > t.ctl->hwm) t.ctl->hwm = in_use;  // rows are handed out in ascending order
     t.ctl->n_admitted += got;
     t.ctl->n_full += total - got;
   }

@@ -68,6 +68,12 @@ class ProfScope {
 
 }  // namespace mono
 
+#define MONO_LAUNCH_SMEM(prof, id, stream, kernel, grid, block, smem, ...)      \
+  do {                                                                       \
+    ::mono::ProfScope mono_ps_((prof), (id), (stream));                      \
+    hipLaunchKernelGGL(kernel, (grid), (block), (smem), (stream), __VA_ARGS__); \
+  } while (0)
+
 #define MONO_LAUNCH(prof, id, stream, kernel, grid, block, ...)              \
   do {                                                                       \
     ::mono::ProfScope mono_ps_((prof), (id), (stream));                      \

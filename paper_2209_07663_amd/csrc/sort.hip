@@ -1,52 +1,68 @@
 // Stable LSD radix sort of (row index, bag) pairs, used to bring the occurrences of one embedding
 // row together before the gradient reduction.
 //
-// Unit of work: one wave owns kSortItemsPerWave consecutive elements.  Per pass:
+// The key width is decided ON THE DEVICE: row indices are handed out in ascending order, so every
+// row in use is below the high-water mark `hwm` kept in the control block, and dropped occurrences
+// (row -1) get the key `hwm` itself.  bit_length(hwm) bits are sorted in the fewest passes of at
+// most kSortMaxBits bits; the host launches the worst-case number of passes and the superfluous
+// ones return at once.  Pass p reads buffer (p even ? a : b) and writes the other one.
+//
+// Unit of work: one block of four waves owns kSortItemsPerBlock consecutive elements, a quarter
+// per wave.  Per pass:
 //   hist     per-unit digit histogram (LDS atomics), written bin-major: hist[bin * units + unit]
 //   scan     one block per bin: exclusive scan along the units; bin totals to `totals`
-//   scatter  each wave turns totals into bin bases (wave scan), adds its own row of the scanned
-//            histogram, then ranks its elements 64 at a time by digit matching with ballots
-//            (stable: rank = number of lower lanes with the same digit) and scatters them.
-// Waves never wait for each other; no kernel spins.
+//   scatter  the block loads its elements into registers (all loads independent), counts the digits
+//            per wave in LDS, turns the counts into per-wave start offsets (bin base + the unit's
+//            scanned histogram + the waves before), then every wave ranks its elements 64 at a time
+//            by digit matching with ballots (stable: rank = number of lower lanes with the same
+//            digit) and scatters the pairs.
+// No kernel spins or waits for another block.
 #include "common.h"
 #include "kernels.h"
 
 namespace mono {
 
-constexpr int kSortBlock = 256;                      // 4 independent waves
+constexpr int kSortBlock = 256;
 constexpr int kSortWaves = kSortBlock / 64;
-constexpr uint32_t kSortRounds = kSortItemsPerWave / 64;
+constexpr uint32_t kSortPerWave = kSortItemsPerBlock / kSortWaves;
+constexpr uint32_t kSortRounds = kSortPerWave / 64;
 
-__device__ inline uint32_t load_key(const uint32_t* keys, uint64_t i, uint32_t clamp) {
-  uint32_t k = keys[i];
-  return k < clamp ? k : clamp;
+// key of occurrence i in pass 0: its row, or hwm if the occurrence was dropped
+__device__ inline uint32_t first_key(const int32_t* rows, uint64_t i, uint32_t hwm) {
+  const uint32_t r = (uint32_t)rows[i];
+  return r < hwm ? r : hwm;
 }
 
-__global__ __launch_bounds__(kSortBlock) void sort_hist_kernel(const uint32_t* __restrict__ keys, uint32_t clamp,
-                                                               uint64_t n, uint64_t units, uint32_t shift,
-                                                               uint32_t bits, uint32_t* __restrict__ hist) {
-  __shared__ uint32_t lds[kSortWaves][kSortMaxBins];
-  const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const uint64_t unit = (uint64_t)blockIdx.x * kSortWaves + wave;
-  const uint32_t nbins = 1u << bits, mask = nbins - 1;
-  uint32_t* cnt = lds[wave];
-  for (uint32_t b = lane; b < nbins; b += 64) cnt[b] = 0;
-  __builtin_amdgcn_wave_barrier();
-  if (unit < units) {
-    const uint64_t base = unit * kSortItemsPerWave;
-#pragma unroll 4
-    for (uint32_t r = 0; r < kSortRounds; ++r) {
-      const uint64_t i = base + (uint64_t)r * 64 + lane;
-      if (i < n) atomicAdd(&cnt[(load_key(keys, i, clamp) >> shift) & mask], 1u);
+__global__ __launch_bounds__(kSortBlock) void sort_hist_kernel(const Control* __restrict__ ctl, uint32_t pass,
+                                                               const int32_t* __restrict__ rows,
+                                                               const uint2* __restrict__ src, uint64_t n,
+                                                               uint64_t units, uint32_t* __restrict__ hist) {
+  const SortPlan plan = make_sort_plan(ctl->hwm);
+  if (pass >= plan.passes) return;
+  __shared__ uint32_t cnt[kSortMaxBins];
+  const uint64_t unit = blockIdx.x;
+  const uint32_t shift = plan.shift(pass), nbins = 1u << plan.width(pass), mask = nbins - 1;
+  for (uint32_t b = threadIdx.x; b < nbins; b += kSortBlock) cnt[b] = 0;
+  __syncthreads();
+  const uint64_t base = unit * kSortItemsPerBlock;
+#pragma unroll 8
+  for (uint32_t r = 0; r < kSortItemsPerBlock / kSortBlock; ++r) {
+    const uint64_t i = base + (uint64_t)r * kSortBlock + threadIdx.x;
+    if (i < n) {
+      const uint32_t k = pass == 0 ? first_key(rows, i, plan.hwm) : src[i].x;
+      atomicAdd(&cnt[(k >> shift) & mask], 1u);
     }
-    __builtin_amdgcn_wave_barrier();
-    for (uint32_t b = lane; b < nbins; b += 64) hist[(uint64_t)b * units + unit] = cnt[b];
   }
+  __syncthreads();
+  for (uint32_t b = threadIdx.x; b < nbins; b += kSortBlock) hist[(uint64_t)b * units + unit] = cnt[b];
 }
 
 // exclusive scan of hist[bin * units + 0 .. units) in place; total of the bin to totals[bin]
-__global__ __launch_bounds__(256) void sort_scan_kernel(uint32_t* __restrict__ hist, uint64_t units,
+__global__ __launch_bounds__(256) void sort_scan_kernel(const Control* __restrict__ ctl, uint32_t pass,
+                                                        uint32_t* __restrict__ hist, uint64_t units,
                                                         uint32_t* __restrict__ totals) {
+  const SortPlan plan = make_sort_plan(ctl->hwm);
+  if (pass >= plan.passes || blockIdx.x >= (1u << plan.width(pass))) return;
   __shared__ uint32_t wave_sum[4];
   __shared__ uint32_t carry_s;
   uint32_t* row = hist + (uint64_t)blockIdx.x * units;
@@ -59,7 +75,7 @@ __global__ __launch_bounds__(256) void sort_scan_kernel(uint32_t* __restrict__ h
     uint32_t x = v;  // inclusive wave scan
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
-      uint32_t y = __shfl_up(x, d);
+      const uint32_t y = __shfl_up(x, d);
       if ((int)lane >= d) x += y;
     }
     if (lane == 63) wave_sum[wave] = x;
@@ -74,18 +90,36 @@ __global__ __launch_bounds__(256) void sort_scan_kernel(uint32_t* __restrict__ h
   if (threadIdx.x == 0) totals[blockIdx.x] = carry_s;
 }
 
-__global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(
-    const uint32_t* __restrict__ keys, const uint32_t* __restrict__ vals, uint32_t clamp, uint64_t n, uint64_t units,
-    uint32_t shift, uint32_t bits, const uint32_t* __restrict__ hist, const uint32_t* __restrict__ totals,
-    uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out) {
-  __shared__ uint32_t lds[kSortWaves][kSortMaxBins];
+__global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(const Control* __restrict__ ctl, uint32_t pass,
+                                                                  const int32_t* __restrict__ rows,
+                                                                  const uint32_t* __restrict__ bag_of,
+                                                                  const uint2* __restrict__ src, uint64_t n,
+                                                                  uint64_t units, const uint32_t* __restrict__ hist,
+                                                                  const uint32_t* __restrict__ totals,
+                                                                  uint2* __restrict__ dst) {
+  const SortPlan plan = make_sort_plan(ctl->hwm);
+  if (pass >= plan.passes) return;
+  __shared__ uint32_t lds[kSortWaves][kSortMaxBins];  // per-wave digit counts, then start offsets
+  __shared__ uint32_t bin_base[kSortMaxBins];
   const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const uint64_t unit = (uint64_t)blockIdx.x * kSortWaves + wave;
-  if (unit >= units) return;
-  const uint32_t nbins = 1u << bits, mask = nbins - 1;
-  volatile uint32_t* off = lds[wave];
-  // bin bases: exclusive scan of the totals over the bins, `per` consecutive bins per lane
-  {
+  const uint64_t unit = blockIdx.x;
+  const uint32_t shift = plan.shift(pass), bits = plan.width(pass), nbins = 1u << bits, mask = nbins - 1;
+
+  // 1. this wave's elements -> registers (independent, coalesced loads)
+  const uint64_t base = unit * kSortItemsPerBlock + (uint64_t)wave * kSortPerWave;
+  uint2 kv[kSortRounds];
+#pragma unroll
+  for (uint32_t r = 0; r < kSortRounds; ++r) {
+    const uint64_t i = base + (uint64_t)r * 64 + lane;
+    kv[r] = make_uint2(0xFFFFFFFFu, 0u);
+    if (i < n) kv[r] = pass == 0 ? make_uint2(first_key(rows, i, plan.hwm), bag_of[i]) : src[i];
+  }
+  for (uint32_t b = threadIdx.x; b < nbins; b += kSortBlock) {
+#pragma unroll
+    for (int w = 0; w < kSortWaves; ++w) lds[w][b] = 0;
+  }
+  // bin bases: exclusive scan of the totals over the bins by wave 0, `per` consecutive bins per lane
+  if (wave == 0) {
     const uint32_t per = (nbins + 63) / 64;
     uint32_t local[kSortMaxBins / 64];
     uint32_t sum = 0;
@@ -98,7 +132,7 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(
     uint32_t x = sum;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
-      uint32_t y = __shfl_up(x, d);
+      const uint32_t y = __shfl_up(x, d);
       if ((int)lane >= d) x += y;
     }
     uint32_t run = x - sum;
@@ -106,71 +140,65 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(
     for (uint32_t q = 0; q < kSortMaxBins / 64; ++q) {
       const uint32_t b = lane * per + q;
       if (q < per && b < nbins) {
-        off[b] = run + hist[(uint64_t)b * units + unit];
+        bin_base[b] = run;
         run += local[q];
       }
     }
   }
-  __builtin_amdgcn_wave_barrier();
-  const uint64_t base = unit * kSortItemsPerWave;
-#pragma unroll 2
+  __syncthreads();
+  // 2. per-wave digit counts
+#pragma unroll
+  for (uint32_t r = 0; r < kSortRounds; ++r) {
+    const uint64_t i = base + (uint64_t)r * 64 + lane;
+    if (i < n) atomicAdd(&lds[wave][(kv[r].x >> shift) & mask], 1u);
+  }
+  __syncthreads();
+  // 3. counts -> start offset of every (wave, bin)
+  for (uint32_t b = threadIdx.x; b < nbins; b += kSortBlock) {
+    uint32_t run = bin_base[b] + hist[(uint64_t)b * units + unit];
+#pragma unroll
+    for (int w = 0; w < kSortWaves; ++w) {
+      const uint32_t c = lds[w][b];
+      lds[w][b] = run;
+      run += c;
+    }
+  }
+  __syncthreads();
+  // 4. rank (stable) and scatter, 64 elements at a time
+  volatile uint32_t* off = lds[wave];
+#pragma unroll
   for (uint32_t r = 0; r < kSortRounds; ++r) {
     const uint64_t i = base + (uint64_t)r * 64 + lane;
     const bool valid = i < n;
-    uint32_t k = 0, v = 0;
-    if (valid) {
-      k = load_key(keys, i, clamp);
-      v = vals[i];
-    }
-    const uint32_t digit = (k >> shift) & mask;
+    const uint32_t digit = (kv[r].x >> shift) & mask;
     uint64_t peers = __ballot(valid);
-    if (peers == 0) break;
     for (uint32_t b = 0; b < bits; ++b) {
       const bool bit = (digit >> b) & 1u;
       const uint64_t vote = __ballot(bit);
       peers &= bit ? vote : ~vote;
     }
-    if (valid) {
-      const uint32_t rank = __popcll(peers & lanes_below());
-      const uint32_t dst = off[digit] + rank;
-      keys_out[dst] = k;
-      vals_out[dst] = v;
-    }
+    if (valid) dst[off[digit] + (uint32_t)__popcll(peers & lanes_below())] = kv[r];
     __builtin_amdgcn_wave_barrier();
-    if (valid && (peers & lanes_below()) == 0) off[digit] += __popcll(peers);
+    if (valid && (peers & lanes_below()) == 0) off[digit] += (uint32_t)__popcll(peers);
     __builtin_amdgcn_wave_barrier();
   }
 }
 
-hipError_t launch_sort_pairs(const UpdateWorkspace& ws, const uint32_t* keys_in, uint32_t clamp, uint64_t n,
-                             uint32_t bits, int* result_in_b, hipStream_t stream, Profiler* prof) {
-  *result_in_b = 0;
-  if (n == 0 || bits == 0) return hipSuccess;
+hipError_t launch_sort_pairs(const TableView& t, const UpdateWorkspace& ws, const int32_t* d_rows, uint64_t n,
+                             hipStream_t stream, Profiler* prof) {
+  if (n == 0) return hipSuccess;
   const uint64_t units = sort_units(n);
-  const uint32_t passes = (bits + kSortMaxBits - 1) / kSortMaxBits;
-  const uint32_t per = (bits + passes - 1) / passes;
-  uint32_t* totals = ws.hist + (uint64_t)kSortMaxBins * sort_units(n);
-  const uint32_t* src_k = keys_in ? keys_in : ws.key_a;
-  const uint32_t* src_v = ws.val_a;
-  uint32_t* dst_k = ws.key_b;
-  uint32_t* dst_v = ws.val_b;
-  dim3 block(kSortBlock), grid((unsigned)((units + kSortWaves - 1) / kSortWaves));
-  uint32_t shift = 0;
-  for (uint32_t p = 0; p < passes; ++p) {
-    const uint32_t b = bits - shift < per ? bits - shift : per;
-    const uint32_t cl = p == 0 ? clamp : 0xFFFFFFFFu;
-    MONO_LAUNCH(prof, K_SORT_HIST, stream, sort_hist_kernel, grid, block, src_k, cl, n, units, shift, b, ws.hist);
-    MONO_LAUNCH(prof, K_SORT_SCAN, stream, sort_scan_kernel, dim3(1u << b), dim3(256), ws.hist, units, totals);
-    MONO_LAUNCH(prof, K_SORT_SCATTER, stream, sort_scatter_kernel, grid, block, src_k, src_v, cl, n, units, shift, b, ws.hist,
-                       totals, dst_k, dst_v);
-    shift += b;
-    // ping-pong; after the first pass the source is always one of the workspace pairs
-    if (p % 2 == 0) {
-      src_k = ws.key_b; src_v = ws.val_b; dst_k = ws.key_a; dst_v = ws.val_a;
-    } else {
-      src_k = ws.key_a; src_v = ws.val_a; dst_k = ws.key_b; dst_v = ws.val_b;
-    }
-    *result_in_b = p % 2 == 0 ? 1 : 0;
+  uint32_t* totals = ws.hist + (uint64_t)kSortMaxBins * units;
+  const SortPlan worst = make_sort_plan((uint32_t)t.capacity);
+  const dim3 block(kSortBlock), grid((unsigned)units);
+  for (uint32_t p = 0; p < worst.passes; ++p) {
+    const uint2* src = p % 2 == 0 ? ws.pair_a : ws.pair_b;
+    uint2* dst = p % 2 == 0 ? ws.pair_b : ws.pair_a;
+    MONO_LAUNCH(prof, K_SORT_HIST, stream, sort_hist_kernel, grid, block, t.ctl, p, d_rows, src, n, units, ws.hist);
+    MONO_LAUNCH(prof, K_SORT_SCAN, stream, sort_scan_kernel, dim3(kSortMaxBins), dim3(256), t.ctl, p, ws.hist, units,
+                totals);
+    MONO_LAUNCH(prof, K_SORT_SCATTER, stream, sort_scatter_kernel, grid, block, t.ctl, p, d_rows, ws.bag_of, src, n,
+                units, ws.hist, totals, dst);
   }
   return hipGetLastError();
 }

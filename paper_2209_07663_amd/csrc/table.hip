@@ -65,13 +65,15 @@ size_t layout(mono_table* t, char* base, uint64_t capacity, uint32_t dim, uint32
   char* win_cnt = take(kWinLists * kWinStride * sizeof(uint32_t));
   char* sweep_list = take(kWinLists * sweep_cap * sizeof(uint32_t));
   char* sweep_cnt = take(kWinLists * kWinStride * sizeof(uint32_t));
-  char* key_a = take(max_ids * 4);
-  char* key_b = take(max_ids * 4);
-  char* val_a = take(max_ids * 4);
-  char* val_b = take(max_ids * 4);
+  uint32_t group = 1;  // lanes per row in the update kernels: dim/4 rounded up to a power of two
+  while (4 * group < dim) group <<= 1;
+  const uint64_t tiles = (reduce_chunks(max_ids) + 256 / group - 1) / (256 / group);
+  char* bag_of = take(max_ids * 4);
+  char* pair_a = take(max_ids * sizeof(uint2));
+  char* pair_b = take(max_ids * sizeof(uint2));
   char* hist = take(((size_t)kSortMaxBins * sort_units(max_ids) + kSortMaxBins) * 4);
-  char* part = take(2 * reduce_chunks(max_ids) * dim * sizeof(float));
-  char* part_row = take(2 * reduce_chunks(max_ids) * sizeof(uint32_t));
+  char* part = take(2 * tiles * dim * sizeof(float));
+  char* part_row = take(2 * tiles * sizeof(uint32_t));
   (void)max_bags;
   if (t && base) {
     TableView& v = t->view;
@@ -90,10 +92,9 @@ size_t layout(mono_table* t, char* base, uint64_t capacity, uint32_t dim, uint32
     v.sweep_list = (uint32_t*)sweep_list;
     v.sweep_cnt = (uint32_t*)sweep_cnt;
     v.sweep_cap = sweep_cap;
-    t->ws.key_a = (uint32_t*)key_a;
-    t->ws.key_b = (uint32_t*)key_b;
-    t->ws.val_a = (uint32_t*)val_a;
-    t->ws.val_b = (uint32_t*)val_b;
+    t->ws.bag_of = (uint32_t*)bag_of;
+    t->ws.pair_a = (uint2*)pair_a;
+    t->ws.pair_b = (uint2*)pair_b;
     t->ws.hist = (uint32_t*)hist;
     t->ws.part = (float*)part;
     t->ws.part_row = (uint32_t*)part_row;
