@@ -1,13 +1,20 @@
 // gather_pool: embedding-row gather with per-bag sum pooling.
 //
-// A group of lanes (dim/4 rounded up to a power of two) owns one bag; each lane keeps four
-// consecutive elements of the pooled row in registers, so one row read is one coalesced
-// dim*sizeof(E) access of the group and the pooled row is written once, in full lines.  Up to four
-// row reads of a bag are in flight per lane.  Summation is in occurrence order, in fp32.
+// A wave owns 64 consecutive bags.  First every lane loads the bounds and the first kIdsInRegs row
+// indices of ONE bag (coalesced: the bags of a wave are neighbours in `offsets` and in `rows`).
+// Then the wave walks its bags in rounds: a group of lanes (dim/4 rounded up to a power of two)
+// takes one bag per round, gets the bag's row indices from the owner lane by shuffle, reads the
+// rows (one coalesced dim*sizeof(E) access per row, kIdsInRegs of them in flight) and writes the
+// pooled row once, in full lines.  The few bags longer than kIdsInRegs read their remaining
+// indices from memory.  Measured on MI355X the earlier one-group-per-bag kernel spent half its time
+// on the dependent offset -> index -> row chain issued by eight times as many waves.
+// Summation is in occurrence order, in fp32.
 #include "common.h"
 #include "kernels.h"
 
 namespace mono {
+
+constexpr int kIdsInRegs = 8;
 
 template <typename E>
 __device__ inline float4 load4(const E* rows, uint32_t row, uint32_t dim, uint32_t lane4);
@@ -38,28 +45,43 @@ template <typename E>
 __global__ __launch_bounds__(256) void gather_pool_kernel(const E* __restrict__ rows, const int32_t* __restrict__ idx,
                                                           const int64_t* __restrict__ offsets, uint64_t n_bags,
                                                           uint32_t dim, uint32_t group_log2, float* __restrict__ out) {
-  const uint64_t tid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const uint64_t bag = tid >> group_log2;
-  const uint32_t l = (uint32_t)tid & ((1u << group_log2) - 1u);
-  if (bag >= n_bags || l * 4 >= dim) return;
-  const int64_t s = offsets[bag], e = offsets[bag + 1];
-  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  const float4 zero = acc;
-  for (int64_t i = s; i < e; i += 4) {
-    int32_t r0 = idx[i];
-    int32_t r1 = i + 1 < e ? idx[i + 1] : -1;
-    int32_t r2 = i + 2 < e ? idx[i + 2] : -1;
-    int32_t r3 = i + 3 < e ? idx[i + 3] : -1;
-    float4 v0 = r0 >= 0 ? load4<E>(rows, (uint32_t)r0, dim, l) : zero;
-    float4 v1 = r1 >= 0 ? load4<E>(rows, (uint32_t)r1, dim, l) : zero;
-    float4 v2 = r2 >= 0 ? load4<E>(rows, (uint32_t)r2, dim, l) : zero;
-    float4 v3 = r3 >= 0 ? load4<E>(rows, (uint32_t)r3, dim, l) : zero;
-    add4(acc, v0);
-    add4(acc, v1);
-    add4(acc, v2);
-    add4(acc, v3);
+  const uint64_t wave = ((uint64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const uint64_t bag_base = wave * 64;
+  if (bag_base >= n_bags) return;  // wave-uniform
+  const uint32_t lane = lane_id();
+  // phase 1: lane <-> bag
+  const bool mine = bag_base + lane < n_bags;
+  const int64_t s = mine ? offsets[bag_base + lane] : 0;
+  const int64_t e = mine ? offsets[bag_base + lane + 1] : 0;
+  const int len = (int)(e - s);
+  int32_t id[kIdsInRegs];
+#pragma unroll
+  for (int j = 0; j < kIdsInRegs; ++j) id[j] = j < len ? idx[s + j] : -1;
+  // phase 2: group <-> bag, one bag per group and round
+  const uint32_t group = 1u << group_log2, l = lane & (group - 1u), g = lane >> group_log2;
+  const uint32_t bags_per_round = 64u >> group_log2;
+  const bool active = l * 4 < dim;
+  const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (uint32_t q = 0; q < group; ++q) {
+    const int src = (int)(q * bags_per_round + g);
+    const int blen = __shfl(len, src);
+    const int64_t bs = __shfl(s, src);
+    float4 v[kIdsInRegs];
+#pragma unroll
+    for (int j = 0; j < kIdsInRegs; ++j) {
+      const int32_t r = __shfl(id[j], src);
+      v[j] = (r >= 0 && active) ? load4<E>(rows, (uint32_t)r, dim, l) : zero;
+    }
+    float4 acc = zero;
+#pragma unroll
+    for (int j = 0; j < kIdsInRegs; ++j) add4(acc, v[j]);
+    for (int j = kIdsInRegs; j < blen; ++j) {  // long bag: the rest of its indices straight from memory
+      const int32_t r = idx[bs + j];
+      if (r >= 0 && active) add4(acc, load4<E>(rows, (uint32_t)r, dim, l));
+    }
+    const uint64_t bag = bag_base + (uint32_t)src;
+    if (bag < n_bags && active) *reinterpret_cast<float4*>(out + bag * dim + l * 4) = acc;
   }
-  *reinterpret_cast<float4*>(out + bag * dim + l * 4) = acc;
 }
 
 hipError_t launch_gather_pool(const TableView& t, const int32_t* d_rows, const int64_t* d_offsets, uint64_t n_bags,
@@ -67,14 +89,14 @@ hipError_t launch_gather_pool(const TableView& t, const int32_t* d_rows, const i
   if (n_bags == 0) return hipSuccess;
   uint32_t group_log2 = 0;
   while ((4u << group_log2) < t.dim) ++group_log2;
-  uint64_t threads = n_bags << group_log2;
-  dim3 block(256), grid((unsigned)((threads + 255) / 256));
+  const uint64_t waves = (n_bags + 63) / 64;
+  const dim3 block(256), grid((unsigned)((waves + 3) / 4));
   if (t.bf16)
-    MONO_LAUNCH(prof, K_GATHER_POOL, stream, gather_pool_kernel<uint16_t>, grid, block, (const uint16_t*)t.rows, d_rows, d_offsets,
-                       n_bags, t.dim, group_log2, d_out);
+    MONO_LAUNCH(prof, K_GATHER_POOL, stream, gather_pool_kernel<uint16_t>, grid, block, (const uint16_t*)t.rows, d_rows,
+                d_offsets, n_bags, t.dim, group_log2, d_out);
   else
-    MONO_LAUNCH(prof, K_GATHER_POOL, stream, gather_pool_kernel<float>, grid, block, (const float*)t.rows, d_rows, d_offsets,
-                       n_bags, t.dim, group_log2, d_out);
+    MONO_LAUNCH(prof, K_GATHER_POOL, stream, gather_pool_kernel<float>, grid, block, (const float*)t.rows, d_rows,
+                d_offsets, n_bags, t.dim, group_log2, d_out);
   return hipGetLastError();
 }
 

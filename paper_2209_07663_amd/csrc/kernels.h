@@ -19,10 +19,11 @@ struct UpdateWorkspace {
 constexpr uint32_t kSortMaxBits = 11;              // widest radix digit
 constexpr uint32_t kSortMaxBins = 1u << kSortMaxBits;
 constexpr uint32_t kSortItemsPerBlock = 8192;      // consecutive elements owned by one block of the sort
-constexpr uint32_t kChunk = 128;                   // sorted occurrences reduced by one lane group
+constexpr int kPairsPerLane = 16;                  // sorted pairs per lane of a lane group in seg_reduce
+constexpr uint32_t kReduceTile = 256 * kPairsPerLane;  // sorted pairs reduced by one block
 
 inline uint64_t sort_units(uint64_t n) { return (n + kSortItemsPerBlock - 1) / kSortItemsPerBlock; }
-inline uint64_t reduce_chunks(uint64_t n) { return (n + kChunk - 1) / kChunk; }
+inline uint64_t reduce_tiles(uint64_t n) { return (n + kReduceTile - 1) / kReduceTile; }
 
 // How many bits of the row index are sorted, in how many passes (computed alike on host and device).
 struct SortPlan {

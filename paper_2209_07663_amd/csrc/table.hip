@@ -65,9 +65,7 @@ size_t layout(mono_table* t, char* base, uint64_t capacity, uint32_t dim, uint32
   char* win_cnt = take(kWinLists * kWinStride * sizeof(uint32_t));
   char* sweep_list = take(kWinLists * sweep_cap * sizeof(uint32_t));
   char* sweep_cnt = take(kWinLists * kWinStride * sizeof(uint32_t));
-  uint32_t group = 1;  // lanes per row in the update kernels: dim/4 rounded up to a power of two
-  while (4 * group < dim) group <<= 1;
-  const uint64_t tiles = (reduce_chunks(max_ids) + 256 / group - 1) / (256 / group);
+  const uint64_t tiles = reduce_tiles(max_ids);
   char* bag_of = take(max_ids * 4);
   char* pair_a = take(max_ids * sizeof(uint2));
   char* pair_b = take(max_ids * sizeof(uint2));

@@ -4,8 +4,9 @@
 //                of its occurrences)
 //   sort         stable radix sort of (row, bag) by row: the occurrences of a row become one run;
 //                dropped occurrences (row -1) sort behind everything
-//   seg_reduce   the sorted sequence is cut into chunks of kChunk; a lane group (dim/4 lanes, four
-//                elements each) walks one chunk, summing grad[bag] along each run.  A run that lies
+//   seg_reduce   the sorted sequence is cut into chunks of 16 pairs per lane of a lane group (dim/4
+//                lanes, four elements each); the group loads its chunk's pairs at once, then walks
+//                them with eight gradient rows in flight, summing grad[bag] along each run.  A run that lies
 //                inside the chunk is complete: Adagrad is applied at once.  A run that crosses a
 //                chunk border leaves a partial sum in LDS; the groups of a block then join the
 //                partials of runs that stay inside the block's tile (Adagrad again) and only runs
@@ -87,22 +88,25 @@ __device__ inline void acc4(float4& a, const float4& b) {
   a.w += b.w;
 }
 
-template <typename E>
+// GLOG = log2(lanes per row).  A group owns kPairsPerLane << GLOG consecutive sorted pairs, so a block
+// of 256 threads always owns a tile of kReduceTile pairs.
+template <typename E, int GLOG>
 __global__ __launch_bounds__(256) void seg_reduce_kernel(TableView t, const uint2* __restrict__ pair_a,
                                                          const uint2* __restrict__ pair_b, uint64_t n,
                                                          const float* __restrict__ grad, float lr, float eps,
-                                                         float* __restrict__ part, uint32_t* __restrict__ part_row,
-                                                         uint32_t group_log2) {
+                                                         float* __restrict__ part, uint32_t* __restrict__ part_row) {
   extern __shared__ float4 s_mem[];  // [2 * groups_per_block][dim / 4] vectors, then the slot rows
+  constexpr uint32_t group = 1u << GLOG, gpb = 256u >> GLOG;  // groups (= chunks) per block
+  constexpr uint32_t chunk = kPairsPerLane << GLOG;
+  constexpr int kBatch = group < 8 ? (int)group : 8;          // gradient rows in flight per lane
   const SortPlan plan = make_sort_plan(t.ctl->hwm);
   const uint2* __restrict__ sp = plan.passes % 2 ? pair_b : pair_a;  // where the sort left its result
   const uint32_t hwm = plan.hwm;
-  const uint32_t group = 1u << group_log2, gpb = 256u >> group_log2;  // groups (= chunks) per block
-  const uint32_t g = threadIdx.x >> group_log2, l = threadIdx.x & (group - 1u);
+  const uint32_t g = threadIdx.x >> GLOG, l = threadIdx.x & (group - 1u);
   const uint32_t dim4 = t.dim >> 2;
   float4* s_vec = s_mem;
   uint32_t* s_row = reinterpret_cast<uint32_t*>(s_mem + 2 * gpb * dim4);
-  const uint64_t n_chunks = (n + kChunk - 1) / kChunk;
+  const uint64_t n_chunks = (n + chunk - 1) / chunk;
   const uint64_t c0 = (uint64_t)blockIdx.x * gpb;  // first chunk of this block's tile
   const uint64_t c = c0 + g;
   const uint32_t chunks_here = (uint32_t)(n_chunks - c0 < gpb ? n_chunks - c0 : gpb);
@@ -110,45 +114,97 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(TableView t, const uint
   const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
   const float4* g4 = reinterpret_cast<const float4*>(grad);
 
+  // ---- phase 0: the tile's sorted pairs -> LDS (coalesced) ---------------------------------------
+  __shared__ uint2 s_pairs[kReduceTile];
+  {
+    const uint64_t t0 = (uint64_t)blockIdx.x * kReduceTile;
+#pragma unroll
+    for (int m = 0; m < kPairsPerLane; ++m) {
+      const uint32_t j = (uint32_t)m * 256u + threadIdx.x;
+      s_pairs[j] = t0 + j < n ? sp[t0 + j] : make_uint2(kNoRow, 0u);
+    }
+  }
+  __syncthreads();
+
   // ---- phase 1: every group reduces the runs of its chunk -------------------------------------
   uint32_t a_row = kNoRow, b_row = kNoRow;
   if (c < n_chunks) {
-    const uint64_t cs = c * kChunk, ce = cs + kChunk < n ? cs + kChunk : n;
-    uint32_t run = sp[cs].x;
-    bool head_in = cs == 0 || sp[cs - 1].x != run;
+    const uint64_t cs = c * chunk;
+    const uint32_t count = (uint32_t)(n - cs < chunk ? n - cs : chunk);
+    const uint2* mine = s_pairs + g * chunk;  // this group's chunk
+    const uint32_t before = cs > 0 ? sp[cs - 1].x : kNoRow;
+    const uint32_t after = cs + count < n ? sp[cs + count].x : kNoRow;
+    const uint32_t first = mine[0].x;
+    const bool first_head_in = cs == 0 || before != first;
+    uint32_t run = first;
+    bool head_in = first_head_in;
     float4 sum = zero;
-    auto flush = [&](bool tail_in) {
-      if (run >= hwm) return;  // dropped occurrences
-      if (head_in && tail_in) {
-        adagrad_row<E>(t, run, sum, active, l, group, lr, eps);
-      } else if (tail_in) {  // started in an earlier chunk, ends here
-        a_row = run;
-        if (active) s_vec[(2 * g) * dim4 + l] = sum;
-      } else {  // continues in the next chunk
-        b_row = run | (head_in ? kHeadFlag : 0u);
-        if (active) s_vec[(2 * g + 1) * dim4 + l] = sum;
-      }
-    };
-    for (uint64_t i = cs; i < ce; i += 4) {  // four occurrences in flight
-      uint2 kv[4];
-      float4 v[4];
+    E* rows = reinterpret_cast<E*>(t.rows);
+    const float inv_dim = 1.0f / (float)t.dim;
+    for (uint32_t p0 = 0; p0 < count; p0 += kBatch) {  // position of the batch in the chunk
+      {
+        uint32_t kx[kBatch + 1], ky[kBatch];
+        float4 v[kBatch], w[kBatch];
+        float a[kBatch];
+        bool tail[kBatch], apply[kBatch];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) kv[u] = i + u < ce ? sp[i + u] : make_uint2(kNoRow, 0u);
-#pragma unroll
-      for (int u = 0; u < 4; ++u) v[u] = (kv[u].x < hwm && active) ? g4[(uint64_t)kv[u].y * dim4 + l] : zero;
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        if (i + u >= ce) break;
-        if (kv[u].x != run) {
-          flush(true);
-          run = kv[u].x;
-          head_in = true;
-          sum = zero;
+        for (int u = 0; u < kBatch; ++u) {
+          const uint2 kv = p0 + (uint32_t)u < chunk ? mine[p0 + u] : make_uint2(kNoRow, 0u);
+          kx[u] = kv.x;
+          ky[u] = kv.y;
         }
-        acc4(sum, v[u]);
+        kx[kBatch] = p0 + kBatch < count ? mine[p0 + kBatch].x : after;
+        // everything the batch needs from memory is requested before anything is consumed: the
+        // gradient row of every pair and, for every run that ends in the batch and lies inside the
+        // chunk, its embedding row and accumulator
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+          const bool in = p0 + (uint32_t)u < count;
+          const uint32_t next = p0 + (uint32_t)u + 1 < count ? kx[u + 1] : after;
+          tail[u] = in && next != kx[u];
+          apply[u] = tail[u] && kx[u] < hwm && (kx[u] != first || first_head_in);
+          v[u] = (in && kx[u] < hwm && active) ? g4[(uint64_t)ky[u] * dim4 + l] : zero;
+          w[u] = (apply[u] && active) ? load_row4<E>(rows, kx[u], t.dim, l) : zero;
+          a[u] = apply[u] ? t.acc[kx[u]] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+          if (p0 + (uint32_t)u < count) {
+            if (kx[u] != run) {
+              run = kx[u];
+              head_in = true;
+              sum = zero;
+            }
+            acc4(sum, v[u]);
+            if (tail[u]) {
+              if (apply[u]) {  // the run lies inside the chunk: row-wise Adagrad at once
+                float ss = sum.x * sum.x + sum.y * sum.y + sum.z * sum.z + sum.w * sum.w;
+#pragma unroll
+                for (uint32_t d = 1; d < group; d <<= 1) ss += __shfl_xor(ss, (int)d);
+                const float acc = a[u] + ss * inv_dim;
+                const float denom = sqrtf(acc) + eps;
+                if (active) {
+                  float4 nw = w[u];
+                  nw.x -= lr * sum.x / denom;
+                  nw.y -= lr * sum.y / denom;
+                  nw.z -= lr * sum.z / denom;
+                  nw.w -= lr * sum.w / denom;
+                  store_row4<E>(rows, run, t.dim, l, nw);
+                }
+                if (l == 0) t.acc[run] = acc;
+              } else if (run < hwm) {  // started in an earlier chunk, ends here
+                a_row = run;
+                if (active) s_vec[(2 * g) * dim4 + l] = sum;
+              }
+            }
+          }
+        }
       }
     }
-    flush(!(ce < n && sp[ce].x == run));
+    if (after == run && run < hwm) {  // the last run continues in the next chunk
+      b_row = run | (head_in ? kHeadFlag : 0u);
+      if (active) s_vec[(2 * g + 1) * dim4 + l] = sum;
+    }
   }
   if (l == 0) {
     s_row[2 * g] = a_row;
@@ -252,21 +308,34 @@ hipError_t launch_apply_grad_adagrad(const TableView& t, const UpdateWorkspace& 
   uint32_t group_log2 = 0;
   while ((4u << group_log2) < t.dim) ++group_log2;
   const uint32_t gpb = 256u >> group_log2;
-  const uint64_t n_tiles = (reduce_chunks(n) + gpb - 1) / gpb;
+  const uint64_t n_tiles = (n + kReduceTile - 1) / kReduceTile;
   const dim3 block(256), grid((unsigned)n_tiles);
   const size_t lds_reduce = 2 * gpb * (t.dim / 4) * sizeof(float4) + 2 * gpb * sizeof(uint32_t);
   const size_t lds_combine = gpb * (t.dim / 4) * sizeof(float4);
+#define MONO_SEG_REDUCE(E, GLOG)                                                                                  \
+  MONO_LAUNCH_SMEM(prof, K_SEG_REDUCE, stream, (seg_reduce_kernel<E, GLOG>), grid, block, lds_reduce, t, ws.pair_a, \
+                   ws.pair_b, n, d_grad, lr, eps, ws.part, ws.part_row)
+#define MONO_SEG_REDUCE_ALL(E)                   \
+  switch (group_log2) {                          \
+    case 0: MONO_SEG_REDUCE(E, 0); break;        \
+    case 1: MONO_SEG_REDUCE(E, 1); break;        \
+    case 2: MONO_SEG_REDUCE(E, 2); break;        \
+    case 3: MONO_SEG_REDUCE(E, 3); break;        \
+    case 4: MONO_SEG_REDUCE(E, 4); break;        \
+    case 5: MONO_SEG_REDUCE(E, 5); break;        \
+    default: MONO_SEG_REDUCE(E, 6); break;       \
+  }
   if (t.bf16) {
-    MONO_LAUNCH_SMEM(prof, K_SEG_REDUCE, stream, seg_reduce_kernel<uint16_t>, grid, block, lds_reduce, t, ws.pair_a,
-                     ws.pair_b, n, d_grad, lr, eps, ws.part, ws.part_row, group_log2);
+    MONO_SEG_REDUCE_ALL(uint16_t)
     MONO_LAUNCH_SMEM(prof, K_COMBINE, stream, combine_kernel<uint16_t>, grid, block, lds_combine, t, n_tiles, ws.part,
                      ws.part_row, lr, eps, group_log2);
   } else {
-    MONO_LAUNCH_SMEM(prof, K_SEG_REDUCE, stream, seg_reduce_kernel<float>, grid, block, lds_reduce, t, ws.pair_a,
-                     ws.pair_b, n, d_grad, lr, eps, ws.part, ws.part_row, group_log2);
+    MONO_SEG_REDUCE_ALL(float)
     MONO_LAUNCH_SMEM(prof, K_COMBINE, stream, combine_kernel<float>, grid, block, lds_combine, t, n_tiles, ws.part,
                      ws.part_row, lr, eps, group_log2);
   }
+#undef MONO_SEG_REDUCE_ALL
+#undef MONO_SEG_REDUCE
   return hipGetLastError();
 }
 
