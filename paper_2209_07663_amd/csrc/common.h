@@ -33,6 +33,8 @@ __host__ __device__ inline unsigned long long make_meta(uint32_t row, uint32_t s
 constexpr int kWinLists = 64;               // sub-lists of elected occurrences (spreads the append counter)
 constexpr int kWinStride = 32;              // u32 words between two sub-list counters (one 128-byte line each)
 
+constexpr int kValidPairs = 2;              // Control::scratch slot: (row, bag) pairs kept by the sort
+
 struct StashEntry {
   uint64_t key;
   uint32_t row;
@@ -46,7 +48,7 @@ struct Control {
   uint32_t hwm;              // every row index ever handed out is below this high-water mark
   uint32_t pad_;
   unsigned long long n_admitted, n_expired, n_insert_failed, n_lost, n_full, max_chain;
-  unsigned long long scratch[8];  // per-call scalars (export count, sweep count)
+  unsigned long long scratch[8];  // per-call scalars: [0] sweep count, [1] export count, [kValidPairs]
 };
 
 // Everything a kernel needs to know about a table; passed by value.

@@ -28,28 +28,40 @@
 
 namespace mono {
 
-__device__ inline int find_in_bucket(const Bucket* b, uint64_t k) {
-  const ulonglong2* kp = reinterpret_cast<const ulonglong2*>(b->key);
-  ulonglong2 a0 = kp[0], a1 = kp[1], a2 = kp[2], a3 = kp[3];
+__device__ inline int match_keys(const ulonglong2 (&a)[4], uint64_t k) {
   int j = -1;
-  j = a0.x == k ? 0 : j;
-  j = a0.y == k ? 1 : j;
-  j = a1.x == k ? 2 : j;
-  j = a1.y == k ? 3 : j;
-  j = a2.x == k ? 4 : j;
-  j = a2.y == k ? 5 : j;
-  j = a3.x == k ? 6 : j;
-  j = a3.y == k ? 7 : j;
+  j = a[0].x == k ? 0 : j;
+  j = a[0].y == k ? 1 : j;
+  j = a[1].x == k ? 2 : j;
+  j = a[1].y == k ? 3 : j;
+  j = a[2].x == k ? 4 : j;
+  j = a[2].y == k ? 5 : j;
+  j = a[3].x == k ? 6 : j;
+  j = a[3].y == k ? 7 : j;
   return j;
+}
+
+__device__ inline void load_keys(const Bucket* b, ulonglong2 (&a)[4]) {
+  const ulonglong2* kp = reinterpret_cast<const ulonglong2*>(b->key);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) a[q] = kp[q];
 }
 
 __device__ inline void touch_counter(const TableView& t, uint64_t key, uint32_t step) {
   unsigned long long* w = &t.filter[filter_index(t, key)];
+  if (t.expire_steps == 0) {
+    // nothing ever ages: the stamp only moves forward and the count only grows, so two atomics
+    // whose results nobody waits for do it (low half = count, high half = last step)
+    uint32_t* half = reinterpret_cast<uint32_t*>(w);
+    atomicMax(half + 1, step);
+    atomicAdd(half, 1u);
+    return;
+  }
   unsigned long long cur = ld_agent(w);
   // first toucher of the batch ages the word and stamps the step; increments only ever follow it
   while ((uint32_t)(cur >> 32) != step) {
     uint32_t last = (uint32_t)(cur >> 32), cnt = (uint32_t)cur;
-    if (t.expire_steps > 0 && step - last >= t.expire_steps) cnt = 0;
+    if (step - last >= t.expire_steps) cnt = 0;
     unsigned long long want = ((unsigned long long)step << 32) | cnt;
     unsigned long long old = atomicCAS(w, cur, want);
     if (old == cur) break;
@@ -58,39 +70,76 @@ __device__ inline void touch_counter(const TableView& t, uint64_t key, uint32_t 
   atomicAdd(w, 1ull);  // unsaturated; read as min(count, 255)
 }
 
+// kProbeKeys keys per thread, walked side by side so that their dependent loads (key -> T0 bucket
+// -> T1 bucket -> meta) overlap: the kernel is bound by that chain, not by bytes.
+constexpr int kProbeKeys = 2;
+
 __global__ __launch_bounds__(256) void probe_count_kernel(TableView t, const int64_t* __restrict__ keys, uint64_t n,
                                                           uint32_t step, int32_t* __restrict__ rows_out) {
-  uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n) return;
-  uint64_t k = (uint64_t)keys[i];
-  if (k == kEmptyKey) {
-    rows_out[i] = kRowAbsent;
-    return;
+  const uint64_t base = (uint64_t)blockIdx.x * (256 * kProbeKeys) + threadIdx.x;
+  uint64_t k[kProbeKeys];
+  Bucket* b[kProbeKeys];
+  int j[kProbeKeys];
+  bool live[kProbeKeys];
+#pragma unroll
+  for (int q = 0; q < kProbeKeys; ++q) {
+    const uint64_t i = base + (uint64_t)q * 256;
+    k[q] = i < n ? (uint64_t)keys[i] : kEmptyKey;
+    live[q] = k[q] != kEmptyKey;
+    if (i < n && !live[q]) rows_out[i] = kRowAbsent;  // padding
   }
-  Bucket* b = &t.buckets[bucket_index(t, 0, k)];
-  int j = find_in_bucket(b, k);
-  if (j < 0) {
-    b = &t.buckets[bucket_index(t, 1, k)];
-    j = find_in_bucket(b, k);
+  {  // T0
+    ulonglong2 a[kProbeKeys][4];
+#pragma unroll
+    for (int q = 0; q < kProbeKeys; ++q) {
+      b[q] = &t.buckets[bucket_index(t, 0, k[q])];
+      if (live[q]) load_keys(b[q], a[q]);
+    }
+#pragma unroll
+    for (int q = 0; q < kProbeKeys; ++q) j[q] = live[q] ? match_keys(a[q], k[q]) : -1;
   }
-  if (j >= 0) {
-    const unsigned long long m = b->meta[j];
-    rows_out[i] = (int32_t)meta_row(m);
-    if (meta_seen(m) != step) reinterpret_cast<uint32_t*>(&b->meta[j])[1] = step;  // high half = stamp
-    return;
-  }
-  uint32_t sn = t.ctl->stash_n;
-  if (sn) {
-    sn = sn < kStashCap ? sn : kStashCap;
-    for (uint32_t s = 0; s < sn; ++s)
-      if (t.stash[s].key == k) {
-        rows_out[i] = (int32_t)t.stash[s].row;
-        t.stash[s].seen = step;
-        return;
+  {  // T1 for the keys not found in T0
+    ulonglong2 a[kProbeKeys][4];
+    Bucket* b1[kProbeKeys];
+#pragma unroll
+    for (int q = 0; q < kProbeKeys; ++q) {
+      b1[q] = &t.buckets[bucket_index(t, 1, k[q])];
+      if (live[q] && j[q] < 0) load_keys(b1[q], a[q]);
+    }
+#pragma unroll
+    for (int q = 0; q < kProbeKeys; ++q)
+      if (live[q] && j[q] < 0) {
+        j[q] = match_keys(a[q], k[q]);
+        b[q] = b1[q];
       }
   }
-  touch_counter(t, k, step);
-  rows_out[i] = kRowMiss;
+  unsigned long long m[kProbeKeys];
+#pragma unroll
+  for (int q = 0; q < kProbeKeys; ++q) m[q] = j[q] >= 0 ? b[q]->meta[j[q]] : kNoMeta;
+  const uint32_t sn = t.ctl->stash_n;
+#pragma unroll
+  for (int q = 0; q < kProbeKeys; ++q) {
+    if (!live[q]) continue;
+    const uint64_t i = base + (uint64_t)q * 256;
+    if (j[q] >= 0) {
+      rows_out[i] = (int32_t)meta_row(m[q]);
+      if (meta_seen(m[q]) != step) reinterpret_cast<uint32_t*>(&b[q]->meta[j[q]])[1] = step;  // high half = stamp
+      continue;
+    }
+    bool stashed = false;
+    if (sn) {
+      const uint32_t lim = sn < kStashCap ? sn : kStashCap;
+      for (uint32_t s = 0; s < lim && !stashed; ++s)
+        if (t.stash[s].key == k[q]) {
+          rows_out[i] = (int32_t)t.stash[s].row;
+          t.stash[s].seen = step;
+          stashed = true;
+        }
+    }
+    if (stashed) continue;
+    touch_counter(t, k[q], step);
+    rows_out[i] = kRowMiss;
+  }
 }
 
 // ---- election ------------------------------------------------------------------------------------
@@ -308,7 +357,8 @@ hipError_t launch_lookup_or_insert(const TableView& t, const int64_t* d_keys, ui
   if (n == 0) return hipSuccess;
   const dim3 block(256), grid((unsigned)((n + 255) / 256));
   const dim3 igrid(grid.x < 2048u ? grid.x : 2048u);
-  MONO_LAUNCH(prof, K_PROBE_COUNT, stream, probe_count_kernel, grid, block, t, d_keys, n, step, d_rows_out);
+  const dim3 pgrid((unsigned)((n + 256 * kProbeKeys - 1) / (256 * kProbeKeys)));
+  MONO_LAUNCH(prof, K_PROBE_COUNT, stream, probe_count_kernel, pgrid, block, t, d_keys, n, step, d_rows_out);
   MONO_LAUNCH(prof, K_ADMIT_ELECT, stream, admit_elect_kernel, grid, block, t, d_keys, n, epoch, d_rows_out);
   if (t.bf16)
     MONO_LAUNCH(prof, K_INSERT, stream, insert_kernel<uint16_t>, igrid, block, t, d_keys, step, d_rows_out);

@@ -2,10 +2,11 @@
 // row together before the gradient reduction.
 //
 // The key width is decided ON THE DEVICE: row indices are handed out in ascending order, so every
-// row in use is below the high-water mark `hwm` kept in the control block, and dropped occurrences
-// (row -1) get the key `hwm` itself.  bit_length(hwm) bits are sorted in the fewest passes of at
-// most kSortMaxBits bits; the host launches the worst-case number of passes and the superfluous
-// ones return at once.  Pass p reads buffer (p even ? a : b) and writes the other one.
+// row in use is below the high-water mark `hwm` kept in the control block.  bit_length(hwm) bits
+// are sorted in the fewest passes of at most kSortMaxBits bits; the host launches the worst-case
+// number of passes and the superfluous ones return at once.  Pass p reads buffer (p even ? a : b)
+// and writes the other one.  Dropped occurrences (row -1) are left out by pass 0, which also
+// publishes the number of pairs that remain (kValidPairs slot of the control block's scratch).
 //
 // Unit of work: one block of four waves owns kSortItemsPerBlock consecutive elements, a quarter
 // per wave.  Per pass:
@@ -45,12 +46,13 @@ __global__ __launch_bounds__(kSortBlock) void sort_hist_kernel(const Control* __
   for (uint32_t b = threadIdx.x; b < nbins; b += kSortBlock) cnt[b] = 0;
   __syncthreads();
   const uint64_t base = unit * kSortItemsPerBlock;
+  if (pass > 0) n = ctl->scratch[kValidPairs];
 #pragma unroll 8
   for (uint32_t r = 0; r < kSortItemsPerBlock / kSortBlock; ++r) {
     const uint64_t i = base + (uint64_t)r * kSortBlock + threadIdx.x;
     if (i < n) {
       const uint32_t k = pass == 0 ? first_key(rows, i, plan.hwm) : src[i].x;
-      atomicAdd(&cnt[(k >> shift) & mask], 1u);
+      if (k < plan.hwm) atomicAdd(&cnt[(k >> shift) & mask], 1u);
     }
   }
   __syncthreads();
@@ -90,7 +92,7 @@ __global__ __launch_bounds__(256) void sort_scan_kernel(const Control* __restric
   if (threadIdx.x == 0) totals[blockIdx.x] = carry_s;
 }
 
-__global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(const Control* __restrict__ ctl, uint32_t pass,
+__global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __restrict__ ctl, uint32_t pass,
                                                                   const int32_t* __restrict__ rows,
                                                                   const uint32_t* __restrict__ bag_of,
                                                                   const uint2* __restrict__ src, uint64_t n,
@@ -106,6 +108,7 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(const Control*
   const uint32_t shift = plan.shift(pass), bits = plan.width(pass), nbins = 1u << bits, mask = nbins - 1;
 
   // 1. this wave's elements -> registers (independent, coalesced loads)
+  if (pass > 0) n = ctl->scratch[kValidPairs];
   const uint64_t base = unit * kSortItemsPerBlock + (uint64_t)wave * kSortPerWave;
   uint2 kv[kSortRounds];
 #pragma unroll
@@ -113,6 +116,7 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(const Control*
     const uint64_t i = base + (uint64_t)r * 64 + lane;
     kv[r] = make_uint2(0xFFFFFFFFu, 0u);
     if (i < n) kv[r] = pass == 0 ? make_uint2(first_key(rows, i, plan.hwm), bag_of[i]) : src[i];
+    if (kv[r].x >= plan.hwm) kv[r].x = 0xFFFFFFFFu;  // dropped occurrence (or past the end): left out
   }
   for (uint32_t b = threadIdx.x; b < nbins; b += kSortBlock) {
 #pragma unroll
@@ -144,13 +148,13 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(const Control*
         run += local[q];
       }
     }
+    if (pass == 0 && blockIdx.x == 0 && lane == 63) ctl->scratch[kValidPairs] = x;  // pairs that remain
   }
   __syncthreads();
   // 2. per-wave digit counts
 #pragma unroll
   for (uint32_t r = 0; r < kSortRounds; ++r) {
-    const uint64_t i = base + (uint64_t)r * 64 + lane;
-    if (i < n) atomicAdd(&lds[wave][(kv[r].x >> shift) & mask], 1u);
+    if (kv[r].x != 0xFFFFFFFFu) atomicAdd(&lds[wave][(kv[r].x >> shift) & mask], 1u);
   }
   __syncthreads();
   // 3. counts -> start offset of every (wave, bin)
@@ -168,8 +172,7 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(const Control*
   volatile uint32_t* off = lds[wave];
 #pragma unroll
   for (uint32_t r = 0; r < kSortRounds; ++r) {
-    const uint64_t i = base + (uint64_t)r * 64 + lane;
-    const bool valid = i < n;
+    const bool valid = kv[r].x != 0xFFFFFFFFu;
     const uint32_t digit = (kv[r].x >> shift) & mask;
     uint64_t peers = __ballot(valid);
     for (uint32_t b = 0; b < bits; ++b) {

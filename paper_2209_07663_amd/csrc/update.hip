@@ -3,7 +3,7 @@
 //   expand       bag index of every occurrence (the pooled gradient of bag b is the gradient of each
 //                of its occurrences)
 //   sort         stable radix sort of (row, bag) by row: the occurrences of a row become one run;
-//                dropped occurrences (row -1) sort behind everything
+//                dropped occurrences (row -1) are left out
 //   seg_reduce   the sorted sequence is cut into chunks of 16 pairs per lane of a lane group (dim/4
 //                lanes, four elements each); the group loads its chunk's pairs at once, then walks
 //                them with eight gradient rows in flight, summing grad[bag] along each run.  A run that lies
@@ -60,6 +60,12 @@ __device__ inline void store_row4<uint16_t>(uint16_t* rows, uint32_t row, uint32
   *reinterpret_cast<uint2*>(rows + (uint64_t)row * dim + l * 4) = u;
 }
 
+// lr / (sqrt(acc) + eps) with the hardware square root and reciprocal (1 ulp each: the update is
+// compared at 1e-5, and this runs once per distinct row inside the serial walk of seg_reduce)
+__device__ inline float step_scale(float acc, float lr, float eps) {
+  return lr * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(acc) + eps);
+}
+
 // Row-wise Adagrad on one row by one lane group; g = this lane's four gradient elements (zero in
 // lanes beyond dim).  acc += mean_j g_j^2; w_j -= lr * g_j / (sqrt(acc) + eps).
 template <typename E>
@@ -68,14 +74,14 @@ __device__ inline void adagrad_row(const TableView& t, uint32_t row, float4 g, b
   float ss = g.x * g.x + g.y * g.y + g.z * g.z + g.w * g.w;
   for (uint32_t d = 1; d < group; d <<= 1) ss += __shfl_xor(ss, (int)d);
   const float acc = t.acc[row] + ss / (float)t.dim;
-  const float denom = sqrtf(acc) + eps;
+  const float scale = step_scale(acc, lr, eps);
   if (active) {
     E* rows = reinterpret_cast<E*>(t.rows);
     float4 w = load_row4<E>(rows, row, t.dim, l);
-    w.x -= lr * g.x / denom;
-    w.y -= lr * g.y / denom;
-    w.z -= lr * g.z / denom;
-    w.w -= lr * g.w / denom;
+    w.x = fmaf(-scale, g.x, w.x);
+    w.y = fmaf(-scale, g.y, w.y);
+    w.z = fmaf(-scale, g.z, w.z);
+    w.w = fmaf(-scale, g.w, w.w);
     store_row4<E>(rows, row, t.dim, l, w);
   }
   if (l == 0) t.acc[row] = acc;
@@ -102,6 +108,7 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(TableView t, const uint
   const SortPlan plan = make_sort_plan(t.ctl->hwm);
   const uint2* __restrict__ sp = plan.passes % 2 ? pair_b : pair_a;  // where the sort left its result
   const uint32_t hwm = plan.hwm;
+  n = t.ctl->scratch[kValidPairs];  // the sort left the dropped occurrences out
   const uint32_t g = threadIdx.x >> GLOG, l = threadIdx.x & (group - 1u);
   const uint32_t dim4 = t.dim >> 2;
   float4* s_vec = s_mem;
@@ -182,13 +189,13 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(TableView t, const uint
 #pragma unroll
                 for (uint32_t d = 1; d < group; d <<= 1) ss += __shfl_xor(ss, (int)d);
                 const float acc = a[u] + ss * inv_dim;
-                const float denom = sqrtf(acc) + eps;
+                const float scale = step_scale(acc, lr, eps);
                 if (active) {
                   float4 nw = w[u];
-                  nw.x -= lr * sum.x / denom;
-                  nw.y -= lr * sum.y / denom;
-                  nw.z -= lr * sum.z / denom;
-                  nw.w -= lr * sum.w / denom;
+                  nw.x = fmaf(-scale, sum.x, nw.x);
+                  nw.y = fmaf(-scale, sum.y, nw.y);
+                  nw.z = fmaf(-scale, sum.z, nw.z);
+                  nw.w = fmaf(-scale, sum.w, nw.w);
                   store_row4<E>(rows, run, t.dim, l, nw);
                 }
                 if (l == 0) t.acc[run] = acc;
