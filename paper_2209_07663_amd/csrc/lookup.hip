@@ -28,25 +28,6 @@
 
 namespace mono {
 
-__device__ inline int match_keys(const ulonglong2 (&a)[4], uint64_t k) {
-  int j = -1;
-  j = a[0].x == k ? 0 : j;
-  j = a[0].y == k ? 1 : j;
-  j = a[1].x == k ? 2 : j;
-  j = a[1].y == k ? 3 : j;
-  j = a[2].x == k ? 4 : j;
-  j = a[2].y == k ? 5 : j;
-  j = a[3].x == k ? 6 : j;
-  j = a[3].y == k ? 7 : j;
-  return j;
-}
-
-__device__ inline void load_keys(const Bucket* b, ulonglong2 (&a)[4]) {
-  const ulonglong2* kp = reinterpret_cast<const ulonglong2*>(b->key);
-#pragma unroll
-  for (int q = 0; q < 4; ++q) a[q] = kp[q];
-}
-
 __device__ inline void touch_counter(const TableView& t, uint64_t key, uint32_t step) {
   unsigned long long* w = &t.filter[filter_index(t, key)];
   if (t.expire_steps == 0) {
@@ -70,76 +51,90 @@ __device__ inline void touch_counter(const TableView& t, uint64_t key, uint32_t 
   atomicAdd(w, 1ull);  // unsaturated; read as min(count, 255)
 }
 
-// kProbeKeys keys per thread, walked side by side so that their dependent loads (key -> T0 bucket
-// -> T1 bucket -> meta) overlap: the kernel is bound by that chain, not by bytes.
-constexpr int kProbeKeys = 2;
+// Cooperative probe.  A lane owns one key; the eight lanes of a group then visit the group's eight
+// buckets one after another, each lane reading 16 bytes, so that a bucket line (eight keys + eight
+// meta words) is ONE 128-byte access: lanes 0-3 of the group hold the keys two by two, lanes 4-7 the
+// meta words.  (Four 16-byte loads by one lane on the same line cost ~2.5x more once the line comes
+// from beyond the L2: measured.)  The eight loads of a lane are independent and in flight together.
+// side = 0 probes T0 for the keys flagged `want`, side = 1 probes T1.
+__device__ inline void probe_side(const TableView& t, uint64_t k, uint64_t bucket, bool want, uint32_t gi,
+                                  uint32_t gbase, unsigned long long* meta_out, int* slot_out) {
+  ulonglong2 d[kBucket];
+#pragma unroll
+  for (int r = 0; r < kBucket; ++r) {
+    const int src = (int)gbase + r;
+    const int need = __shfl((int)want, src);
+    const uint64_t bb = __shfl(bucket, src);
+    d[r] = make_ulonglong2(0ull, 0ull);
+    if (need) d[r] = reinterpret_cast<const ulonglong2*>(t.buckets + bb)[gi];
+  }
+#pragma unroll
+  for (int r = 0; r < kBucket; ++r) {
+    const int src = (int)gbase + r;
+    const int need = __shfl((int)want, src);
+    const uint64_t kr = __shfl(k, src);
+    const bool is_key_lane = gi < 4;
+    const uint64_t m0 = __ballot(need && is_key_lane && d[r].x == kr);
+    const uint64_t m1 = __ballot(need && is_key_lane && d[r].y == kr);
+    const uint32_t g0 = (uint32_t)(m0 >> gbase) & 0xFu, g1 = (uint32_t)(m1 >> gbase) & 0xFu;
+    const int s = g0 ? 2 * (__ffs((int)g0) - 1) : (g1 ? 2 * (__ffs((int)g1) - 1) + 1 : -1);
+    const int ml = (int)gbase + 4 + ((s < 0 ? 0 : s) >> 1);
+    const unsigned long long mx = __shfl(d[r].x, ml), my = __shfl(d[r].y, ml);
+    if ((int)gi == r && s >= 0) {
+      *meta_out = (s & 1) ? my : mx;
+      *slot_out = s;
+    }
+  }
+}
 
 __global__ __launch_bounds__(256) void probe_count_kernel(TableView t, const int64_t* __restrict__ keys, uint64_t n,
                                                           uint32_t step, int32_t* __restrict__ rows_out) {
-  const uint64_t base = (uint64_t)blockIdx.x * (256 * kProbeKeys) + threadIdx.x;
-  uint64_t k[kProbeKeys];
-  Bucket* b[kProbeKeys];
-  int j[kProbeKeys];
-  bool live[kProbeKeys];
-#pragma unroll
-  for (int q = 0; q < kProbeKeys; ++q) {
-    const uint64_t i = base + (uint64_t)q * 256;
-    k[q] = i < n ? (uint64_t)keys[i] : kEmptyKey;
-    live[q] = k[q] != kEmptyKey;
-    if (i < n && !live[q]) rows_out[i] = kRowAbsent;  // padding
+  const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const uint32_t lane = lane_id(), gi = lane & 7u, gbase = lane & ~7u;
+  const uint64_t k = i < n ? (uint64_t)keys[i] : kEmptyKey;
+  const bool live = k != kEmptyKey;
+  // Negative lookup through the admission counters.  When nothing ages (expire_steps == 0) a
+  // counter never decreases, and a stored key reached freq_threshold on its counter when it was
+  // admitted: a counter below the threshold proves the key absent, and both bucket probes are saved
+  // (most misses are tail IDs seen once).  Counts added by this very batch can only make the test
+  // err on the side of probing.
+  bool maybe = live;
+  if (t.expire_steps == 0 && live) {
+    const uint32_t cnt = reinterpret_cast<const uint32_t*>(&t.filter[filter_index(t, k)])[0];
+    maybe = cnt >= (t.freq_threshold > 1u ? t.freq_threshold : 1u);
   }
-  {  // T0
-    ulonglong2 a[kProbeKeys][4];
-#pragma unroll
-    for (int q = 0; q < kProbeKeys; ++q) {
-      b[q] = &t.buckets[bucket_index(t, 0, k[q])];
-      if (live[q]) load_keys(b[q], a[q]);
-    }
-#pragma unroll
-    for (int q = 0; q < kProbeKeys; ++q) j[q] = live[q] ? match_keys(a[q], k[q]) : -1;
+  const uint64_t b0 = bucket_index(t, 0, k), b1 = bucket_index(t, 1, k);
+  unsigned long long m = kNoMeta;
+  int slot = -1;
+  probe_side(t, k, b0, maybe, gi, gbase, &m, &slot);
+  uint64_t where = b0;
+  const bool again = maybe && slot < 0;
+  if (__ballot(again)) {  // wave-uniform
+    probe_side(t, k, b1, again, gi, gbase, &m, &slot);
+    if (again) where = b1;
   }
-  {  // T1 for the keys not found in T0
-    ulonglong2 a[kProbeKeys][4];
-    Bucket* b1[kProbeKeys];
-#pragma unroll
-    for (int q = 0; q < kProbeKeys; ++q) {
-      b1[q] = &t.buckets[bucket_index(t, 1, k[q])];
-      if (live[q] && j[q] < 0) load_keys(b1[q], a[q]);
-    }
-#pragma unroll
-    for (int q = 0; q < kProbeKeys; ++q)
-      if (live[q] && j[q] < 0) {
-        j[q] = match_keys(a[q], k[q]);
-        b[q] = b1[q];
+  if (i >= n) return;
+  if (!live) {
+    rows_out[i] = kRowAbsent;
+    return;
+  }
+  if (slot >= 0) {
+    rows_out[i] = (int32_t)meta_row(m);
+    if (meta_seen(m) != step) reinterpret_cast<uint32_t*>(&t.buckets[where].meta[slot])[1] = step;  // stamp
+    return;
+  }
+  const uint32_t sn = t.ctl->stash_n;
+  if (sn) {
+    const uint32_t lim = sn < kStashCap ? sn : kStashCap;
+    for (uint32_t s = 0; s < lim; ++s)
+      if (t.stash[s].key == k) {
+        rows_out[i] = (int32_t)t.stash[s].row;
+        t.stash[s].seen = step;
+        return;
       }
   }
-  unsigned long long m[kProbeKeys];
-#pragma unroll
-  for (int q = 0; q < kProbeKeys; ++q) m[q] = j[q] >= 0 ? b[q]->meta[j[q]] : kNoMeta;
-  const uint32_t sn = t.ctl->stash_n;
-#pragma unroll
-  for (int q = 0; q < kProbeKeys; ++q) {
-    if (!live[q]) continue;
-    const uint64_t i = base + (uint64_t)q * 256;
-    if (j[q] >= 0) {
-      rows_out[i] = (int32_t)meta_row(m[q]);
-      if (meta_seen(m[q]) != step) reinterpret_cast<uint32_t*>(&b[q]->meta[j[q]])[1] = step;  // high half = stamp
-      continue;
-    }
-    bool stashed = false;
-    if (sn) {
-      const uint32_t lim = sn < kStashCap ? sn : kStashCap;
-      for (uint32_t s = 0; s < lim && !stashed; ++s)
-        if (t.stash[s].key == k[q]) {
-          rows_out[i] = (int32_t)t.stash[s].row;
-          t.stash[s].seen = step;
-          stashed = true;
-        }
-    }
-    if (stashed) continue;
-    touch_counter(t, k[q], step);
-    rows_out[i] = kRowMiss;
-  }
+  touch_counter(t, k, step);
+  rows_out[i] = kRowMiss;
 }
 
 // ---- election ------------------------------------------------------------------------------------
@@ -357,8 +352,7 @@ hipError_t launch_lookup_or_insert(const TableView& t, const int64_t* d_keys, ui
   if (n == 0) return hipSuccess;
   const dim3 block(256), grid((unsigned)((n + 255) / 256));
   const dim3 igrid(grid.x < 2048u ? grid.x : 2048u);
-  const dim3 pgrid((unsigned)((n + 256 * kProbeKeys - 1) / (256 * kProbeKeys)));
-  MONO_LAUNCH(prof, K_PROBE_COUNT, stream, probe_count_kernel, pgrid, block, t, d_keys, n, step, d_rows_out);
+  MONO_LAUNCH(prof, K_PROBE_COUNT, stream, probe_count_kernel, grid, block, t, d_keys, n, step, d_rows_out);
   MONO_LAUNCH(prof, K_ADMIT_ELECT, stream, admit_elect_kernel, grid, block, t, d_keys, n, epoch, d_rows_out);
   if (t.bf16)
     MONO_LAUNCH(prof, K_INSERT, stream, insert_kernel<uint16_t>, igrid, block, t, d_keys, step, d_rows_out);
