@@ -115,7 +115,18 @@ def main():
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--cpu-budget", type=float, default=12.0, help="seconds of oracle time; 0 = skip")
     ap.add_argument("--workers", type=int, default=min(16, os.cpu_count() or 8))
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 1 GiB device copy five times (reference for FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
+    if args.calibrate_copy:
+        import torch
+        a = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+        b = torch.empty_like(a)
+        for _ in range(5):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copied_bytes_per_launch": a.numel() * 4, "launches": 5}))
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives are part of it); use --gpus 1",
               file=sys.stderr)
