@@ -28,14 +28,14 @@
 
 namespace mono {
 
-__device__ inline void touch_counter(const TableView& t, uint64_t key, uint32_t step) {
+__device__ inline void touch_counter(const TableView& t, uint64_t key, uint32_t step, uint32_t times) {
   unsigned long long* w = &t.filter[filter_index(t, key)];
   if (t.expire_steps == 0) {
     // nothing ever ages: the stamp only moves forward and the count only grows, so two atomics
     // whose results nobody waits for do it (low half = count, high half = last step)
     uint32_t* half = reinterpret_cast<uint32_t*>(w);
     atomicMax(half + 1, step);
-    atomicAdd(half, 1u);
+    atomicAdd(half, times);
     return;
   }
   unsigned long long cur = ld_agent(w);
@@ -48,7 +48,7 @@ __device__ inline void touch_counter(const TableView& t, uint64_t key, uint32_t 
     if (old == cur) break;
     cur = old;
   }
-  atomicAdd(w, 1ull);  // unsaturated; read as min(count, 255)
+  atomicAdd(w, (unsigned long long)times);  // unsaturated; read as min(count, 255)
 }
 
 // Cooperative probe.  A lane owns one key; the eight lanes of a group then visit the group's eight
@@ -87,8 +87,21 @@ __device__ inline void probe_side(const TableView& t, uint64_t k, uint64_t bucke
   }
 }
 
-__global__ __launch_bounds__(256) void probe_count_kernel(TableView t, const int64_t* __restrict__ keys, uint64_t n,
-                                                          uint32_t step, int32_t* __restrict__ rows_out) {
+constexpr int kProbeBlock = 1024;           // threads (= keys) per block of probe_count
+constexpr int kMissSlots = 2 * kProbeBlock;  // slots of the block's LDS set of missing keys
+
+__global__ __launch_bounds__(kProbeBlock) void probe_count_kernel(TableView t, const int64_t* __restrict__ keys,
+                                                                  uint64_t n, uint32_t step,
+                                                                  int32_t* __restrict__ rows_out) {
+  // The block's missing keys are gathered in an LDS set with their multiplicities, and each distinct
+  // one touches its counter once: a hot ID that is not (yet) admitted would otherwise hit one counter
+  // word with 10^5 atomics, which serialise at ~12 ns each.
+  __shared__ unsigned long long miss_key[kMissSlots];
+  __shared__ uint32_t miss_cnt[kMissSlots];
+  for (int s = threadIdx.x; s < kMissSlots; s += kProbeBlock) {
+    miss_key[s] = kEmptyKey;
+    miss_cnt[s] = 0;
+  }
   const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const uint32_t lane = lane_id(), gi = lane & 7u, gbase = lane & ~7u;
   const uint64_t k = i < n ? (uint64_t)keys[i] : kEmptyKey;
@@ -113,28 +126,41 @@ __global__ __launch_bounds__(256) void probe_count_kernel(TableView t, const int
     probe_side(t, k, b1, again, gi, gbase, &m, &slot);
     if (again) where = b1;
   }
-  if (i >= n) return;
-  if (!live) {
-    rows_out[i] = kRowAbsent;
-    return;
-  }
-  if (slot >= 0) {
-    rows_out[i] = (int32_t)meta_row(m);
-    if (meta_seen(m) != step) reinterpret_cast<uint32_t*>(&t.buckets[where].meta[slot])[1] = step;  // stamp
-    return;
-  }
-  const uint32_t sn = t.ctl->stash_n;
-  if (sn) {
-    const uint32_t lim = sn < kStashCap ? sn : kStashCap;
-    for (uint32_t s = 0; s < lim; ++s)
-      if (t.stash[s].key == k) {
-        rows_out[i] = (int32_t)t.stash[s].row;
-        t.stash[s].seen = step;
-        return;
+  bool miss = false;
+  if (i < n) {
+    if (!live) {
+      rows_out[i] = kRowAbsent;
+    } else if (slot >= 0) {
+      rows_out[i] = (int32_t)meta_row(m);
+      if (meta_seen(m) != step) reinterpret_cast<uint32_t*>(&t.buckets[where].meta[slot])[1] = step;  // stamp
+    } else {
+      miss = true;
+      const uint32_t sn = t.ctl->stash_n;
+      if (sn) {
+        const uint32_t lim = sn < kStashCap ? sn : kStashCap;
+        for (uint32_t s = 0; s < lim && miss; ++s)
+          if (t.stash[s].key == k) {
+            rows_out[i] = (int32_t)t.stash[s].row;
+            t.stash[s].seen = step;
+            miss = false;
+          }
       }
+      if (miss) rows_out[i] = kRowMiss;
+    }
   }
-  touch_counter(t, k, step);
-  rows_out[i] = kRowMiss;
+  __syncthreads();  // the LDS set is cleared
+  if (miss) {
+    uint32_t pos = (uint32_t)(mix64(k ^ t.s_dedup) >> 40) & (kMissSlots - 1);
+    for (;;) {  // at most kProbeBlock keys in 2 * kProbeBlock slots: a free slot always turns up
+      const unsigned long long old = atomicCAS(&miss_key[pos], (unsigned long long)kEmptyKey, (unsigned long long)k);
+      if (old == kEmptyKey || old == k) break;
+      pos = (pos + 1) & (kMissSlots - 1);
+    }
+    atomicAdd(&miss_cnt[pos], 1u);
+  }
+  __syncthreads();
+  for (int s = threadIdx.x; s < kMissSlots; s += kProbeBlock)
+    if (miss_cnt[s]) touch_counter(t, miss_key[s], step, miss_cnt[s]);
 }
 
 // ---- election ------------------------------------------------------------------------------------
@@ -352,7 +378,8 @@ hipError_t launch_lookup_or_insert(const TableView& t, const int64_t* d_keys, ui
   if (n == 0) return hipSuccess;
   const dim3 block(256), grid((unsigned)((n + 255) / 256));
   const dim3 igrid(grid.x < 2048u ? grid.x : 2048u);
-  MONO_LAUNCH(prof, K_PROBE_COUNT, stream, probe_count_kernel, grid, block, t, d_keys, n, step, d_rows_out);
+  MONO_LAUNCH(prof, K_PROBE_COUNT, stream, probe_count_kernel, dim3((unsigned)((n + kProbeBlock - 1) / kProbeBlock)),
+              dim3(kProbeBlock), t, d_keys, n, step, d_rows_out);
   MONO_LAUNCH(prof, K_ADMIT_ELECT, stream, admit_elect_kernel, grid, block, t, d_keys, n, epoch, d_rows_out);
   if (t.bf16)
     MONO_LAUNCH(prof, K_INSERT, stream, insert_kernel<uint16_t>, igrid, block, t, d_keys, step, d_rows_out);
