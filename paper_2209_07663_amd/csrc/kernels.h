@@ -23,7 +23,7 @@ constexpr int kPairsPerLane = 16;                  // sorted pairs per lane of a
 constexpr uint32_t kReduceTile = 256 * kPairsPerLane;  // sorted pairs reduced by one block
 
 inline uint64_t sort_units(uint64_t n) { return (n + kSortItemsPerBlock - 1) / kSortItemsPerBlock; }
-inline uint64_t reduce_tiles(uint64_t n) { return (n + kReduceTile - 1) / kReduceTile; }
+inline uint64_t reduce_tiles(uint64_t n) { return (n + 255) / 256; }  // most tiles a batch can need (one pair per lane)
 
 // How many bits of the row index are sorted, in how many passes (computed alike on host and device).
 struct SortPlan {

@@ -94,16 +94,18 @@ __device__ inline void acc4(float4& a, const float4& b) {
   a.w += b.w;
 }
 
-// GLOG = log2(lanes per row).  A group owns kPairsPerLane << GLOG consecutive sorted pairs, so a block
-// of 256 threads always owns a tile of kReduceTile pairs.
+// GLOG = log2(lanes per row).  A group owns ppl << GLOG consecutive sorted pairs (ppl = pairs per
+// lane, at most kPairsPerLane), so a block of 256 threads always owns a tile of 256 * ppl pairs; the
+// host picks ppl so that small batches still fill the machine.
 template <typename E, int GLOG>
 __global__ __launch_bounds__(256) void seg_reduce_kernel(TableView t, const uint2* __restrict__ pair_a,
                                                          const uint2* __restrict__ pair_b, uint64_t n,
                                                          const float* __restrict__ grad, float lr, float eps,
-                                                         float* __restrict__ part, uint32_t* __restrict__ part_row) {
+                                                         float* __restrict__ part, uint32_t* __restrict__ part_row,
+                                                         uint32_t ppl) {
   extern __shared__ float4 s_mem[];  // [2 * groups_per_block][dim / 4] vectors, then the slot rows
   constexpr uint32_t group = 1u << GLOG, gpb = 256u >> GLOG;  // groups (= chunks) per block
-  constexpr uint32_t chunk = kPairsPerLane << GLOG;
+  const uint32_t chunk = ppl << GLOG, tile = 256u * ppl;
   constexpr int kBatch = group < 8 ? (int)group : 8;          // gradient rows in flight per lane
   const SortPlan plan = make_sort_plan(t.ctl->hwm);
   const uint2* __restrict__ sp = plan.passes % 2 ? pair_b : pair_a;  // where the sort left its result
@@ -124,11 +126,11 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(TableView t, const uint
   // ---- phase 0: the tile's sorted pairs -> LDS (coalesced) ---------------------------------------
   __shared__ uint2 s_pairs[kReduceTile];
   {
-    const uint64_t t0 = (uint64_t)blockIdx.x * kReduceTile;
+    const uint64_t t0 = (uint64_t)blockIdx.x * tile;
 #pragma unroll
     for (int m = 0; m < kPairsPerLane; ++m) {
       const uint32_t j = (uint32_t)m * 256u + threadIdx.x;
-      s_pairs[j] = t0 + j < n ? sp[t0 + j] : make_uint2(kNoRow, 0u);
+      if ((uint32_t)m < ppl) s_pairs[j] = t0 + j < n ? sp[t0 + j] : make_uint2(kNoRow, 0u);
     }
   }
   __syncthreads();
@@ -315,13 +317,15 @@ hipError_t launch_apply_grad_adagrad(const TableView& t, const UpdateWorkspace& 
   uint32_t group_log2 = 0;
   while ((4u << group_log2) < t.dim) ++group_log2;
   const uint32_t gpb = 256u >> group_log2;
-  const uint64_t n_tiles = (n + kReduceTile - 1) / kReduceTile;
+  uint32_t ppl = kPairsPerLane;  // fewer pairs per lane for small batches: at least ~2048 tiles
+  while (ppl > 1 && (n + 256ull * ppl - 1) / (256ull * ppl) < 2048) ppl >>= 1;
+  const uint64_t n_tiles = (n + 256ull * ppl - 1) / (256ull * ppl);
   const dim3 block(256), grid((unsigned)n_tiles);
   const size_t lds_reduce = 2 * gpb * (t.dim / 4) * sizeof(float4) + 2 * gpb * sizeof(uint32_t);
   const size_t lds_combine = gpb * (t.dim / 4) * sizeof(float4);
 #define MONO_SEG_REDUCE(E, GLOG)                                                                                  \
   MONO_LAUNCH_SMEM(prof, K_SEG_REDUCE, stream, (seg_reduce_kernel<E, GLOG>), grid, block, lds_reduce, t, ws.pair_a, \
-                   ws.pair_b, n, d_grad, lr, eps, ws.part, ws.part_row)
+                   ws.pair_b, n, d_grad, lr, eps, ws.part, ws.part_row, ppl)
 #define MONO_SEG_REDUCE_ALL(E)                   \
   switch (group_log2) {                          \
     case 0: MONO_SEG_REDUCE(E, 0); break;        \
