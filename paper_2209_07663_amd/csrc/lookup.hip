@@ -290,11 +290,18 @@ done:
 }
 
 template <typename E>
-__device__ inline void store_init(E* rows, uint64_t idx, float v);
+__device__ inline void store_init4(E* rows, uint64_t idx, float4 v);
 template <>
-__device__ inline void store_init<float>(float* rows, uint64_t idx, float v) { rows[idx] = v; }
+__device__ inline void store_init4<float>(float* rows, uint64_t idx, float4 v) {
+  *reinterpret_cast<float4*>(rows + idx) = v;
+}
 template <>
-__device__ inline void store_init<uint16_t>(uint16_t* rows, uint64_t idx, float v) { rows[idx] = f32_to_bf16(v); }
+__device__ inline void store_init4<uint16_t>(uint16_t* rows, uint64_t idx, float4 v) {
+  uint2 u;
+  u.x = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
+  u.y = (uint32_t)f32_to_bf16(v.z) | ((uint32_t)f32_to_bf16(v.w) << 16);
+  *reinterpret_cast<uint2*>(rows + idx) = u;
+}
 
 // Dense over the elected occurrences: winner number w of the call takes free_rows[free_n - 1 - w].
 template <typename E>
@@ -337,16 +344,24 @@ __global__ __launch_bounds__(256) void insert_kernel(TableView t, const int64_t*
       rows_out[e.x] = row == kNoRow ? kRowAbsent : (int32_t)row;
       if (row != kNoRow) cuckoo_insert(t, k, make_meta(row, step));
     }
-    // the wave initialises its new rows together: coalesced stores, one mixer call per lane
-    uint64_t imask = __ballot(valid && row != kNoRow);
-    while (imask) {
-      const int l = __ffsll((unsigned long long)imask) - 1;
-      imask &= imask - 1;
-      const uint64_t kk = __shfl(k, l);
-      const uint32_t rr = __shfl(row, l);
-      const uint64_t base_h = mix64(kk ^ t.s_init);
-      for (uint32_t j = lane; j < t.dim; j += 64) store_init<E>(rows, (uint64_t)rr * t.dim + j, init_value(base_h, j));
-      if (lane == 0) t.acc[rr] = 0.0f;
+    // the wave initialises its new rows together: a group of dim/4 lanes per row, four elements per
+    // lane, 64/group rows at a time, stored as whole 16-byte (fp32) or 8-byte (bf16) pieces
+    uint32_t glog = 0;
+    while ((4u << glog) < t.dim) ++glog;
+    const uint32_t group = 1u << glog, per_round = 64u >> glog, l = lane & (group - 1u), gi = lane >> glog;
+    const int ok = valid && row != kNoRow;
+    if (__ballot(ok) == 0) continue;  // wave-uniform
+    for (uint32_t q = 0; q < group; ++q) {
+      const int src = (int)(q * per_round + gi);
+      const uint64_t kk = __shfl(k, src);
+      const uint32_t rr = __shfl(row, src);
+      if (__shfl(ok, src) && l * 4 < t.dim) {
+        const uint64_t base_h = mix64(kk ^ t.s_init);
+        const float4 v = make_float4(init_value(base_h, l * 4), init_value(base_h, l * 4 + 1),
+                                     init_value(base_h, l * 4 + 2), init_value(base_h, l * 4 + 3));
+        store_init4<E>(rows, (uint64_t)rr * t.dim + l * 4, v);
+        if (l == 0) t.acc[rr] = 0.0f;
+      }
     }
   }
 }
