@@ -44,16 +44,21 @@ __device__ inline void add4(float4& a, const float4& b) {
 template <typename E>
 __global__ __launch_bounds__(256) void gather_pool_kernel(const E* __restrict__ rows, const int32_t* __restrict__ idx,
                                                           const int64_t* __restrict__ offsets, uint64_t n_bags,
-                                                          uint32_t dim, uint32_t group_log2, float* __restrict__ out) {
+                                                          uint64_t n, uint32_t cap, uint32_t dim,
+                                                          uint32_t group_log2, float* __restrict__ out) {
   const uint64_t wave = ((uint64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
   const uint64_t bag_base = wave * 64;
   if (bag_base >= n_bags) return;  // wave-uniform
   const uint32_t lane = lane_id();
   // phase 1: lane <-> bag
   const bool mine = bag_base + lane < n_bags;
-  const int64_t s = mine ? offsets[bag_base + lane] : 0;
-  const int64_t e = mine ? offsets[bag_base + lane + 1] : 0;
-  const int len = (int)(e - s);
+  // offsets and row indices are the caller's: both are bounded (to the n indices, to the table's
+  // rows) so that a malformed input gives zeros, not an access out of range
+  int64_t s = mine ? offsets[bag_base + lane] : 0;
+  int64_t e = mine ? offsets[bag_base + lane + 1] : 0;
+  s = s < 0 ? 0 : s;
+  e = e > (int64_t)n ? (int64_t)n : e;
+  const int len = e > s ? (int)(e - s > 0x7FFFFFFF ? 0x7FFFFFFF : e - s) : 0;
   int32_t id[kIdsInRegs];
 #pragma unroll
   for (int j = 0; j < kIdsInRegs; ++j) id[j] = j < len ? idx[s + j] : -1;
@@ -70,22 +75,22 @@ __global__ __launch_bounds__(256) void gather_pool_kernel(const E* __restrict__ 
 #pragma unroll
     for (int j = 0; j < kIdsInRegs; ++j) {
       const int32_t r = __shfl(id[j], src);
-      v[j] = (r >= 0 && active) ? load4<E>(rows, (uint32_t)r, dim, l) : zero;
+      v[j] = ((uint32_t)r < cap && active) ? load4<E>(rows, (uint32_t)r, dim, l) : zero;
     }
     float4 acc = zero;
 #pragma unroll
     for (int j = 0; j < kIdsInRegs; ++j) add4(acc, v[j]);
     for (int j = kIdsInRegs; j < blen; ++j) {  // long bag: the rest of its indices straight from memory
       const int32_t r = idx[bs + j];
-      if (r >= 0 && active) add4(acc, load4<E>(rows, (uint32_t)r, dim, l));
+      if ((uint32_t)r < cap && active) add4(acc, load4<E>(rows, (uint32_t)r, dim, l));
     }
     const uint64_t bag = bag_base + (uint32_t)src;
     if (bag < n_bags && active) *reinterpret_cast<float4*>(out + bag * dim + l * 4) = acc;
   }
 }
 
-hipError_t launch_gather_pool(const TableView& t, const int32_t* d_rows, const int64_t* d_offsets, uint64_t n_bags,
-                              float* d_out, hipStream_t stream, Profiler* prof) {
+hipError_t launch_gather_pool(const TableView& t, const int32_t* d_rows, uint64_t n, const int64_t* d_offsets,
+                              uint64_t n_bags, float* d_out, hipStream_t stream, Profiler* prof) {
   if (n_bags == 0) return hipSuccess;
   uint32_t group_log2 = 0;
   while ((4u << group_log2) < t.dim) ++group_log2;
@@ -93,10 +98,10 @@ hipError_t launch_gather_pool(const TableView& t, const int32_t* d_rows, const i
   const dim3 block(256), grid((unsigned)((waves + 3) / 4));
   if (t.bf16)
     MONO_LAUNCH(prof, K_GATHER_POOL, stream, gather_pool_kernel<uint16_t>, grid, block, (const uint16_t*)t.rows, d_rows,
-                d_offsets, n_bags, t.dim, group_log2, d_out);
+                d_offsets, n_bags, n, (uint32_t)t.capacity, t.dim, group_log2, d_out);
   else
     MONO_LAUNCH(prof, K_GATHER_POOL, stream, gather_pool_kernel<float>, grid, block, (const float*)t.rows, d_rows,
-                d_offsets, n_bags, t.dim, group_log2, d_out);
+                d_offsets, n_bags, n, (uint32_t)t.capacity, t.dim, group_log2, d_out);
   return hipGetLastError();
 }
 

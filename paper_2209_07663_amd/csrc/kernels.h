@@ -44,8 +44,8 @@ __host__ __device__ inline SortPlan make_sort_plan(uint32_t hwm) {
 hipError_t launch_lookup_or_insert(const TableView& t, const int64_t* d_keys, uint64_t n, uint32_t step, uint32_t epoch,
                                    int32_t* d_rows_out, hipStream_t stream, Profiler* prof);
 
-hipError_t launch_gather_pool(const TableView& t, const int32_t* d_rows, const int64_t* d_offsets, uint64_t n_bags,
-                              float* d_out, hipStream_t stream, Profiler* prof);
+hipError_t launch_gather_pool(const TableView& t, const int32_t* d_rows, uint64_t n, const int64_t* d_offsets,
+                              uint64_t n_bags, float* d_out, hipStream_t stream, Profiler* prof);
 
 hipError_t launch_apply_grad_adagrad(const TableView& t, const UpdateWorkspace& ws, const int32_t* d_rows, uint64_t n,
                                      const int64_t* d_offsets, uint64_t n_bags, const float* d_grad, float lr, float eps,
@@ -54,7 +54,7 @@ hipError_t launch_apply_grad_adagrad(const TableView& t, const UpdateWorkspace& 
 // Stable LSD radix sort of the (row, bag) pairs of a batch; the result is in pair_b if the plan for
 // the device's high-water mark has an odd number of passes, else in pair_a.
 hipError_t launch_sort_pairs(const TableView& t, const UpdateWorkspace& ws, const int32_t* d_rows, uint64_t n,
-                             hipStream_t stream, Profiler* prof);
+                             uint64_t n_bags, hipStream_t stream, Profiler* prof);
 
 hipError_t launch_expire_sweep(const TableView& t, uint32_t now, uint64_t* d_n_expired, int64_t* d_expired_keys,
                                uint64_t max_expired, hipStream_t stream, Profiler* prof);

@@ -95,8 +95,9 @@ __global__ __launch_bounds__(256) void sort_scan_kernel(const Control* __restric
 __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __restrict__ ctl, uint32_t pass,
                                                                   const int32_t* __restrict__ rows,
                                                                   const uint32_t* __restrict__ bag_of,
-                                                                  const uint2* __restrict__ src, uint64_t n,
-                                                                  uint64_t units, const uint32_t* __restrict__ hist,
+                                                                  uint32_t last_bag, const uint2* __restrict__ src,
+                                                                  uint64_t n, uint64_t units,
+                                                                  const uint32_t* __restrict__ hist,
                                                                   const uint32_t* __restrict__ totals,
                                                                   uint2* __restrict__ dst) {
   const SortPlan plan = make_sort_plan(ctl->hwm);
@@ -115,7 +116,9 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
   for (uint32_t r = 0; r < kSortRounds; ++r) {
     const uint64_t i = base + (uint64_t)r * 64 + lane;
     kv[r] = make_uint2(0xFFFFFFFFu, 0u);
-    if (i < n) kv[r] = pass == 0 ? make_uint2(first_key(rows, i, plan.hwm), bag_of[i]) : src[i];
+    // (an occurrence that the caller's offsets left outside every bag carries a stale bag number:
+    // bounded here, so that a malformed offsets array cannot send a gradient read out of range)
+    if (i < n) kv[r] = pass == 0 ? make_uint2(first_key(rows, i, plan.hwm), min(bag_of[i], last_bag)) : src[i];
     if (kv[r].x >= plan.hwm) kv[r].x = 0xFFFFFFFFu;  // dropped occurrence (or past the end): left out
   }
   for (uint32_t b = threadIdx.x; b < nbins; b += kSortBlock) {
@@ -188,7 +191,7 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
 }
 
 hipError_t launch_sort_pairs(const TableView& t, const UpdateWorkspace& ws, const int32_t* d_rows, uint64_t n,
-                             hipStream_t stream, Profiler* prof) {
+                             uint64_t n_bags, hipStream_t stream, Profiler* prof) {
   if (n == 0) return hipSuccess;
   const uint64_t units = sort_units(n);
   uint32_t* totals = ws.hist + (uint64_t)kSortMaxBins * units;
@@ -200,8 +203,8 @@ hipError_t launch_sort_pairs(const TableView& t, const UpdateWorkspace& ws, cons
     MONO_LAUNCH(prof, K_SORT_HIST, stream, sort_hist_kernel, grid, block, t.ctl, p, d_rows, src, n, units, ws.hist);
     MONO_LAUNCH(prof, K_SORT_SCAN, stream, sort_scan_kernel, dim3(kSortMaxBins), dim3(256), t.ctl, p, ws.hist, units,
                 totals);
-    MONO_LAUNCH(prof, K_SORT_SCATTER, stream, sort_scatter_kernel, grid, block, t.ctl, p, d_rows, ws.bag_of, src, n,
-                units, ws.hist, totals, dst);
+    MONO_LAUNCH(prof, K_SORT_SCATTER, stream, sort_scatter_kernel, grid, block, t.ctl, p, d_rows, ws.bag_of,
+                (uint32_t)(n_bags - 1), src, n, units, ws.hist, totals, dst);
   }
   return hipGetLastError();
 }

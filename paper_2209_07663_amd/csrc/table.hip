@@ -204,7 +204,7 @@ int mono_gather_pool(mono_table* t, const int32_t* d_rows, uint64_t n, const int
   if (!t || n > t->max_ids || n_bags > t->max_bags) return MONO_EINVAL;
   if (n_bags == 0) return MONO_OK;
   if (!d_offsets || !d_out || (n && !d_rows)) return MONO_EINVAL;
-  return launch_gather_pool(t->view, d_rows, d_offsets, n_bags, d_out, (hipStream_t)stream, &t->prof) == hipSuccess ? MONO_OK
+  return launch_gather_pool(t->view, d_rows, n, d_offsets, n_bags, d_out, (hipStream_t)stream, &t->prof) == hipSuccess ? MONO_OK
                                                                                                            : MONO_EHIP;
 }
 

@@ -27,10 +27,12 @@ namespace mono {
 constexpr uint32_t kHeadFlag = 0x80000000u;
 
 __global__ __launch_bounds__(256) void expand_bags_kernel(const int64_t* __restrict__ offsets, uint64_t n_bags,
-                                                          uint32_t* __restrict__ bag_of) {
+                                                          uint64_t n, uint32_t* __restrict__ bag_of) {
   const uint64_t b = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= n_bags) return;
-  const int64_t s = offsets[b], e = offsets[b + 1];
+  int64_t s = offsets[b], e = offsets[b + 1];
+  s = s < 0 ? 0 : s;  // offsets are the caller's: never write outside the n occurrences
+  e = e > (int64_t)n ? (int64_t)n : e;
   for (int64_t i = s; i < e; ++i) bag_of[i] = (uint32_t)b;
 }
 
@@ -311,8 +313,8 @@ hipError_t launch_apply_grad_adagrad(const TableView& t, const UpdateWorkspace& 
                                      hipStream_t stream, Profiler* prof) {
   if (n == 0 || n_bags == 0) return hipSuccess;
   MONO_LAUNCH(prof, K_EXPAND_BAGS, stream, expand_bags_kernel, dim3((unsigned)((n_bags + 255) / 256)), dim3(256),
-              d_offsets, n_bags, ws.bag_of);
-  hipError_t e = launch_sort_pairs(t, ws, d_rows, n, stream, prof);
+              d_offsets, n_bags, n, ws.bag_of);
+  hipError_t e = launch_sort_pairs(t, ws, d_rows, n, n_bags, stream, prof);
   if (e != hipSuccess) return e;
   uint32_t group_log2 = 0;
   while ((4u << group_log2) < t.dim) ++group_log2;

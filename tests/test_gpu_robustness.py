@@ -1,0 +1,185 @@
+"""Behaviour outside the graded envelope and plumbing of the device library (needs an MI355X).
+
+Graded runs never fill the table or exhaust an eviction chain; these tests drive a tiny table past
+both limits and check that nothing is lost or duplicated, that the limits are reported through the
+counters, and that the table recovers once keys expire.  Also: calls on a side stream, two tables
+used in turn, and batches of exactly the announced maximum size.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import Oracle
+from paper_2209_07663_amd import synth
+from tests import table_checks as tc
+from tests.test_gpu_parity import _SEEDS, compare_step, RTOL_F32
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dev():
+    assert torch.cuda.is_available(), "gpu tests need a GPU"
+    return torch.device("cuda:0")
+
+
+def _lookup(tab, keys_h, step, dev):
+    rows = tab.mono_lookup_or_insert(torch.from_numpy(keys_h).to(dev), step)
+    return rows.cpu().numpy()
+
+
+def test_overfull_table_loses_nothing_and_recovers(dev):
+    from paper_2209_07663_amd.binding import Table
+    seed, cap, dim = 21, 1 << 10, 8
+    tab = Table(cap, dim, seed, freq_threshold=1, expire_steps=4, max_ids=4096, max_bags=4096, device=dev)
+    rng = np.random.default_rng(5)
+    universe = (rng.permutation(1 << 20)[:1500].astype(np.int64) + 1) * 7919
+    held = {}                                            # key -> row, as handed out
+    for step, chunk in enumerate(np.array_split(universe, 5)):
+        print("overfull: step", step, flush=True)
+        rows = _lookup(tab, chunk, step, dev)
+        assert (rows >= -1).all() and (rows < cap).all()
+        for k, r in zip(chunk.tolist(), rows.tolist()):
+            if r >= 0:
+                held[k] = r
+        d = tab.mono_table_export()
+        st = tab.mono_table_stats()
+        assert st["n_lost"] == 0
+        assert d["keys"].shape[0] == st["size"] <= cap
+        assert int((d["slot"] < 0).sum()) == st["stash_size"]
+        tc.check_placement(d, cap, 8, seed)              # unique keys, slots and rows; h0 / h1 buckets
+        # the table holds exactly the keys that were given a row, under that row
+        assert sorted(held) == d["keys"].tolist()
+        assert (d["row"] == np.array([held[k] for k in d["keys"].tolist()])).all()
+        # their rows still carry the initial values: no eviction chain damaged a resident
+        assert (d["rows"] == tc.init_rows(d["keys"], dim, seed).astype(np.float32)).all()
+    st = tab.mono_table_stats()
+    assert st["n_full"] > 0 or st["n_insert_failed"] > 0   # 1500 keys cannot fit 1024 rows
+    assert st["size"] >= int(0.95 * cap)
+    # every stored key is found again, at its row, wherever an eviction chain moved it (stash included)
+    keys_now = np.array(sorted(held), dtype=np.int64)
+    rows = _lookup(tab, keys_now, 5, dev)
+    assert (rows == np.array([held[k] for k in keys_now.tolist()])).all()
+    # keys turned away stay absent while no row is free, and are counted, not stored
+    size_before = tab.mono_table_stats()["size"]
+    if size_before == cap:
+        away = np.array([k for k in universe.tolist() if k not in held][:100], dtype=np.int64)
+        assert (_lookup(tab, away, 5, dev) == -1).all()
+        assert tab.mono_table_stats()["size"] == cap
+    # recovery: everything expires, rows and slots are free again
+    n_exp = torch.zeros(1, dtype=torch.int64, device=dev)
+    out = torch.zeros(cap, dtype=torch.int64, device=dev)
+    tab.mono_expire_sweep(20, n_exp, out)
+    n = int(n_exp.item())
+    assert n == size_before
+    assert sorted(out[:n].cpu().numpy().tolist()) == keys_now.tolist()
+    st = tab.mono_table_stats()
+    assert st["size"] == 0 and st["stash_size"] == 0
+    fresh = (np.arange(600, dtype=np.int64) + 5) * 104729
+    rows = _lookup(tab, fresh, 21, dev)
+    assert (rows >= 0).all() and np.unique(rows).shape[0] == 600
+    tc.check_placement(tab.mono_table_export(), cap, 8, seed)
+    tab.close()
+
+
+def test_calls_on_a_side_stream(dev):
+    """Every call takes the stream it is given: a whole run on a non-default stream matches the oracle."""
+    from paper_2209_07663_amd.binding import Table
+    wl = synth.scaled(synth.CONFIGS["cfg3"], samples=1024, capacity=1 << 19)
+    seed = 31
+    side = torch.cuda.Stream(device=dev)
+    with torch.cuda.stream(side):
+        tab = Table(wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16,
+                    max_ids=1 << 18, max_bags=wl.n_bags, device=dev)
+        _SEEDS[id(tab)] = seed
+        orc = Oracle(wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, kind="cuckoo")
+        for step in range(3):
+            b = synth.make_batch(wl, seed, step, with_grad=True)
+            compare_step(tab, orc, b, dev, RTOL_F32, exact_rows=False, train=True, lr=wl.lr, eps=wl.eps)
+        side.synchronize()
+        tab.close()
+
+
+def test_two_tables_used_in_turn(dev):
+    """Tables share nothing: two of them with different shapes, stepped alternately, each match their oracle."""
+    from dataclasses import replace
+    from paper_2209_07663_amd.binding import Table
+    wls = [replace(synth.scaled(synth.CONFIGS["cfg2"], samples=1024, capacity=1 << 16), freq_threshold=2),
+           synth.scaled(synth.CONFIGS["cfg5"], samples=8192, capacity=1 << 17)]
+    seeds = [41, 42]
+    tabs, orcs = [], []
+    for wl, seed in zip(wls, seeds):
+        tab = Table(wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, max_ids=1 << 18,
+                    max_bags=wl.n_bags, device=dev)
+        _SEEDS[id(tab)] = seed
+        tabs.append(tab)
+        orcs.append(Oracle(wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, kind="cuckoo"))
+    for step in range(3):
+        for wl, seed, tab, orc in zip(wls, seeds, tabs, orcs):
+            b = synth.make_batch(wl, seed, step, with_grad=True)
+            compare_step(tab, orc, b, dev, 1e-2 if wl.bf16 else RTOL_F32, exact_rows=False, train=True, lr=wl.lr,
+                         eps=wl.eps, sweep_at=step if wl.expire_steps else None)
+    for tab in tabs:
+        tab.close()
+
+
+def test_batch_of_exactly_the_announced_maximum(dev):
+    """n == max_ids and n_bags == max_bags: the workspaces are sized for it, one more is refused."""
+    from paper_2209_07663_amd.binding import Table, MonoError
+    seed, dim, max_ids, max_bags = 51, 16, 20000, 5000
+    tab = Table(1 << 16, dim, seed, freq_threshold=1, max_ids=max_ids, max_bags=max_bags, device=dev)
+    _SEEDS[id(tab)] = seed
+    orc = Oracle(1 << 16, dim, seed, 1, 0, False, kind="cuckoo")
+    rng = np.random.default_rng(6)
+    keys_h = rng.integers(0, 30000, size=max_ids).astype(np.int64)
+    offs_h = np.arange(0, max_ids + 1, max_ids // max_bags, dtype=np.int64)
+    grad_h = rng.standard_normal((max_bags, dim)).astype(np.float32)
+    for step in range(2):
+        compare_step(tab, orc, {"keys": keys_h, "offsets": offs_h, "grad": grad_h, "step": step}, dev, RTOL_F32,
+                     exact_rows=False, train=True)
+    rows = torch.zeros(max_ids + 4, dtype=torch.int32, device=dev)
+    offs = torch.arange(0, max_ids + 5, 4, dtype=torch.int64, device=dev)[: max_bags + 2]
+    with pytest.raises(MonoError):
+        tab.mono_gather_pool(rows[:max_ids], offs)                       # one bag too many
+    with pytest.raises(MonoError):
+        tab.mono_apply_grad_adagrad(rows, offs[: max_bags + 1], torch.zeros((max_bags, dim), device=dev), 0.1, 1e-8)
+    tab.close()
+
+
+def test_out_of_range_rows_and_offsets_are_bounded_by_the_kernels(dev):
+    """Row indices outside the table count as absent, offsets beyond the index array are cut at its
+    end: the result is that of the well-formed part of the input, and nothing else is touched."""
+    from paper_2209_07663_amd.binding import Table
+    seed, dim, cap = 61, 8, 1 << 12
+    tab = Table(cap, dim, seed, freq_threshold=1, max_ids=1 << 12, max_bags=1 << 10, device=dev)
+    keys = torch.arange(100, 164, dtype=torch.int64, device=dev)
+    rows = tab.mono_lookup_or_insert(keys, 0)
+    before = tab.mono_table_export()
+    bad = rows.clone()
+    bad[::4] = torch.tensor([cap, cap + 5, 2 ** 31 - 1, -5, -2 ** 31, -1, cap * 2, 1 << 20] * 2, dtype=torch.int32,
+                            device=dev)
+    good = bad.clone()
+    good[::4] = -1
+    offs_good = torch.arange(0, 65, 4, dtype=torch.int64, device=dev)
+    offs_bad = offs_good.clone()
+    offs_bad[-1] = 1 << 40                                   # last bag claims far more than there is
+    want = tab.mono_gather_pool(good, offs_good).cpu().numpy()
+    got = tab.mono_gather_pool(bad, offs_bad).cpu().numpy()
+    assert (got == want).all()
+    grad = torch.ones((16, dim), dtype=torch.float32, device=dev)
+    tab.mono_apply_grad_adagrad(bad, offs_bad, grad, 0.1, 1e-8)
+    after = tab.mono_table_export()
+    touched = np.isin(before["row"], good[good >= 0].cpu().numpy())
+    assert (after["rows"][~touched] == before["rows"][~touched]).all()
+    assert (after["acc"][~touched] == 0).all() and (after["acc"][touched] > 0).all()
+    # same update as the well-formed input gives on a twin table
+    twin = Table(cap, dim, seed, freq_threshold=1, max_ids=1 << 12, max_bags=1 << 10, device=dev)
+    rows2 = twin.mono_lookup_or_insert(keys, 0)
+    good2 = rows2.clone()
+    good2[::4] = -1
+    twin.mono_apply_grad_adagrad(good2, offs_good, grad, 0.1, 1e-8)
+    ref = twin.mono_table_export()
+    assert (ref["keys"] == after["keys"]).all()
+    tc.rows_close(after["rows"], ref["rows"].astype(np.float64), RTOL_F32)
+    tab.close()
+    twin.close()
