@@ -29,6 +29,18 @@
 //      w_j -= lr * g_j / (sqrt(acc) + eps);
 //   9. sweep(now) erases every key with now - last_seen >= expire_steps (expire_steps > 0).
 //
+// Three maintenance operations around that path (same two models, same interface):
+//  10. touched keys (the paper's incremental parameter synchronisation): the set of keys whose
+//      embeddings were trained since the last synchronisation; taking it clears it; a key that
+//      expires leaves it;
+//  11. snapshot / restore (the paper's fault tolerance): the dump plus the counter words are the
+//      snapshot; restore places given (key, row, accumulator, last-seen) records into a table
+//      and writes counter words back;
+//  12. rehash / grow (section 2.1: rehash when an insertion runs into a cycle): every stored key
+//      is re-inserted under the hash functions of a new generation, in a table of the same or a
+//      larger power-of-two capacity; when the number of counters grows by 2^k, a counter's value
+//      goes to all 2^k counters that its keys can now map to (never an under-count).
+//
 // Parity unpinned: what happens when an eviction chain exceeds its bound (which key ends up in
 // the overflow stash depends on insertion order); graded runs must have zero such failures.
 //
@@ -40,6 +52,7 @@
 #include <cstring>
 #include <map>
 #include <memory>
+#include <set>
 #include <vector>
 
 namespace {
@@ -61,6 +74,11 @@ uint64_t mix64(uint64_t z) {
 
 // salt i is the (i+1)-th output of the SplitMix64 generator started at `seed`.
 uint64_t salt(uint64_t seed, int i) { return mix64(seed + (uint64_t)(i + 1) * 0x9E3779B97F4A7C15ull); }
+// The placement hashes h0 / h1 of rehash generation g use the salts of seed + g * (an odd
+// constant); generation 0 is the table as created.  Counter and initial-value hashes never change.
+uint64_t placement_seed(uint64_t seed, uint32_t generation) {
+  return seed + (uint64_t)generation * 0xD1B54A32D192ED03ull;
+}
 
 // top `lg` bits of h (0 when lg == 0)
 uint64_t top_bits(uint64_t h, int lg) { return lg == 0 ? 0 : h >> (64 - lg); }
@@ -164,13 +182,35 @@ class Model {
   virtual void sweep(uint32_t now, std::vector<uint64_t>* erased) = 0;
   virtual void dump(std::vector<Exported>* out) const = 0;  // sorted by key
   virtual uint32_t filter_word(uint64_t index) const = 0;
+  // -- maintenance ------------------------------------------------------------------------------
+  // keys trained since the last call, ascending; the set is cleared
+  void take_touched(std::vector<uint64_t>* out) {
+    out->assign(touched_.begin(), touched_.end());
+    touched_.clear();
+  }
+  // place a record; false (and nothing changes) if the key is already stored or is the reserved key
+  virtual bool import_entry(uint64_t key, const Entry& e) = 0;
+  virtual void set_filter_word(uint64_t index, uint32_t word) = 0;
+  // re-insert everything under generation `generation` in a table of `new_capacity` >= capacity
+  virtual void rehash(uint64_t new_capacity, uint32_t generation) = 0;
   virtual uint64_t insert_failures() const { return 0; }
   virtual uint64_t max_chain() const { return 0; }
   const Params& params() const { return p_; }
   uint64_t filter_index(uint64_t key) const { return top_bits(mix64(key ^ p_.s_filter), p_.lg_filter); }
 
  protected:
+  // new table geometry and placement salts; returns log2 of the growth factor of the counter array
+  int regrow_params(uint64_t new_capacity, uint32_t generation) {
+    int k = log2_exact(new_capacity / p_.capacity);
+    p_.capacity = new_capacity;
+    p_.n_filter <<= k;
+    p_.lg_filter += k;
+    p_.s_h0 = salt(placement_seed(p_.seed, generation), 0);
+    p_.s_h1 = salt(placement_seed(p_.seed, generation), 1);
+    return k;
+  }
   Params p_;
+  std::set<uint64_t> touched_;
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -234,7 +274,10 @@ class BruteForceModel final : public Model {
         gk.resize(p_.dim, 0.0);
         for (uint32_t j = 0; j < p_.dim; ++j) gk[j] += (double)grad[b * p_.dim + j];
       }
-    for (auto& kv : g) adagrad_entry(p_, kv.second, (double)lr, (double)eps, &table_[kv.first]);
+    for (auto& kv : g) {
+      adagrad_entry(p_, kv.second, (double)lr, (double)eps, &table_[kv.first]);
+      touched_.insert(kv.first);
+    }
   }
 
   void sweep(uint32_t now, std::vector<uint64_t>* erased) override {
@@ -243,6 +286,7 @@ class BruteForceModel final : public Model {
     for (auto it = table_.begin(); it != table_.end();) {
       if (now - it->second.last_seen >= p_.expire_steps) {
         erased->push_back(it->first);
+        touched_.erase(it->first);
         it = table_.erase(it);
       } else {
         ++it;
@@ -258,6 +302,20 @@ class BruteForceModel final : public Model {
   uint32_t filter_word(uint64_t index) const override {
     auto it = filter_.find(index);
     return it == filter_.end() ? 0u : it->second;
+  }
+
+  bool import_entry(uint64_t key, const Entry& e) override {
+    if (key == kEmptyKey || table_.count(key)) return false;
+    table_[key] = e;
+    return true;
+  }
+  void set_filter_word(uint64_t index, uint32_t word) override { filter_[index] = word; }
+  void rehash(uint64_t new_capacity, uint32_t generation) override {
+    int k = regrow_params(new_capacity, generation);  // the map itself has no positions to redo
+    std::map<uint64_t, uint32_t> grown;
+    for (auto& iw : filter_)
+      for (uint64_t c = 0; c < (1ull << k); ++c) grown[(iw.first << k) + c] = iw.second;
+    filter_.swap(grown);
   }
 
  private:
@@ -315,6 +373,7 @@ class CuckooModel final : public Model {
   int32_t alloc_entry() {
     if (!free_.empty()) { int32_t e = free_.back(); free_.pop_back(); return e; }
     pool_.emplace_back();
+    key_of_entry_.push_back(kEmptyKey);
     return (int32_t)pool_.size() - 1;
   }
 
@@ -364,6 +423,7 @@ class CuckooModel final : public Model {
       if (size_ >= p_.capacity) { ++insert_failures_; continue; }  // no row left
       int32_t e = alloc_entry();
       init_entry(p_, k, step, &pool_[e]);
+      key_of_entry_[e] = k;
       insert(k, e);
       ++size_;
     }
@@ -406,6 +466,7 @@ class CuckooModel final : public Model {
       }
     for (int32_t id : touched) {  // once per distinct key
       adagrad_entry(p_, gsum_[id], (double)lr, (double)eps, &pool_[id]);
+      touched_.insert(key_of_entry_[id]);
       gsum_[id].clear();
       gsum_[id].shrink_to_fit();
     }
@@ -418,6 +479,7 @@ class CuckooModel final : public Model {
       if (slot_key_[s] == kEmptyKey) continue;
       if (now - pool_[slot_entry_[s]].last_seen >= p_.expire_steps) {
         erased->push_back(slot_key_[s]);
+        touched_.erase(slot_key_[s]);
         free_.push_back(slot_entry_[s]);
         slot_key_[s] = kEmptyKey;
         slot_entry_[s] = -1;
@@ -427,6 +489,7 @@ class CuckooModel final : public Model {
     for (size_t i = 0; i < stash_.size();) {
       if (now - pool_[stash_[i].second].last_seen >= p_.expire_steps) {
         erased->push_back(stash_[i].first);
+        touched_.erase(stash_[i].first);
         free_.push_back(stash_[i].second);
         stash_.erase(stash_.begin() + (long)i);
         --size_;
@@ -446,6 +509,38 @@ class CuckooModel final : public Model {
   }
 
   uint32_t filter_word(uint64_t index) const override { return filter_[index]; }
+
+  bool import_entry(uint64_t key, const Entry& e) override {
+    if (key == kEmptyKey || find(key)) return false;
+    if (size_ >= p_.capacity) { ++insert_failures_; return false; }  // no row left
+    int32_t id = alloc_entry();
+    pool_[id] = e;
+    key_of_entry_[id] = key;
+    insert(key, id);
+    ++size_;
+    return true;
+  }
+  void set_filter_word(uint64_t index, uint32_t word) override { filter_[index] = word; }
+
+  // Every stored element is taken out and inserted again, slots in ascending order and then the
+  // stash, into empty sub-tables of the new size addressed by the new generation's h0 / h1.
+  void rehash(uint64_t new_capacity, uint32_t generation) override {
+    std::vector<std::pair<uint64_t, int32_t>> all;
+    for (uint64_t s = 0; s < p_.capacity; ++s)
+      if (slot_key_[s] != kEmptyKey) all.push_back({slot_key_[s], slot_entry_[s]});
+    for (auto& st : stash_) all.push_back(st);
+    stash_.clear();
+    int k = regrow_params(new_capacity, generation);
+    n_buckets_ = p_.capacity / 2 / bucket_;
+    lg_buckets_ = log2_exact(n_buckets_);
+    slot_key_.assign(p_.capacity, kEmptyKey);
+    slot_entry_.assign(p_.capacity, -1);
+    std::vector<uint32_t> grown(p_.n_filter);
+    for (uint64_t i = 0; i < p_.n_filter; ++i) grown[i] = filter_[i >> k];
+    filter_.swap(grown);
+    for (auto& ke : all) insert(ke.first, ke.second);
+  }
+
   uint64_t insert_failures() const override { return insert_failures_; }
   uint64_t max_chain() const override { return max_chain_; }
 
@@ -457,6 +552,7 @@ class CuckooModel final : public Model {
   std::vector<uint64_t> slot_key_;
   std::vector<int32_t> slot_entry_;
   std::vector<Entry> pool_;
+  std::vector<uint64_t> key_of_entry_;  // pool index -> key (for the touched-keys set)
   std::vector<int32_t> free_;
   std::vector<std::pair<uint64_t, int32_t>> stash_;
   std::vector<uint32_t> filter_;
@@ -468,6 +564,7 @@ struct Handle {
   std::unique_ptr<Model> m;
   std::vector<Exported> dump;
   std::vector<uint64_t> erased;
+  std::vector<uint64_t> touched;
 };
 
 bool is_pow2(uint64_t v) { return v && !(v & (v - 1)); }
@@ -492,8 +589,8 @@ void* orc_create(int kind, uint64_t capacity, uint32_t dim, uint64_t seed, uint3
   p.bf16 = bf16 != 0;
   p.n_filter = n_filter;
   p.lg_filter = log2_exact(n_filter);
-  p.s_h0 = salt(seed, 0);
-  p.s_h1 = salt(seed, 1);
+  p.s_h0 = salt(placement_seed(seed, 0), 0);
+  p.s_h1 = salt(placement_seed(seed, 0), 1);
   p.s_filter = salt(seed, 2);
   p.s_init = salt(seed, 3);
   auto* h = new Handle;
@@ -566,6 +663,55 @@ uint64_t orc_filter_index(void* hv, int64_t key) { return ((Handle*)hv)->m->filt
 
 uint64_t orc_insert_failures(void* hv) { return ((Handle*)hv)->m->insert_failures(); }
 uint64_t orc_max_chain(void* hv) { return ((Handle*)hv)->m->max_chain(); }
+
+// -- maintenance operations -------------------------------------------------------------------
+
+// keys trained since the last call: returns how many, then orc_touched_keys copies them (ascending)
+uint64_t orc_take_touched(void* hv) {
+  Handle* h = (Handle*)hv;
+  h->m->take_touched(&h->touched);
+  return h->touched.size();
+}
+void orc_touched_keys(void* hv, int64_t* out) {
+  Handle* h = (Handle*)hv;
+  for (size_t i = 0; i < h->touched.size(); ++i) out[i] = (int64_t)h->touched[i];
+}
+
+// restore: records are placed in the order given; rows[n * dim] are rounded to the storage type.
+// Returns the number of records NOT placed (key already stored, reserved key, or no row left).
+uint64_t orc_import(void* hv, const int64_t* keys, const float* rows, const float* acc,
+                    const uint32_t* last_seen, uint64_t n) {
+  Handle* h = (Handle*)hv;
+  const Params& p = h->m->params();
+  uint64_t rejected = 0;
+  for (uint64_t i = 0; i < n; ++i) {
+    Entry e;
+    e.w.resize(p.dim);
+    for (uint32_t j = 0; j < p.dim; ++j) e.w[j] = p.bf16 ? bf16_round(rows[i * p.dim + j]) : rows[i * p.dim + j];
+    e.acc = acc[i];
+    e.last_seen = last_seen[i];
+    if (!h->m->import_entry((uint64_t)keys[i], e)) ++rejected;
+  }
+  return rejected;
+}
+void orc_filter_write(void* hv, uint64_t first, uint64_t count, const uint32_t* words) {
+  Handle* h = (Handle*)hv;
+  for (uint64_t i = 0; i < count; ++i) h->m->set_filter_word(first + i, words[i]);
+}
+
+// rehash / grow: new_capacity a power of two >= the current one; 0 on success, -1 on a bad argument
+int orc_rehash(void* hv, uint64_t new_capacity, uint32_t generation) {
+  Handle* h = (Handle*)hv;
+  uint64_t cap = h->m->params().capacity;
+  if (!is_pow2(new_capacity) || new_capacity < cap || !is_pow2(cap)) return -1;
+  h->m->rehash(new_capacity, generation);
+  return 0;
+}
+uint64_t orc_capacity(void* hv) { return ((Handle*)hv)->m->params().capacity; }
+uint64_t orc_n_filter(void* hv) { return ((Handle*)hv)->m->params().n_filter; }
+uint64_t orc_placement_salt(uint64_t seed, uint32_t generation, int side) {
+  return salt(placement_seed(seed, generation), side);
+}
 
 // building blocks exposed so that tests can pin them separately
 uint64_t orc_mix64(uint64_t z) { return mix64(z); }

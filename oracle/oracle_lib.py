@@ -54,6 +54,20 @@ def oracle_lib():
         lib.orc_insert_failures.argtypes = [_vp]
         lib.orc_max_chain.restype = _u64
         lib.orc_max_chain.argtypes = [_vp]
+        lib.orc_take_touched.restype = _u64
+        lib.orc_take_touched.argtypes = [_vp]
+        lib.orc_touched_keys.argtypes = [_vp, _vp]
+        lib.orc_import.restype = _u64
+        lib.orc_import.argtypes = [_vp, _vp, _vp, _vp, _vp, _u64]
+        lib.orc_filter_write.argtypes = [_vp, _u64, _u64, _vp]
+        lib.orc_rehash.restype = ctypes.c_int
+        lib.orc_rehash.argtypes = [_vp, _u64, _u32]
+        lib.orc_capacity.restype = _u64
+        lib.orc_capacity.argtypes = [_vp]
+        lib.orc_n_filter.restype = _u64
+        lib.orc_n_filter.argtypes = [_vp]
+        lib.orc_placement_salt.restype = _u64
+        lib.orc_placement_salt.argtypes = [_u64, _u32, ctypes.c_int]
         lib.orc_mix64.restype = _u64
         lib.orc_mix64.argtypes = [_u64]
         lib.orc_salt.restype = _u64
@@ -139,6 +153,34 @@ class Oracle:
 
     def filter_index(self, key):
         return self.lib.orc_filter_index(self.h, int(key))
+
+    # -- maintenance operations --------------------------------------------------------------
+
+    def take_touched(self):
+        """Keys trained since the last call (ascending, as uint64 order); clears the set."""
+        n = self.lib.orc_take_touched(self.h)
+        out = np.empty(n, dtype=np.int64)
+        if n:
+            self.lib.orc_touched_keys(self.h, _ptr(out))
+        return out
+
+    def import_entries(self, keys, rows, acc, last_seen):
+        """Restore records in the order given; returns how many were not placed."""
+        keys = np.ascontiguousarray(keys, dtype=np.int64)
+        rows = np.ascontiguousarray(rows, dtype=np.float32).reshape(keys.shape[0], self.dim)
+        acc = np.ascontiguousarray(acc, dtype=np.float32)
+        last_seen = np.ascontiguousarray(last_seen, dtype=np.uint32)
+        return self.lib.orc_import(self.h, _ptr(keys), _ptr(rows), _ptr(acc), _ptr(last_seen), keys.shape[0])
+
+    def write_filter_words(self, words, first=0):
+        words = np.ascontiguousarray(words, dtype=np.uint32)
+        self.lib.orc_filter_write(self.h, first, words.shape[0], _ptr(words))
+
+    def rehash(self, new_capacity, generation):
+        if self.lib.orc_rehash(self.h, int(new_capacity), int(generation)) != 0:
+            raise ValueError("oracle: bad rehash parameters")
+        self.capacity = int(self.lib.orc_capacity(self.h))
+        self.n_filter = int(self.lib.orc_n_filter(self.h))
 
     @property
     def insert_failures(self):

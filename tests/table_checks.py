@@ -33,11 +33,20 @@ def top_bits(h, lg):
     return h >> U64(64 - lg)
 
 
-def bucket_of(side, keys, capacity, bucket, seed):
+PLACEMENT_STEP = U64(0xD1B54A32D192ED03)
+
+
+def placement_seed(seed, generation):
+    """Seed of the h0 / h1 salts after `generation` rehashes (generation 0: the table as created)."""
+    with np.errstate(over="ignore"):
+        return U64(seed) + U64(generation) * PLACEMENT_STEP
+
+
+def bucket_of(side, keys, capacity, bucket, seed, generation=0):
     n_buckets = capacity // 2 // bucket
     lg = int(n_buckets).bit_length() - 1
     keys = np.asarray(keys).astype(U64)
-    return top_bits(mix64(keys ^ salt(seed, side)), lg)
+    return top_bits(mix64(keys ^ salt(placement_seed(seed, generation), side)), lg)
 
 
 def filter_index(keys, n_filter, seed):
@@ -58,7 +67,7 @@ def init_rows(keys, dim, seed):
     return out
 
 
-def check_placement(dump, capacity, bucket, seed):
+def check_placement(dump, capacity, bucket, seed, generation=0):
     """I1 (placement) and I2 (no key twice, no slot twice) on a dump with global slot indices.
 
     Global slot = side * capacity/2 + bucket_index * bucket + lane; negative slots (stash) are
@@ -76,7 +85,7 @@ def check_placement(dump, capacity, bucket, seed):
     k = keys[placed]
     for sd in (0, 1):
         m = side == sd
-        want = bucket_of(sd, k[m], capacity, bucket, seed).astype(np.int64)
+        want = bucket_of(sd, k[m], capacity, bucket, seed, generation).astype(np.int64)
         assert (bidx[m] == want).all(), "a key sits outside its h%d bucket" % sd
     if "row" in dump:
         r = dump["row"]
