@@ -97,15 +97,15 @@ def algorithmic_bytes(kernel, s, wl):
     return 0
 
 
-def step_bytes(s, wl):
-    """Compulsory bytes of a whole step (forward + backward; sweep when the table expires keys)."""
+def step_bytes(s, wl, sweep_every):
+    """Compulsory bytes of a whole step (forward + backward; the sweep's share when the table expires keys)."""
     e = 2 if wl.bf16 else 4
     row = wl.dim * e
     n, nb = s["n"], s["n_bags"]
     fwd = (8 * n + 8 * (nb + 1) + 128 * (s["u_hit"] + s["u_miss"]) + 2 * SECTOR * s["u_miss"] + 4 * s["u_present"]
            + row * s["u_present"] + row * s["u_new"] + 4 * wl.dim * nb)
     bwd = 4 * wl.dim * nb + 2 * row * s["u_present"] + 8 * s["u_present"]
-    sweep = 8 * wl.capacity if wl.expire_steps else 0
+    sweep = 8 * wl.capacity / sweep_every if wl.expire_steps else 0
     return fwd + bwd + sweep
 
 
@@ -244,7 +244,7 @@ def main():
         achieved = algorithmic_bytes(dom, mean, wl) / (prof[dom][0] / prof[dom][1]) / 1e6
         roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None}
-        sb = step_bytes(mean, wl)
+        sb = step_bytes(mean, wl, sweep_every)
         step_roof = {"algorithmic_bytes_per_step": int(sb),
                      "achieved_GBps": round(sb / (np.median(step_ms) * 1e-3) / 1e9, 1),
                      "frac_of_hbm_peak": round(sb / (np.median(step_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),

@@ -115,15 +115,21 @@ __global__ void sweep_end_kernel(TableView t, uint64_t* n_expired) {
   if (n_expired) *n_expired = removed;
 }
 
+__global__ void sweep_nothing_kernel(uint64_t* n_expired) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) *n_expired = 0;
+}
+
 hipError_t launch_expire_sweep(const TableView& t, uint32_t now, uint64_t* d_n_expired, int64_t* d_expired_keys,
                                uint64_t max_expired, hipStream_t stream, Profiler* prof) {
-  MONO_LAUNCH(prof, K_SWEEP_BEGIN, stream, sweep_begin_kernel, dim3(1), dim3(64), t, now, d_expired_keys, max_expired);
-  if (t.expire_steps > 0) {
-    const dim3 block(256), grid((unsigned)((t.capacity + 255) / 256));
-    MONO_LAUNCH(prof, K_SWEEP, stream, sweep_find_kernel, grid, block, t, now);
-    MONO_LAUNCH(prof, K_SWEEP_REMOVE, stream, sweep_remove_kernel, dim3(grid.x < 2048u ? grid.x : 2048u), block, t,
-                d_expired_keys, max_expired, d_n_expired);
+  if (t.expire_steps == 0) {  // nothing ever expires: only the count is reported
+    if (d_n_expired) MONO_LAUNCH(prof, K_SWEEP_END, stream, sweep_nothing_kernel, dim3(1), dim3(64), d_n_expired);
+    return hipGetLastError();
   }
+  MONO_LAUNCH(prof, K_SWEEP_BEGIN, stream, sweep_begin_kernel, dim3(1), dim3(64), t, now, d_expired_keys, max_expired);
+  const dim3 block(256), grid((unsigned)((t.capacity + 255) / 256));
+  MONO_LAUNCH(prof, K_SWEEP, stream, sweep_find_kernel, grid, block, t, now);
+  MONO_LAUNCH(prof, K_SWEEP_REMOVE, stream, sweep_remove_kernel, dim3(grid.x < 2048u ? grid.x : 2048u), block, t,
+              d_expired_keys, max_expired, d_n_expired);
   MONO_LAUNCH(prof, K_SWEEP_END, stream, sweep_end_kernel, dim3(1), dim3(64), t, d_n_expired);
   return hipGetLastError();
 }
