@@ -112,6 +112,20 @@ int mono_apply_grad_adagrad(mono_table* t, const int32_t* d_rows, uint64_t n, co
 int mono_expire_sweep(mono_table* t, uint32_t now, uint64_t* d_n_expired, int64_t* d_expired_keys,
                       uint64_t max_expired, void* stream);
 
+/* ---- maintenance: incremental synchronisation (not part of the timed step; synchronises `stream`) ---- */
+
+/* Incremental parameter synchronisation (section 2.2.3: the training side keeps the set of touched
+ * keys, the IDs whose embeddings were trained since the last synchronisation, and pushes only
+ * those).  A key is touched once mono_apply_grad_adagrad has updated its row; a key that expires
+ * before the next synchronisation is not reported.  Writes the touched keys in no particular order:
+ *   d_keys[max_n], d_row[max_n] (row index), d_values[max_n * dim] (rows widened to fp32),
+ *   d_acc[max_n]; any of them may be NULL (d_values / d_acc need d_row).
+ * *h_n receives the number of touched keys.  If it is at most max_n the set is now empty (a new
+ * window starts); otherwise nothing was taken and the call can be repeated with larger buffers.
+ * Marking a row costs the update no extra memory access, and starting a window clears nothing. */
+int mono_export_touched(mono_table* t, int64_t* d_keys, int32_t* d_row, float* d_values, float* d_acc, uint64_t max_n,
+                        uint64_t* h_n, void* stream);
+
 /* ---- observability / test surface (not part of the timed path; these synchronise `stream`) ---- */
 
 int mono_table_stats(mono_table* t, mono_stats* h_out, void* stream);

@@ -34,6 +34,7 @@ SYMBOLS = {
     "mono_expire_sweep": (ctypes.c_int, [_vp, _u32, _vp, _vp, _u64, _vp]),
     "mono_table_stats": (ctypes.c_int, [_vp, ctypes.POINTER(mono_stats), _vp]),
     "mono_table_export": (ctypes.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _u64, ctypes.POINTER(_u64), _vp]),
+    "mono_export_touched": (ctypes.c_int, [_vp, _vp, _vp, _vp, _vp, _u64, ctypes.POINTER(_u64), _vp]),
     "mono_filter_export": (ctypes.c_int, [_vp, _vp, _u64, _u64, _vp]),
     "mono_profile_enable": (ctypes.c_int, [_vp, ctypes.c_int]),
     "mono_profile_read": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_double),
@@ -177,6 +178,29 @@ class Table:
         if with_values:
             d["rows"] = vals.cpu().numpy()[order]
             d["acc"] = acc.cpu().numpy()[order]
+        return d
+
+    def mono_export_touched(self, max_n=None, with_values=True):
+        """Keys trained since the last synchronisation, as host numpy arrays sorted by key: keys, row, rows, acc.
+        With max_n below the number of touched keys nothing is taken: returns {"n": count} only."""
+        max_n = self.mono_table_stats()["size"] if max_n is None else max_n
+        dev = self.device
+        keys = torch.empty(max_n, dtype=torch.int64, device=dev)
+        row = torch.empty(max_n, dtype=torch.int32, device=dev)
+        vals = torch.empty((max_n, self.dim), dtype=torch.float32, device=dev) if with_values else None
+        acc = torch.empty(max_n, dtype=torch.float32, device=dev) if with_values else None
+        got = _u64()
+        _check(self.lib.mono_export_touched(self.h, _p(keys), _p(row), _p(vals), _p(acc), max_n, ctypes.byref(got),
+                                            _stream()), "mono_export_touched")
+        n = got.value
+        if n > max_n:
+            return {"n": n}
+        k = keys[:n].cpu().numpy()
+        order = k.view("uint64").argsort(kind="stable")
+        d = {"n": n, "keys": k[order], "row": row[:n].cpu().numpy()[order]}
+        if with_values:
+            d["rows"] = vals[:n].cpu().numpy()[order]
+            d["acc"] = acc[:n].cpu().numpy()[order]
         return d
 
     def mono_profile_enable(self, on):

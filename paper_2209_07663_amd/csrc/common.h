@@ -41,6 +41,14 @@ struct StashEntry {
   uint32_t seen;
 };
 
+// Per-row optimizer state.  `touch` is the number of the synchronisation window in which the row
+// was last trained (paper section 2.2.3: touched keys); it shares the accumulator's 8-byte word so
+// that marking a row costs no memory access of its own.
+struct alignas(8) RowState {
+  float acc;
+  uint32_t touch;
+};
+
 // Counters that live on the device for the whole life of the table.
 struct Control {
   int32_t free_n;            // rows on the free stack
@@ -56,7 +64,7 @@ struct TableView {
   Bucket* buckets;           // [2 * n_buckets]: T0 then T1
   unsigned long long* filter;  // [n_filter] occurrence counters: step << 32 | count
   void* rows;                // [capacity * dim] fp32 or bf16
-  float* acc;                // [capacity]
+  RowState* state;           // [capacity] Adagrad accumulator + touched mark
   uint32_t* free_rows;       // [capacity] stack of free row indices
   Control* ctl;
   StashEntry* stash;         // [kStashCap]
@@ -79,6 +87,7 @@ struct TableView {
   uint32_t freq_threshold;
   uint32_t expire_steps;
   uint32_t bf16;
+  uint32_t sync_epoch;       // current synchronisation window (>= 1); rows with touch == sync_epoch are "touched"
 };
 
 __host__ __device__ inline uint64_t mix64(uint64_t z) {

@@ -60,7 +60,7 @@ hipError_t launch_expire_sweep(const TableView& t, uint32_t now, uint64_t* d_n_e
                                uint64_t max_expired, hipStream_t stream, Profiler* prof);
 
 hipError_t launch_export(const TableView& t, int64_t* d_keys, int32_t* d_row, uint32_t* d_last_seen, int64_t* d_slot,
-                         uint64_t max_n, hipStream_t stream);
+                         uint64_t max_n, bool touched_only, hipStream_t stream);
 hipError_t launch_export_values(const TableView& t, const int32_t* d_row, uint64_t n, float* d_values, float* d_acc,
                                 hipStream_t stream);
 hipError_t launch_filter_export(const TableView& t, uint32_t* d_words, uint64_t first, uint64_t count,

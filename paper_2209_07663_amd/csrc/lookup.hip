@@ -360,7 +360,7 @@ __global__ __launch_bounds__(256) void insert_kernel(TableView t, const int64_t*
         const float4 v = make_float4(init_value(base_h, l * 4), init_value(base_h, l * 4 + 1),
                                      init_value(base_h, l * 4 + 2), init_value(base_h, l * 4 + 3));
         store_init4<E>(rows, (uint64_t)rr * t.dim + l * 4, v);
-        if (l == 0) t.acc[rr] = 0.0f;
+        if (l == 0) t.state[rr] = RowState{0.0f, 0u};
       }
     }
   }

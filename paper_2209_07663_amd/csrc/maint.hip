@@ -140,8 +140,9 @@ __global__ void export_begin_kernel(TableView t) {
   if (blockIdx.x == 0 && threadIdx.x == 0) t.ctl->scratch[1] = 0;
 }
 
+// touched_only: keep only the keys whose row was trained in the current synchronisation window
 __global__ __launch_bounds__(256) void export_kernel(TableView t, int64_t* keys, int32_t* rows, uint32_t* last_seen,
-                                                     int64_t* slot, uint64_t max_n) {
+                                                     int64_t* slot, uint64_t max_n, bool touched_only) {
   const uint64_t g = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const uint64_t total = t.capacity + kStashCap;
   bool live = false;
@@ -167,6 +168,7 @@ __global__ __launch_bounds__(256) void export_kernel(TableView t, int64_t* keys,
       seen = t.stash[s].seen;
     }
   }
+  if (live && touched_only) live = t.state[row].touch == t.sync_epoch;
   const uint64_t m = __ballot(live);
   if (m == 0) return;
   const int leader = __ffsll((unsigned long long)m) - 1;
@@ -185,11 +187,11 @@ __global__ __launch_bounds__(256) void export_kernel(TableView t, int64_t* keys,
 }
 
 hipError_t launch_export(const TableView& t, int64_t* d_keys, int32_t* d_row, uint32_t* d_last_seen, int64_t* d_slot,
-                         uint64_t max_n, hipStream_t stream) {
+                         uint64_t max_n, bool touched_only, hipStream_t stream) {
   hipLaunchKernelGGL(export_begin_kernel, dim3(1), dim3(64), 0, stream, t);
   const uint64_t total = t.capacity + kStashCap;
   hipLaunchKernelGGL(export_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, t, d_keys, d_row,
-                     d_last_seen, d_slot, max_n);
+                     d_last_seen, d_slot, max_n, touched_only);
   return hipGetLastError();
 }
 
@@ -208,7 +210,7 @@ __global__ __launch_bounds__(256) void export_values_kernel(TableView t, const i
     else
       values[g] = (float)src[(uint64_t)r * t.dim + j];
   }
-  if (acc && j == 0) acc[i] = t.acc[r];
+  if (acc && j == 0) acc[i] = t.state[r].acc;
 }
 
 hipError_t launch_export_values(const TableView& t, const int32_t* d_row, uint64_t n, float* d_values, float* d_acc,

@@ -53,7 +53,7 @@ size_t layout(mono_table* t, char* base, uint64_t capacity, uint32_t dim, uint32
   char* buckets = take(2 * n_buckets * sizeof(Bucket));
   char* filter = take(n_filter * sizeof(unsigned long long));
   char* rows = take(capacity * dim * esize);
-  char* acc = take(capacity * sizeof(float));
+  char* state = take(capacity * sizeof(RowState));
   char* free_rows = take(capacity * sizeof(uint32_t));
   char* ctl = take(sizeof(Control));
   char* stash = take(kStashCap * sizeof(StashEntry));
@@ -78,7 +78,7 @@ size_t layout(mono_table* t, char* base, uint64_t capacity, uint32_t dim, uint32
     v.buckets = (Bucket*)buckets;
     v.filter = (unsigned long long*)filter;
     v.rows = rows;
-    v.acc = (float*)acc;
+    v.state = (RowState*)state;
     v.free_rows = (uint32_t*)free_rows;
     v.ctl = (Control*)ctl;
     v.stash = (StashEntry*)stash;
@@ -163,6 +163,7 @@ int mono_table_create(mono_table** out, uint64_t capacity, uint32_t dim, uint64_
   v.freq_threshold = freq_threshold;
   v.expire_steps = expire_steps;
   v.bf16 = flags == MONO_ROWS_BF16;
+  v.sync_epoch = 1;
   t->max_ids = max_ids;
   t->max_bags = max_bags;
   if (launch_table_init(v, t->dset_size, (hipStream_t)stream) != hipSuccess) {
@@ -251,7 +252,7 @@ int mono_table_export(mono_table* t, int64_t* d_keys, int32_t* d_row, uint32_t* 
   if (!t || !h_n) return MONO_EINVAL;
   if ((d_values || d_acc) && !d_row) return MONO_EINVAL;  // values are gathered through the row indices
   hipStream_t s = (hipStream_t)stream;
-  if (launch_export(t->view, d_keys, d_row, d_last_seen, d_slot, max_n, s) != hipSuccess) return MONO_EHIP;
+  if (launch_export(t->view, d_keys, d_row, d_last_seen, d_slot, max_n, false, s) != hipSuccess) return MONO_EHIP;
   unsigned long long n = 0;
   if (hipMemcpyAsync(&n, &t->view.ctl->scratch[1], sizeof(n), hipMemcpyDeviceToHost, s) != hipSuccess ||
       hipStreamSynchronize(s) != hipSuccess)
@@ -262,6 +263,26 @@ int mono_table_export(mono_table* t, int64_t* d_keys, int32_t* d_row, uint32_t* 
     if (launch_export_values(t->view, d_row, wrote, d_values, d_acc, s) != hipSuccess) return MONO_EHIP;
     if (hipStreamSynchronize(s) != hipSuccess) return MONO_EHIP;
   }
+  return MONO_OK;
+}
+
+int mono_export_touched(mono_table* t, int64_t* d_keys, int32_t* d_row, float* d_values, float* d_acc, uint64_t max_n,
+                        uint64_t* h_n, void* stream) {
+  if (!t || !h_n) return MONO_EINVAL;
+  if ((d_values || d_acc) && !d_row) return MONO_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  if (launch_export(t->view, d_keys, d_row, nullptr, nullptr, max_n, true, s) != hipSuccess) return MONO_EHIP;
+  unsigned long long n = 0;
+  if (hipMemcpyAsync(&n, &t->view.ctl->scratch[1], sizeof(n), hipMemcpyDeviceToHost, s) != hipSuccess ||
+      hipStreamSynchronize(s) != hipSuccess)
+    return MONO_EHIP;
+  *h_n = n;
+  if (n > max_n) return MONO_OK;  // the caller's buffers are too small: the window stays open
+  if ((d_values || d_acc) && n) {
+    if (launch_export_values(t->view, d_row, n, d_values, d_acc, s) != hipSuccess) return MONO_EHIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return MONO_EHIP;
+  }
+  t->view.sync_epoch += 1;  // a new window: nothing is touched any more, and no memory was cleared for it
   return MONO_OK;
 }
 

@@ -75,7 +75,7 @@ __device__ inline void adagrad_row(const TableView& t, uint32_t row, float4 g, b
                                    uint32_t group, float lr, float eps) {
   float ss = g.x * g.x + g.y * g.y + g.z * g.z + g.w * g.w;
   for (uint32_t d = 1; d < group; d <<= 1) ss += __shfl_xor(ss, (int)d);
-  const float acc = t.acc[row] + ss / (float)t.dim;
+  const float acc = t.state[row].acc + ss / (float)t.dim;
   const float scale = step_scale(acc, lr, eps);
   if (active) {
     E* rows = reinterpret_cast<E*>(t.rows);
@@ -86,7 +86,7 @@ __device__ inline void adagrad_row(const TableView& t, uint32_t row, float4 g, b
     w.w = fmaf(-scale, g.w, w.w);
     store_row4<E>(rows, row, t.dim, l, w);
   }
-  if (l == 0) t.acc[row] = acc;
+  if (l == 0) t.state[row] = RowState{acc, t.sync_epoch};  // trained in this window
 }
 
 __device__ inline void acc4(float4& a, const float4& b) {
@@ -176,7 +176,7 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(TableView t, const uint
           apply[u] = tail[u] && kx[u] < hwm && (kx[u] != first || first_head_in);
           v[u] = (in && kx[u] < hwm && active) ? g4[(uint64_t)ky[u] * dim4 + l] : zero;
           w[u] = (apply[u] && active) ? load_row4<E>(rows, kx[u], t.dim, l) : zero;
-          a[u] = apply[u] ? t.acc[kx[u]] : 0.f;
+          a[u] = apply[u] ? t.state[kx[u]].acc : 0.f;
         }
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {
@@ -202,7 +202,7 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(TableView t, const uint
                   nw.w = fmaf(-scale, sum.w, nw.w);
                   store_row4<E>(rows, run, t.dim, l, nw);
                 }
-                if (l == 0) t.acc[run] = acc;
+                if (l == 0) t.state[run] = RowState{acc, t.sync_epoch};
               } else if (run < hwm) {  // started in an earlier chunk, ends here
                 a_row = run;
                 if (active) s_vec[(2 * g) * dim4 + l] = sum;

@@ -77,7 +77,7 @@ def test_touched_key_cases(kind):
 
 
 def test_synchronisation_payload_of_the_papers_example():
-    """Section 4 (parameter synchronisation frequency): 100,000 IDs updated in a minute, embedding
+    """Section 3.2.2 (synchronisation frequency of sparse parameters): 100,000 IDs updated in a minute, embedding
     dimension 1024 -> 4 KB x 100,000, about 400 MB to transfer."""
     dim, ids = 1024, 100000
     o = Oracle(1 << 18, dim, 3, freq_threshold=1, kind="map")
