@@ -126,6 +126,36 @@ int mono_expire_sweep(mono_table* t, uint32_t now, uint64_t* d_n_expired, int64_
 int mono_export_touched(mono_table* t, int64_t* d_keys, int32_t* d_row, float* d_values, float* d_acc, uint64_t max_n,
                         uint64_t* h_n, void* stream);
 
+/* ---- maintenance: snapshot / restore, rehash / grow (not part of the timed step) ---- */
+
+/* Restore (section 2.3: a parameter server recovers from its latest snapshot).  A snapshot is what
+ * mono_table_export and mono_filter_export return; this call places n records (key, row values,
+ * accumulator, last-seen step) into the table: each gets a free row, is inserted by the eviction-chain
+ * insertion of section 2.1 without consulting the occurrence filter, and is not marked touched.
+ *   d_keys[n], d_values[n * dim] (fp32; rounded to nearest-even for bf16 rows), d_acc[n], d_last_seen[n]
+ *   n <= max_ids per call (call repeatedly for more)
+ *   h_refused  nullable; receives the number of records not placed: key already stored, key -1,
+ *              second record of a key within the call, or no free row.  Non-NULL synchronises `stream`.
+ * Later lookups need step >= the largest restored last-seen step for expiry to be meaningful. */
+int mono_table_import(mono_table* t, const int64_t* d_keys, const float* d_values, const float* d_acc,
+                      const uint32_t* d_last_seen, uint64_t n, uint64_t* h_refused, void* stream);
+
+/* Writes occurrence counters [first, first + count) from canonical words (see mono_filter_export). */
+int mono_filter_import(mono_table* t, const uint32_t* d_words, uint64_t first, uint64_t count, void* stream);
+
+/* Rehash / grow (section 2.1: a rehash answers an insertion that runs into a cycle; the table is
+ * meant to be adjusted elastically).  `dst` is a table just created with the same dim, flags, seed,
+ * freq_threshold and expire_steps as `src`, a capacity >= src's, and not yet used.  Every key of
+ * src (its overflow stash included) is inserted into dst under the hash functions h0 / h1 of rehash
+ * `generation` (0 = the functions a new table starts with; any other value gives fresh ones); rows
+ * keep their indices, values, accumulators, last-seen steps and touched marks; the free-row stack
+ * and the life-time counters carry over; an occurrence counter of a grown table starts with the
+ * value of the counter its keys shared before, so no count is lost.  src is left unchanged and can
+ * be destroyed afterwards.  Synchronises `stream` once (to read src's counters).
+ * A caller rehashes when mono_table_stats reports stash_size > 0 or a load factor it finds too high.
+ * Errors: MONO_EINVAL if dst does not match src or has been used. */
+int mono_table_migrate(mono_table* dst, mono_table* src, uint32_t generation, void* stream);
+
 /* ---- observability / test surface (not part of the timed path; these synchronise `stream`) ---- */
 
 int mono_table_stats(mono_table* t, mono_stats* h_out, void* stream);

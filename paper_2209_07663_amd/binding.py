@@ -35,6 +35,9 @@ SYMBOLS = {
     "mono_table_stats": (ctypes.c_int, [_vp, ctypes.POINTER(mono_stats), _vp]),
     "mono_table_export": (ctypes.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _u64, ctypes.POINTER(_u64), _vp]),
     "mono_export_touched": (ctypes.c_int, [_vp, _vp, _vp, _vp, _vp, _u64, ctypes.POINTER(_u64), _vp]),
+    "mono_table_import": (ctypes.c_int, [_vp, _vp, _vp, _vp, _vp, _u64, ctypes.POINTER(_u64), _vp]),
+    "mono_filter_import": (ctypes.c_int, [_vp, _vp, _u64, _u64, _vp]),
+    "mono_table_migrate": (ctypes.c_int, [_vp, _vp, _u32, _vp]),
     "mono_filter_export": (ctypes.c_int, [_vp, _vp, _u64, _u64, _vp]),
     "mono_profile_enable": (ctypes.c_int, [_vp, ctypes.c_int]),
     "mono_profile_read": (ctypes.c_int, [_vp, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_double),
@@ -88,6 +91,7 @@ class Table:
                  max_bags=None, device="cuda:0"):
         self.lib = load_library()
         self.capacity, self.dim, self.bf16 = int(capacity), int(dim), bool(bf16)
+        self.seed, self.freq_threshold, self.expire_steps = int(seed), int(freq_threshold), int(expire_steps)
         self.max_ids = int(max_ids)
         self.max_bags = int(max_bags) if max_bags is not None else self.max_ids
         self.device = torch.device(device)
@@ -202,6 +206,36 @@ class Table:
             d["rows"] = vals[:n].cpu().numpy()[order]
             d["acc"] = acc[:n].cpu().numpy()[order]
         return d
+
+    def mono_table_import(self, keys, values, acc, last_seen):
+        """Restores snapshot records (device tensors: int64, fp32 [n, dim], fp32, int32 holding uint32 steps),
+        max_ids at a time; returns how many were refused."""
+        _dev(keys, torch.int64), _dev(values, torch.float32), _dev(acc, torch.float32), _dev(last_seen, torch.int32)
+        n, refused = keys.shape[0], 0
+        assert values.shape == (n, self.dim) and acc.shape[0] == n and last_seen.shape[0] == n
+        for lo in range(0, n, self.max_ids):
+            hi = min(n, lo + self.max_ids)
+            r = _u64()
+            _check(self.lib.mono_table_import(self.h, _p(keys[lo:hi]), _p(values[lo:hi]), _p(acc[lo:hi]),
+                                              _p(last_seen[lo:hi]), hi - lo, ctypes.byref(r), _stream()),
+                   "mono_table_import")
+            refused += r.value
+        return refused
+
+    def mono_filter_import(self, words, first=0):
+        _dev(words, torch.int32)
+        _check(self.lib.mono_filter_import(self.h, _p(words), first, words.shape[0], _stream()), "mono_filter_import")
+
+    def mono_table_migrate(self, src, generation):
+        """Fills this (fresh) table with everything `src` holds, under the hash functions of `generation`."""
+        _check(self.lib.mono_table_migrate(self.h, src.h, generation, _stream()), "mono_table_migrate")
+
+    def rehashed(self, new_capacity, generation):
+        """A new table of `new_capacity` >= capacity holding this table's contents (this one stays as it is)."""
+        dst = Table(new_capacity, self.dim, self.seed, self.freq_threshold, self.expire_steps, self.bf16,
+                    max_ids=self.max_ids, max_bags=self.max_bags, device=self.device)
+        dst.mono_table_migrate(self, generation)
+        return dst
 
     def mono_profile_enable(self, on):
         _check(self.lib.mono_profile_enable(self.h, int(on)), "mono_profile_enable")

@@ -34,6 +34,7 @@ constexpr int kWinLists = 64;               // sub-lists of elected occurrences 
 constexpr int kWinStride = 32;              // u32 words between two sub-list counters (one 128-byte line each)
 
 constexpr int kValidPairs = 2;              // Control::scratch slot: (row, bag) pairs kept by the sort
+constexpr int kRefusedRecords = 3;          // Control::scratch slot: records refused by the running restore call
 
 struct StashEntry {
   uint64_t key;

@@ -41,8 +41,20 @@ __host__ __device__ inline SortPlan make_sort_plan(uint32_t hwm) {
   return s;
 }
 
+// What a restore call supplies per record instead of the initial state of a fresh key
+// (values == nullptr: an ordinary lookup_or_insert).
+struct RestoreSource {
+  const float* values;   // [n * dim] fp32, rounded to the storage type on the way in
+  const float* acc;      // [n] accumulators
+  const uint32_t* seen;  // [n] last-seen steps
+};
+
 hipError_t launch_lookup_or_insert(const TableView& t, const int64_t* d_keys, uint64_t n, uint32_t step, uint32_t epoch,
-                                   int32_t* d_rows_out, hipStream_t stream, Profiler* prof);
+                                   int32_t* d_rows_out, const RestoreSource& src, hipStream_t stream, Profiler* prof);
+
+// Re-inserts every element of src into dst (dst empty, same dim and storage type, capacity >= src's),
+// carries the free-row stack over and spreads the occurrence counters; rows are copied by the caller.
+hipError_t launch_migrate(const TableView& dst, const TableView& src, int32_t src_free_n, hipStream_t stream);
 
 hipError_t launch_gather_pool(const TableView& t, const int32_t* d_rows, uint64_t n, const int64_t* d_offsets,
                               uint64_t n_bags, float* d_out, hipStream_t stream, Profiler* prof);
@@ -64,6 +76,8 @@ hipError_t launch_export(const TableView& t, int64_t* d_keys, int32_t* d_row, ui
 hipError_t launch_export_values(const TableView& t, const int32_t* d_row, uint64_t n, float* d_values, float* d_acc,
                                 hipStream_t stream);
 hipError_t launch_filter_export(const TableView& t, uint32_t* d_words, uint64_t first, uint64_t count,
+                                hipStream_t stream);
+hipError_t launch_filter_import(const TableView& t, const uint32_t* d_words, uint64_t first, uint64_t count,
                                 hipStream_t stream);
 hipError_t launch_table_init(const TableView& t, uint64_t dset_size, hipStream_t stream);
 

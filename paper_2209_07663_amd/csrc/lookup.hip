@@ -14,6 +14,11 @@
 //   resolve       duplicates of an admitted key pick up the row of the elected occurrence; one
 //                 thread settles the counters
 //
+// The same four kernels restore snapshot records (`Restore` below): every record is a forced
+// admission whose row, accumulator and last-seen step come from the caller instead of from
+// init(seed, key) / the current step; a record whose key is already stored is refused.  The
+// migrate kernel re-inserts every stored element of one table into another (rehash / grow).
+//
 // Slot protocol (no 128-bit atomics, no fences): a slot's `meta` word doubles as its lock.
 //   free slot:   key == EMPTY, meta == kNoMeta
 //   claim:       CAS key EMPTY -> k (wait for the result); then store meta (publishes row + stamp)
@@ -90,9 +95,11 @@ __device__ inline void probe_side(const TableView& t, uint64_t k, uint64_t bucke
 constexpr int kProbeBlock = 1024;           // threads (= keys) per block of probe_count
 constexpr int kMissSlots = 2 * kProbeBlock;  // slots of the block's LDS set of missing keys
 
+// restore != 0: the keys are snapshot records; a stored key is marked absent (its record is refused)
+// and nothing is stamped or counted.
 __global__ __launch_bounds__(kProbeBlock) void probe_count_kernel(TableView t, const int64_t* __restrict__ keys,
                                                                   uint64_t n, uint32_t step,
-                                                                  int32_t* __restrict__ rows_out) {
+                                                                  int32_t* __restrict__ rows_out, int restore) {
   // The block's missing keys are gathered in an LDS set with their multiplicities, and each distinct
   // one touches its counter once: a hot ID that is not (yet) admitted would otherwise hit one counter
   // word with 10^5 atomics, which serialise at ~12 ns each.
@@ -112,7 +119,7 @@ __global__ __launch_bounds__(kProbeBlock) void probe_count_kernel(TableView t, c
   // (most misses are tail IDs seen once).  Counts added by this very batch can only make the test
   // err on the side of probing.
   bool maybe = live;
-  if (t.expire_steps == 0 && live) {
+  if (t.expire_steps == 0 && live && !restore) {
     const uint32_t cnt = reinterpret_cast<const uint32_t*>(&t.filter[filter_index(t, k)])[0];
     maybe = cnt >= (t.freq_threshold > 1u ? t.freq_threshold : 1u);
   }
@@ -131,8 +138,9 @@ __global__ __launch_bounds__(kProbeBlock) void probe_count_kernel(TableView t, c
     if (!live) {
       rows_out[i] = kRowAbsent;
     } else if (slot >= 0) {
-      rows_out[i] = (int32_t)meta_row(m);
-      if (meta_seen(m) != step) reinterpret_cast<uint32_t*>(&t.buckets[where].meta[slot])[1] = step;  // stamp
+      rows_out[i] = restore ? kRowAbsent : (int32_t)meta_row(m);
+      if (!restore && meta_seen(m) != step)
+        reinterpret_cast<uint32_t*>(&t.buckets[where].meta[slot])[1] = step;  // stamp
     } else {
       miss = true;
       const uint32_t sn = t.ctl->stash_n;
@@ -140,14 +148,15 @@ __global__ __launch_bounds__(kProbeBlock) void probe_count_kernel(TableView t, c
         const uint32_t lim = sn < kStashCap ? sn : kStashCap;
         for (uint32_t s = 0; s < lim && miss; ++s)
           if (t.stash[s].key == k) {
-            rows_out[i] = (int32_t)t.stash[s].row;
-            t.stash[s].seen = step;
+            rows_out[i] = restore ? kRowAbsent : (int32_t)t.stash[s].row;
+            if (!restore) t.stash[s].seen = step;
             miss = false;
           }
       }
       if (miss) rows_out[i] = kRowMiss;
     }
   }
+  if (restore) return;  // block-uniform: records are not occurrences, nothing is counted
   __syncthreads();  // the LDS set is cleared
   if (miss) {
     uint32_t pos = (uint32_t)(mix64(k ^ t.s_dedup) >> 40) & (kMissSlots - 1);
@@ -166,7 +175,7 @@ __global__ __launch_bounds__(kProbeBlock) void probe_count_kernel(TableView t, c
 // ---- election ------------------------------------------------------------------------------------
 
 __global__ __launch_bounds__(256) void admit_elect_kernel(TableView t, const int64_t* __restrict__ keys, uint64_t n,
-                                                          uint32_t epoch, int32_t* rows_out) {
+                                                          uint32_t epoch, int32_t* rows_out, int restore) {
   __shared__ uint32_t wave_cnt[4];
   __shared__ uint32_t block_base;
   const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -175,12 +184,15 @@ __global__ __launch_bounds__(256) void admit_elect_kernel(TableView t, const int
   uint64_t pos = 0;
   if (miss) {
     const uint64_t k = (uint64_t)keys[i];
-    unsigned long long* w = &t.filter[filter_index(t, k)];
-    const unsigned long long word = *w;
-    uint32_t cnt = (uint32_t)word;
-    if (cnt > 255u) {  // keep the unsaturated count from ever wrapping
-      atomicMin(w, (word & 0xFFFFFFFF00000000ull) | 255ull);
-      cnt = 255u;
+    uint32_t cnt = 255u;  // a snapshot record is admitted whatever its counter says
+    if (!restore) {
+      unsigned long long* w = &t.filter[filter_index(t, k)];
+      const unsigned long long word = *w;
+      cnt = (uint32_t)word;
+      if (cnt > 255u) {  // keep the unsaturated count from ever wrapping
+        atomicMin(w, (word & 0xFFFFFFFF00000000ull) | 255ull);
+        cnt = 255u;
+      }
     }
     if (cnt < t.freq_threshold) {
       rows_out[i] = kRowAbsent;
@@ -202,7 +214,8 @@ __global__ __launch_bounds__(256) void admit_elect_kernel(TableView t, const int
         if ((uint64_t)keys[(uint32_t)e] == k) break;  // duplicate of the owner
         pos = (pos + 1) & t.dset_mask;
       }
-      if (!winner) rows_out[i] = -(int32_t)pos - 3;
+      // (a second record of the same key in one restore call is refused like a stored key)
+      if (!winner) rows_out[i] = restore ? kRowAbsent : -(int32_t)pos - 3;
     }
   }
   // block-aggregated append to sub-list (blockIdx mod kWinLists)
@@ -306,7 +319,7 @@ __device__ inline void store_init4<uint16_t>(uint16_t* rows, uint64_t idx, float
 // Dense over the elected occurrences: winner number w of the call takes free_rows[free_n - 1 - w].
 template <typename E>
 __global__ __launch_bounds__(256) void insert_kernel(TableView t, const int64_t* __restrict__ keys, uint32_t step,
-                                                     int32_t* rows_out) {
+                                                     int32_t* rows_out, RestoreSource src) {
   const uint32_t lane = lane_id();
   // inclusive prefix of the sub-list fills, one list per lane
   uint32_t inc = t.win_cnt[lane * kWinStride];
@@ -334,15 +347,16 @@ __global__ __launch_bounds__(256) void insert_kernel(TableView t, const int64_t*
     }
     const uint32_t before = __shfl(inc, (int)(lo > 0 ? lo - 1 : 0));
     uint64_t k = 0;
-    uint32_t row = kNoRow;
+    uint32_t row = kNoRow, occ = 0;
     if (valid) {
       const uint32_t p = w - (lo > 0 ? before : 0u);
       const uint2 e = t.win_list[(uint64_t)lo * t.win_cap + p];
+      occ = e.x;
       k = (uint64_t)keys[e.x];
       if ((int64_t)w < (int64_t)free0) row = t.free_rows[free0 - 1 - (int32_t)w];
       t.dset_row[e.y] = row == kNoRow ? kRowAbsent : (int32_t)row;
       rows_out[e.x] = row == kNoRow ? kRowAbsent : (int32_t)row;
-      if (row != kNoRow) cuckoo_insert(t, k, make_meta(row, step));
+      if (row != kNoRow) cuckoo_insert(t, k, make_meta(row, src.seen ? src.seen[e.x] : step));
     }
     // the wave initialises its new rows together: a group of dim/4 lanes per row, four elements per
     // lane, 64/group rows at a time, stored as whole 16-byte (fp32) or 8-byte (bf16) pieces
@@ -352,15 +366,21 @@ __global__ __launch_bounds__(256) void insert_kernel(TableView t, const int64_t*
     const int ok = valid && row != kNoRow;
     if (__ballot(ok) == 0) continue;  // wave-uniform
     for (uint32_t q = 0; q < group; ++q) {
-      const int src = (int)(q * per_round + gi);
-      const uint64_t kk = __shfl(k, src);
-      const uint32_t rr = __shfl(row, src);
-      if (__shfl(ok, src) && l * 4 < t.dim) {
-        const uint64_t base_h = mix64(kk ^ t.s_init);
-        const float4 v = make_float4(init_value(base_h, l * 4), init_value(base_h, l * 4 + 1),
-                                     init_value(base_h, l * 4 + 2), init_value(base_h, l * 4 + 3));
+      const int from = (int)(q * per_round + gi);
+      const uint64_t kk = __shfl(k, from);
+      const uint32_t rr = __shfl(row, from);
+      const uint32_t oo = __shfl(occ, from);
+      if (__shfl(ok, from) && l * 4 < t.dim) {
+        float4 v;
+        if (src.values) {
+          v = *reinterpret_cast<const float4*>(src.values + (uint64_t)oo * t.dim + l * 4);
+        } else {
+          const uint64_t base_h = mix64(kk ^ t.s_init);
+          v = make_float4(init_value(base_h, l * 4), init_value(base_h, l * 4 + 1), init_value(base_h, l * 4 + 2),
+                          init_value(base_h, l * 4 + 3));
+        }
         store_init4<E>(rows, (uint64_t)rr * t.dim + l * 4, v);
-        if (l == 0) t.state[rr] = RowState{0.0f, 0u};
+        if (l == 0) t.state[rr] = RowState{src.acc ? src.acc[oo] : 0.0f, 0u};
       }
     }
   }
@@ -388,19 +408,78 @@ __global__ __launch_bounds__(256) void resolve_kernel(TableView t, uint64_t n, i
   }
 }
 
+// Records of a restore call that were refused (rows_out < 0 after the resolve step) -> scratch slot.
+__global__ __launch_bounds__(256) void count_refused_kernel(TableView t, uint64_t n, const int32_t* rows_out) {
+  const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const uint64_t m = __ballot(i < n && rows_out[i] < 0);
+  if (m && lane_id() == 0) atomicAdd(&t.ctl->scratch[kRefusedRecords], (unsigned long long)__popcll(m));
+}
+
 hipError_t launch_lookup_or_insert(const TableView& t, const int64_t* d_keys, uint64_t n, uint32_t step, uint32_t epoch,
-                                   int32_t* d_rows_out, hipStream_t stream, Profiler* prof) {
+                                   int32_t* d_rows_out, const RestoreSource& src, hipStream_t stream, Profiler* prof) {
   if (n == 0) return hipSuccess;
+  const int restore = src.values != nullptr;
   const dim3 block(256), grid((unsigned)((n + 255) / 256));
   const dim3 igrid(grid.x < 2048u ? grid.x : 2048u);
   MONO_LAUNCH(prof, K_PROBE_COUNT, stream, probe_count_kernel, dim3((unsigned)((n + kProbeBlock - 1) / kProbeBlock)),
-              dim3(kProbeBlock), t, d_keys, n, step, d_rows_out);
-  MONO_LAUNCH(prof, K_ADMIT_ELECT, stream, admit_elect_kernel, grid, block, t, d_keys, n, epoch, d_rows_out);
+              dim3(kProbeBlock), t, d_keys, n, step, d_rows_out, restore);
+  MONO_LAUNCH(prof, K_ADMIT_ELECT, stream, admit_elect_kernel, grid, block, t, d_keys, n, epoch, d_rows_out, restore);
   if (t.bf16)
-    MONO_LAUNCH(prof, K_INSERT, stream, insert_kernel<uint16_t>, igrid, block, t, d_keys, step, d_rows_out);
+    MONO_LAUNCH(prof, K_INSERT, stream, insert_kernel<uint16_t>, igrid, block, t, d_keys, step, d_rows_out, src);
   else
-    MONO_LAUNCH(prof, K_INSERT, stream, insert_kernel<float>, igrid, block, t, d_keys, step, d_rows_out);
+    MONO_LAUNCH(prof, K_INSERT, stream, insert_kernel<float>, igrid, block, t, d_keys, step, d_rows_out, src);
   MONO_LAUNCH(prof, K_RESOLVE, stream, resolve_kernel, grid, block, t, n, d_rows_out);
+  if (restore) hipLaunchKernelGGL(count_refused_kernel, grid, block, 0, stream, t, n, d_rows_out);
+  return hipGetLastError();
+}
+
+// ---- rehash / grow -------------------------------------------------------------------------------
+
+// Every stored element of `src` (slots, then the stash) is inserted into `dst` under dst's hash
+// functions, with its row index and last-seen step unchanged (the rows themselves are copied
+// separately, position for position).  Elements are distinct and none is in dst: the insertion
+// protocol's preconditions hold.
+__global__ __launch_bounds__(256) void migrate_kernel(TableView dst, TableView src) {
+  const uint64_t g = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (g < src.capacity) {
+    const Bucket* b = &src.buckets[g >> 3];
+    const unsigned long long m = b->meta[g & 7];
+    if (meta_row(m) != kNoRow) cuckoo_insert(dst, b->key[g & 7], m);
+  } else if (g < src.capacity + kStashCap) {
+    const uint32_t s = (uint32_t)(g - src.capacity);
+    const uint32_t sn = src.ctl->stash_n < kStashCap ? src.ctl->stash_n : kStashCap;
+    if (s < sn) cuckoo_insert(dst, src.stash[s].key, make_meta(src.stash[s].row, src.stash[s].seen));
+  }
+}
+
+// Free stack of the grown table: the new rows at the bottom (handed out last, in ascending order),
+// the free rows of the old table above them in their old order.
+__global__ __launch_bounds__(256) void migrate_free_rows_kernel(TableView dst, TableView src, int32_t src_free_n) {
+  const uint64_t g = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const uint64_t extra = dst.capacity - src.capacity;
+  if (g < extra)
+    dst.free_rows[g] = (uint32_t)(dst.capacity - 1 - g);
+  else if (g < extra + (uint64_t)src_free_n)
+    dst.free_rows[g] = src.free_rows[g - extra];
+}
+
+// Counter i of the grown array takes the value of the counter its keys used to share (top-bit
+// addressing: old index = new index >> shift).
+__global__ __launch_bounds__(256) void migrate_filter_kernel(TableView dst, TableView src, uint32_t shift) {
+  const uint64_t g = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (g < dst.n_filter) dst.filter[g] = src.filter[g >> shift];
+}
+
+hipError_t launch_migrate(const TableView& dst, const TableView& src, int32_t src_free_n, hipStream_t stream) {
+  uint32_t shift = 0;
+  while ((src.capacity << shift) < dst.capacity) ++shift;
+  const dim3 block(256);
+  hipLaunchKernelGGL(migrate_filter_kernel, dim3((unsigned)((dst.n_filter + 255) / 256)), block, 0, stream, dst, src,
+                     shift);
+  hipLaunchKernelGGL(migrate_free_rows_kernel, dim3((unsigned)((dst.capacity + 255) / 256)), block, 0, stream, dst, src,
+                     src_free_n);
+  const uint64_t total = src.capacity + kStashCap;
+  hipLaunchKernelGGL(migrate_kernel, dim3((unsigned)((total + 255) / 256)), block, 0, stream, dst, src);
   return hipGetLastError();
 }
 

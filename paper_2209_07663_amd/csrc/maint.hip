@@ -242,6 +242,23 @@ hipError_t launch_filter_export(const TableView& t, uint32_t* d_words, uint64_t 
   return hipGetLastError();
 }
 
+// canonical word -> the table's own form (step << 32 | count)
+__global__ __launch_bounds__(256) void filter_import_kernel(TableView t, const uint32_t* words, uint64_t first,
+                                                            uint64_t count) {
+  const uint64_t g = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (g >= count) return;
+  const uint32_t w = words[g];
+  t.filter[first + g] = ((unsigned long long)(w >> 8) << 32) | (unsigned long long)(w & 255u);
+}
+
+hipError_t launch_filter_import(const TableView& t, const uint32_t* d_words, uint64_t first, uint64_t count,
+                                hipStream_t stream) {
+  if (count == 0) return hipSuccess;
+  hipLaunchKernelGGL(filter_import_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, stream, t, d_words,
+                     first, count);
+  return hipGetLastError();
+}
+
 // ---- initialisation ------------------------------------------------------------------------------
 
 // Free stack filled so that rows are handed out in ascending order: keys admitted early (the

@@ -14,6 +14,8 @@ struct mono_table {
   uint64_t max_ids = 0, max_bags = 0, dset_size = 0;
   uint32_t epoch = 0;       // per-call tag of the dedup set
   uint32_t last_step = 0;
+  uint64_t seed = 0;
+  uint32_t generation = 0;  // rehash generation of the placement hashes h0 / h1
   int device = 0;
   Profiler prof;
 };
@@ -27,6 +29,14 @@ int log2u(uint64_t v) {
   return lg;
 }
 size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// salt i of a seed: output i + 1 of the SplitMix64 sequence started at the seed
+uint64_t salt(uint64_t seed, int i) { return mix64(seed + (uint64_t)(i + 1) * 0x9E3779B97F4A7C15ull); }
+// The placement hashes of rehash generation g are salted from seed + g * (an odd constant);
+// generation 0 is the table as created.  Counter, initial-value and dedup hashes never change.
+uint64_t placement_seed(uint64_t seed, uint32_t generation) {
+  return seed + (uint64_t)generation * 0xD1B54A32D192ED03ull;
+}
 
 bool valid_shape(uint64_t capacity, uint32_t dim, uint32_t flags, uint64_t max_ids, uint64_t max_bags) {
   return is_pow2(capacity) && capacity >= 16 && capacity <= (1ull << 30) && dim >= 4 && dim <= 256 && dim % 4 == 0 &&
@@ -151,7 +161,8 @@ int mono_table_create(mono_table** out, uint64_t capacity, uint32_t dim, uint64_
   t->dset_size = dedup_size(max_ids);
   v.dset_mask = t->dset_size - 1;
   uint64_t s[5];
-  for (int i = 0; i < 5; ++i) s[i] = mix64(seed + (uint64_t)(i + 1) * 0x9E3779B97F4A7C15ull);
+  for (int i = 0; i < 5; ++i) s[i] = salt(seed, i);
+  t->seed = seed;
   v.s_h0 = s[0];
   v.s_h1 = s[1];
   v.s_filter = s[2];
@@ -195,7 +206,9 @@ int mono_lookup_or_insert(mono_table* t, const int64_t* d_keys, uint64_t n, uint
       return MONO_EHIP;
     t->epoch = 1;
   }
-  return launch_lookup_or_insert(t->view, d_keys, n, step, t->epoch, d_rows_out, (hipStream_t)stream, &t->prof) == hipSuccess
+  const RestoreSource none = {nullptr, nullptr, nullptr};
+  return launch_lookup_or_insert(t->view, d_keys, n, step, t->epoch, d_rows_out, none, (hipStream_t)stream, &t->prof) ==
+                 hipSuccess
              ? MONO_OK
              : MONO_EHIP;
 }
@@ -284,6 +297,72 @@ int mono_export_touched(mono_table* t, int64_t* d_keys, int32_t* d_row, float* d
   }
   t->view.sync_epoch += 1;  // a new window: nothing is touched any more, and no memory was cleared for it
   return MONO_OK;
+}
+
+int mono_table_import(mono_table* t, const int64_t* d_keys, const float* d_values, const float* d_acc,
+                      const uint32_t* d_last_seen, uint64_t n, uint64_t* h_refused, void* stream) {
+  if (!t || n > t->max_ids) return MONO_EINVAL;
+  if (h_refused) *h_refused = 0;
+  if (n == 0) return MONO_OK;
+  if (!d_keys || !d_values || !d_acc || !d_last_seen) return MONO_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  if (++t->epoch == 0) {
+    if (hipMemsetAsync(t->view.dset, 0, t->dset_size * sizeof(unsigned long long), s) != hipSuccess) return MONO_EHIP;
+    t->epoch = 1;
+  }
+  if (hipMemsetAsync(&t->view.ctl->scratch[kRefusedRecords], 0, sizeof(unsigned long long), s) != hipSuccess)
+    return MONO_EHIP;
+  const RestoreSource src = {d_values, d_acc, d_last_seen};
+  // the per-occurrence result array of the four kernels lives in the update workspace (max_ids words)
+  if (launch_lookup_or_insert(t->view, d_keys, n, 0, t->epoch, (int32_t*)t->ws.bag_of, src, s, &t->prof) != hipSuccess)
+    return MONO_EHIP;
+  if (h_refused) {
+    unsigned long long r = 0;
+    if (hipMemcpyAsync(&r, &t->view.ctl->scratch[kRefusedRecords], sizeof(r), hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess)
+      return MONO_EHIP;
+    *h_refused = r;
+  }
+  return MONO_OK;
+}
+
+int mono_filter_import(mono_table* t, const uint32_t* d_words, uint64_t first, uint64_t count, void* stream) {
+  if (!t || first + count > t->view.n_filter || (count && !d_words)) return MONO_EINVAL;
+  return launch_filter_import(t->view, d_words, first, count, (hipStream_t)stream) == hipSuccess ? MONO_OK : MONO_EHIP;
+}
+
+int mono_table_migrate(mono_table* dst, mono_table* src, uint32_t generation, void* stream) {
+  if (!dst || !src || dst == src) return MONO_EINVAL;
+  const TableView& a = src->view;
+  TableView& b = dst->view;
+  if (b.capacity < a.capacity || b.dim != a.dim || b.bf16 != a.bf16 || dst->seed != src->seed ||
+      b.freq_threshold != a.freq_threshold || b.expire_steps != a.expire_steps || dst->epoch != 0 || dst->last_step != 0)
+    return MONO_EINVAL;  // dst must be a fresh table with the same parameters
+  hipStream_t s = (hipStream_t)stream;
+  Control c;
+  if (hipMemcpyAsync(&c, a.ctl, sizeof(Control), hipMemcpyDeviceToHost, s) != hipSuccess ||
+      hipStreamSynchronize(s) != hipSuccess)
+    return MONO_EHIP;
+  b.s_h0 = salt(placement_seed(dst->seed, generation), 0);
+  b.s_h1 = salt(placement_seed(dst->seed, generation), 1);
+  b.sync_epoch = a.sync_epoch;
+  dst->generation = generation;
+  dst->last_step = src->last_step;
+  // rows and their state keep their indices: copied position for position up to the high-water mark
+  const size_t esize = a.bf16 ? 2 : 4;
+  if (c.hwm) {
+    if (hipMemcpyAsync(b.rows, a.rows, (size_t)c.hwm * a.dim * esize, hipMemcpyDeviceToDevice, s) != hipSuccess ||
+        hipMemcpyAsync(b.state, a.state, (size_t)c.hwm * sizeof(RowState), hipMemcpyDeviceToDevice, s) != hipSuccess)
+      return MONO_EHIP;
+  }
+  Control d = c;
+  d.stash_n = 0;  // stash elements get a new chance under the new hash functions
+  d.free_n = c.free_n + (int32_t)(b.capacity - a.capacity);
+  for (auto& x : d.scratch) x = 0;
+  if (hipMemcpyAsync(b.ctl, &d, sizeof(Control), hipMemcpyHostToDevice, s) != hipSuccess ||
+      hipStreamSynchronize(s) != hipSuccess)  // `d` is a local: the copy must have left it
+    return MONO_EHIP;
+  return launch_migrate(b, a, c.free_n, s) == hipSuccess ? MONO_OK : MONO_EHIP;
 }
 
 int mono_filter_export(mono_table* t, uint32_t* d_words, uint64_t first, uint64_t count, void* stream) {
