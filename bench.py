@@ -109,6 +109,66 @@ def step_bytes(s, wl, sweep_every):
     return fwd + bwd + sweep
 
 
+def time_maintenance(tab, wl, seed, max_ids, dev):
+    """Wall time (host clock around calls that synchronise) of the operations around the hot path, on the
+    table as the timed steps left it: delta export of the touched keys, full snapshot, restore of that
+    snapshot into a fresh table, rehash into a table twice the size.  Bytes are the payloads moved."""
+    import ctypes
+    import torch
+    from paper_2209_07663_amd.binding import Table, _check, _p, _stream
+    size = tab.mono_table_stats()["size"]
+    keys = torch.empty(size, dtype=torch.int64, device=dev)
+    row = torch.empty(size, dtype=torch.int32, device=dev)
+    seen = torch.empty(size, dtype=torch.int32, device=dev)
+    vals = torch.empty((size, wl.dim), dtype=torch.float32, device=dev)
+    acc = torch.empty(size, dtype=torch.float32, device=dev)
+    words = torch.empty(4 * wl.capacity, dtype=torch.int32, device=dev)
+    got = ctypes.c_uint64()
+    rec = 8 + 4 * wl.dim + 4 + 4                     # key, fp32 row, accumulator, last-seen / row index
+    res = {}
+
+    def timed(fn):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3
+
+    ms = timed(lambda: _check(tab.lib.mono_export_touched(tab.h, _p(keys), _p(row), _p(vals), _p(acc), size,
+                                                         ctypes.byref(got), _stream()), "mono_export_touched"))
+    n = got.value
+    res["export_touched"] = {"keys": n, "ms": round(ms, 3), "payload_GBps": round(n * rec / ms / 1e6, 1),
+                             "window": "every update since the table was created"}
+    ms = timed(lambda: (_check(tab.lib.mono_table_export(tab.h, _p(keys), _p(row), _p(seen), None, _p(vals), _p(acc),
+                                                         size, ctypes.byref(got), _stream()), "mono_table_export"),
+                        _check(tab.lib.mono_filter_export(tab.h, _p(words), 0, 4 * wl.capacity, _stream()),
+                               "mono_filter_export")))
+    snap_bytes = size * rec + 4 * 4 * wl.capacity
+    res["snapshot"] = {"keys": size, "ms": round(ms, 3), "payload_GBps": round(snap_bytes / ms / 1e6, 1)}
+    fresh = Table(wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, max_ids=max_ids,
+                  max_bags=wl.n_bags, device=dev)
+
+    def restore():
+        for lo in range(0, size, max_ids):
+            hi = min(size, lo + max_ids)
+            _check(fresh.lib.mono_table_import(fresh.h, _p(keys[lo:hi]), _p(vals[lo:hi]), _p(acc[lo:hi]), _p(seen[lo:hi]),
+                                               hi - lo, None, _stream()), "mono_table_import")
+        fresh.mono_filter_import(words)
+    ms = timed(restore)
+    assert fresh.mono_table_stats()["size"] == size
+    res["restore"] = {"keys": size, "ms": round(ms, 3), "payload_GBps": round(snap_bytes / ms / 1e6, 1),
+                      "keys_per_s": round(size / ms * 1e3)}
+    fresh.close()
+    big = Table(2 * wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, max_ids=max_ids,
+                max_bags=wl.n_bags, device=dev)
+    ms = timed(lambda: big.mono_table_migrate(tab, 1))
+    st = big.mono_table_stats()
+    assert st["size"] == size and st["stash_size"] == 0
+    res["rehash_to_double_capacity"] = {"keys": size, "ms": round(ms, 3), "keys_per_s": round(size / ms * 1e3)}
+    big.close()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -122,6 +182,8 @@ def main():
     ap.add_argument("--workers", type=int, default=min(16, os.cpu_count() or 8))
     ap.add_argument("--fill-load", type=float, default=0.0,
                     help="before anything else, admit the hottest IDs until this load factor (configs[3] asks for 0.9)")
+    ap.add_argument("--no-maintenance", action="store_true",
+                    help="skip the timing of delta export, snapshot, restore and rehash after the timed steps")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy five times (reference for FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -252,6 +314,8 @@ def main():
     else:
         step_roof = None
 
+    maintenance = None if args.no_maintenance else time_maintenance(tab, wl, args.seed, max_ids, dev)
+
     out = {
         "metric": "sparse IDs/sec per training step (lookup+pool+update)",
         "value": ids / elapsed, "unit": "IDs/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -265,7 +329,7 @@ def main():
                    "load_factor": round(load_before, 4), "sweep_every_steps": sweep_every,
                    "step": "lookup_or_insert+gather_pool+apply_grad_adagrad+expire_sweep"},
         "median_step_ms_events": float(np.median(step_ms)), "min_step_ms_events": float(np.min(step_ms)),
-        "roofline": roofline, "step_roofline": step_roof, "kernels": kernels, "cpu_baseline": cpu,
+        "roofline": roofline, "step_roofline": step_roof, "kernels": kernels, "maintenance": maintenance, "cpu_baseline": cpu,
     }
     print(json.dumps(out))
 

@@ -140,9 +140,12 @@ __global__ void export_begin_kernel(TableView t) {
   if (blockIdx.x == 0 && threadIdx.x == 0) t.ctl->scratch[1] = 0;
 }
 
+constexpr int kExportBlock = 1024;
+
 // touched_only: keep only the keys whose row was trained in the current synchronisation window
-__global__ __launch_bounds__(256) void export_kernel(TableView t, int64_t* keys, int32_t* rows, uint32_t* last_seen,
-                                                     int64_t* slot, uint64_t max_n, bool touched_only) {
+__global__ __launch_bounds__(kExportBlock) void export_kernel(TableView t, int64_t* keys, int32_t* rows,
+                                                              uint32_t* last_seen, int64_t* slot, uint64_t max_n,
+                                                              bool touched_only) {
   const uint64_t g = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const uint64_t total = t.capacity + kStashCap;
   bool live = false;
@@ -169,14 +172,22 @@ __global__ __launch_bounds__(256) void export_kernel(TableView t, int64_t* keys,
     }
   }
   if (live && touched_only) live = t.state[row].touch == t.sync_epoch;
+  // one append per block: the waves' counts meet in LDS (a counter hit once per wave would serialise)
+  __shared__ uint32_t wave_cnt[kExportBlock / 64];
+  __shared__ unsigned long long block_base;
+  const uint32_t wave = threadIdx.x >> 6;
   const uint64_t m = __ballot(live);
-  if (m == 0) return;
-  const int leader = __ffsll((unsigned long long)m) - 1;
-  unsigned long long base = 0;
-  if ((int)lane_id() == leader) base = atomicAdd(&t.ctl->scratch[1], (unsigned long long)__popcll(m));
-  base = __shfl(base, leader);
+  if (lane_id() == 0) wave_cnt[wave] = (uint32_t)__popcll(m);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t found = 0;
+    for (int w = 0; w < kExportBlock / 64; ++w) found += wave_cnt[w];
+    block_base = found ? atomicAdd(&t.ctl->scratch[1], (unsigned long long)found) : 0ull;
+  }
+  __syncthreads();
   if (live) {
-    const uint64_t o = base + __popcll(m & lanes_below());
+    uint64_t o = block_base + __popcll(m & lanes_below());
+    for (uint32_t w = 0; w < wave; ++w) o += wave_cnt[w];
     if (o < max_n) {
       if (keys) keys[o] = (int64_t)key;
       if (rows) rows[o] = (int32_t)row;
@@ -190,38 +201,46 @@ hipError_t launch_export(const TableView& t, int64_t* d_keys, int32_t* d_row, ui
                          uint64_t max_n, bool touched_only, hipStream_t stream) {
   hipLaunchKernelGGL(export_begin_kernel, dim3(1), dim3(64), 0, stream, t);
   const uint64_t total = t.capacity + kStashCap;
-  hipLaunchKernelGGL(export_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, t, d_keys, d_row,
-                     d_last_seen, d_slot, max_n, touched_only);
+  hipLaunchKernelGGL(export_kernel, dim3((unsigned)((total + kExportBlock - 1) / kExportBlock)), dim3(kExportBlock), 0,
+                     stream, t, d_keys, d_row, d_last_seen, d_slot, max_n, touched_only);
   return hipGetLastError();
 }
 
+// A group of lanes (dim / 4 rounded up to a power of two) copies one row, four elements per lane.
 template <typename E>
 __global__ __launch_bounds__(256) void export_values_kernel(TableView t, const int32_t* rows, uint64_t n, float* values,
-                                                            float* acc) {
+                                                            float* acc, uint32_t group_log2) {
   const uint64_t g = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (g >= n * t.dim) return;
-  const uint64_t i = g / t.dim;
-  const uint32_t j = (uint32_t)(g % t.dim);
+  const uint64_t i = g >> group_log2;
+  const uint32_t l = (uint32_t)g & ((1u << group_log2) - 1u);
+  if (i >= n || l * 4 >= t.dim) return;
   const uint32_t r = (uint32_t)rows[i];
-  const E* src = reinterpret_cast<const E*>(t.rows);
+  const E* src = reinterpret_cast<const E*>(t.rows) + (uint64_t)r * t.dim + l * 4;
   if (values) {
-    if constexpr (sizeof(E) == 2)
-      values[g] = bf16_to_f32((uint16_t)src[(uint64_t)r * t.dim + j]);
-    else
-      values[g] = (float)src[(uint64_t)r * t.dim + j];
+    float4 v;
+    if constexpr (sizeof(E) == 2) {
+      const uint2 u = *reinterpret_cast<const uint2*>(src);
+      v = make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xFFFF0000u), __uint_as_float(u.y << 16),
+                      __uint_as_float(u.y & 0xFFFF0000u));
+    } else {
+      v = *reinterpret_cast<const float4*>(src);
+    }
+    *reinterpret_cast<float4*>(values + i * t.dim + l * 4) = v;
   }
-  if (acc && j == 0) acc[i] = t.state[r].acc;
+  if (acc && l == 0) acc[i] = t.state[r].acc;
 }
 
 hipError_t launch_export_values(const TableView& t, const int32_t* d_row, uint64_t n, float* d_values, float* d_acc,
                                 hipStream_t stream) {
   if (n == 0) return hipSuccess;
-  const uint64_t total = n * t.dim;
+  uint32_t group_log2 = 0;
+  while ((4u << group_log2) < t.dim) ++group_log2;
+  const uint64_t total = n << group_log2;
   dim3 block(256), grid((unsigned)((total + 255) / 256));
   if (t.bf16)
-    hipLaunchKernelGGL(export_values_kernel<uint16_t>, grid, block, 0, stream, t, d_row, n, d_values, d_acc);
+    hipLaunchKernelGGL(export_values_kernel<uint16_t>, grid, block, 0, stream, t, d_row, n, d_values, d_acc, group_log2);
   else
-    hipLaunchKernelGGL(export_values_kernel<float>, grid, block, 0, stream, t, d_row, n, d_values, d_acc);
+    hipLaunchKernelGGL(export_values_kernel<float>, grid, block, 0, stream, t, d_row, n, d_values, d_acc, group_log2);
   return hipGetLastError();
 }
 
