@@ -25,6 +25,14 @@ from paper_2209_07663_amd import synth  # noqa: E402
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 SECTOR = 32             # bytes: smallest HBM access counted for a random 4/8-byte word
 
+# HBM bytes per launch (read + written) from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this command
+# on the default workload, scaled by the factors a plain 1 GiB copy gives (2.0 and 1.0); the runs and
+# the table are in profiles/bench_cfg2_full_step.md.  Workloads that were not profiled report null.
+MEASURED_TRAFFIC = {
+    "cfg2": {"probe_count": 881.1e6, "seg_reduce": 972.1e6, "gather_pool": 503.0e6, "admit_elect": 359.7e6,
+             "sort_scatter": 149.9e6, "sort_hist": 68.8e6, "insert": 124.2e6},
+}
+
 
 def _gen(args):
     wl_name, seed, step = args
@@ -305,7 +313,8 @@ def main():
         dom = max(prof, key=lambda k: prof[k][0])
         achieved = algorithmic_bytes(dom, mean, wl) / (prof[dom][0] / prof[dom][1]) / 1e6
         roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None}
+                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                    "traffic": MEASURED_TRAFFIC.get(wl.name, {}).get(dom)}
         sb = step_bytes(mean, wl, sweep_every)
         step_roof = {"algorithmic_bytes_per_step": int(sb),
                      "achieved_GBps": round(sb / (np.median(step_ms) * 1e-3) / 1e9, 1),
