@@ -123,7 +123,9 @@ struct Params {
   bool bf16 = false;            // rows stored in bfloat16
   uint64_t n_filter = 0;        // number of occurrence counters (power of two)
   int lg_filter = 0;
-  uint64_t s_h0 = 0, s_h1 = 0, s_filter = 0, s_init = 0;
+  uint32_t filter_hashes = 1;   // counters per key (1..4): the key's count is the MINIMUM of them
+  uint64_t s_h0 = 0, s_h1 = 0, s_init = 0;
+  uint64_t s_filter[4] = {0, 0, 0, 0};
 };
 
 // Occurrence counter word, canonical form: (step & 0xFFFFFF) << 8 | count, count saturates at
@@ -196,7 +198,10 @@ class Model {
   virtual uint64_t insert_failures() const { return 0; }
   virtual uint64_t max_chain() const { return 0; }
   const Params& params() const { return p_; }
-  uint64_t filter_index(uint64_t key) const { return top_bits(mix64(key ^ p_.s_filter), p_.lg_filter); }
+  // counter j of a key (j < filter_hashes); every hash addresses the whole array
+  uint64_t filter_index(uint64_t key, uint32_t j = 0) const {
+    return top_bits(mix64(key ^ p_.s_filter[j]), p_.lg_filter);
+  }
 
  protected:
   // new table geometry and placement salts; returns log2 of the growth factor of the counter array
@@ -231,14 +236,17 @@ class BruteForceModel final : public Model {
     for (uint64_t i = 0; i < n; ++i) {
       uint64_t k = (uint64_t)keys[i];
       if (k == kEmptyKey || was_hit[i]) continue;
-      uint32_t& w = filter_[filter_index(k)];
-      w = filter_touch(w, step, p_.expire_steps);
+      for (uint32_t j = 0; j < p_.filter_hashes; ++j) {  // one touch per counter of the key
+        uint32_t& w = filter_[filter_index(k, j)];
+        w = filter_touch(w, step, p_.expire_steps);
+      }
     }
-    // ... then admission
+    // ... then admission: the key's count is the smallest of its counters
     for (uint64_t i = 0; i < n; ++i) {
       uint64_t k = (uint64_t)keys[i];
       if (k == kEmptyKey || was_hit[i] || table_.count(k)) continue;
-      uint32_t count = filter_[filter_index(k)] & 255u;
+      uint32_t count = 255u;
+      for (uint32_t j = 0; j < p_.filter_hashes; ++j) count = std::min(count, filter_[filter_index(k, j)] & 255u);
       if (count >= p_.freq_threshold) init_entry(p_, k, step, &table_[k]);
     }
     for (uint64_t i = 0; i < n; ++i) {
@@ -413,13 +421,17 @@ class CuckooModel final : public Model {
     for (uint64_t i = 0; i < n; ++i) {
       uint64_t k = (uint64_t)keys[i];
       if (k == kEmptyKey || was_hit[i]) continue;
-      uint32_t& w = filter_[filter_index(k)];
-      w = filter_touch(w, step, p_.expire_steps);
+      for (uint32_t j = 0; j < p_.filter_hashes; ++j) {
+        uint32_t& w = filter_[filter_index(k, j)];
+        w = filter_touch(w, step, p_.expire_steps);
+      }
     }
     for (uint64_t i = 0; i < n; ++i) {  // ascending first-occurrence order
       uint64_t k = (uint64_t)keys[i];
       if (k == kEmptyKey || was_hit[i] || find(k)) continue;
-      if ((filter_[filter_index(k)] & 255u) < p_.freq_threshold) continue;
+      uint32_t count = 255u;
+      for (uint32_t j = 0; j < p_.filter_hashes; ++j) count = std::min(count, filter_[filter_index(k, j)] & 255u);
+      if (count < p_.freq_threshold) continue;
       if (size_ >= p_.capacity) { ++insert_failures_; continue; }  // no row left
       int32_t e = alloc_entry();
       init_entry(p_, k, step, &pool_[e]);
@@ -574,12 +586,14 @@ bool is_pow2(uint64_t v) { return v && !(v & (v - 1)); }
 extern "C" {
 
 // kind: 0 = R0 (std::map definition), 1 = R1 (cuckoo).  bucket / max_kicks / hash_mode only
-// matter for R1.  n_filter = number of occurrence counters (power of two).  Returns NULL on a
-// bad argument.
+// matter for R1.  n_filter = number of occurrence counters (power of two); filter_hashes = counters
+// per key, 1..4 (1: the plain hashed counter array; more: the count of a key is the minimum of its
+// counters, the probabilistic filter of section 2.1 read as a counting filter with several hashes).
+// Returns NULL on a bad argument.
 void* orc_create(int kind, uint64_t capacity, uint32_t dim, uint64_t seed, uint32_t freq_threshold,
                  uint32_t expire_steps, int bf16, uint64_t n_filter, uint32_t bucket,
-                 uint32_t max_kicks, int hash_mode) {
-  if (dim == 0 || freq_threshold > 255 || !is_pow2(n_filter)) return nullptr;
+                 uint32_t max_kicks, int hash_mode, uint32_t filter_hashes) {
+  if (dim == 0 || freq_threshold > 255 || !is_pow2(n_filter) || filter_hashes < 1 || filter_hashes > 4) return nullptr;
   Params p;
   p.capacity = capacity;
   p.dim = dim;
@@ -591,7 +605,9 @@ void* orc_create(int kind, uint64_t capacity, uint32_t dim, uint64_t seed, uint3
   p.lg_filter = log2_exact(n_filter);
   p.s_h0 = salt(placement_seed(seed, 0), 0);
   p.s_h1 = salt(placement_seed(seed, 0), 1);
-  p.s_filter = salt(seed, 2);
+  p.filter_hashes = filter_hashes;
+  p.s_filter[0] = salt(seed, 2);
+  for (int j = 1; j < 4; ++j) p.s_filter[j] = salt(seed, 7 + j);
   p.s_init = salt(seed, 3);
   auto* h = new Handle;
   if (kind == 0) {
@@ -660,6 +676,9 @@ void orc_filter_read(void* hv, uint64_t first, uint64_t count, uint32_t* out) {
   for (uint64_t i = 0; i < count; ++i) out[i] = h->m->filter_word(first + i);
 }
 uint64_t orc_filter_index(void* hv, int64_t key) { return ((Handle*)hv)->m->filter_index((uint64_t)key); }
+uint64_t orc_filter_index_j(void* hv, int64_t key, uint32_t j) {
+  return ((Handle*)hv)->m->filter_index((uint64_t)key, j);
+}
 
 uint64_t orc_insert_failures(void* hv) { return ((Handle*)hv)->m->insert_failures(); }
 uint64_t orc_max_chain(void* hv) { return ((Handle*)hv)->m->max_chain(); }

@@ -36,7 +36,7 @@ def oracle_lib():
         lib = ctypes.CDLL(build_oracle())
         lib.orc_create.restype = _vp
         lib.orc_create.argtypes = [ctypes.c_int, _u64, _u32, _u64, _u32, _u32, ctypes.c_int, _u64, _u32, _u32,
-                                   ctypes.c_int]
+                                   ctypes.c_int, _u32]
         lib.orc_destroy.argtypes = [_vp]
         lib.orc_lookup_or_insert.argtypes = [_vp, _vp, _u64, _u32, _vp]
         lib.orc_pool.argtypes = [_vp, _vp, _vp, _u64, _vp]
@@ -50,6 +50,8 @@ def oracle_lib():
         lib.orc_filter_read.argtypes = [_vp, _u64, _u64, _vp]
         lib.orc_filter_index.restype = _u64
         lib.orc_filter_index.argtypes = [_vp, ctypes.c_int64]
+        lib.orc_filter_index_j.restype = _u64
+        lib.orc_filter_index_j.argtypes = [_vp, ctypes.c_int64, _u32]
         lib.orc_insert_failures.restype = _u64
         lib.orc_insert_failures.argtypes = [_vp]
         lib.orc_max_chain.restype = _u64
@@ -90,12 +92,13 @@ class Oracle:
     """One table.  Arrays are numpy, C-contiguous; keys int64, offsets int64, grads float32."""
 
     def __init__(self, capacity, dim, seed, freq_threshold=1, expire_steps=0, bf16=False, kind="cuckoo",
-                 n_filter=None, bucket=8, max_kicks=512, hash_mode=0):
+                 n_filter=None, bucket=8, max_kicks=512, hash_mode=0, filter_hashes=1):
         self.lib = oracle_lib()
         self.capacity, self.dim = int(capacity), int(dim)
         self.n_filter = int(n_filter) if n_filter is not None else 4 * self.capacity
         self.h = self.lib.orc_create({"map": 0, "cuckoo": 1}[kind], self.capacity, self.dim, seed, freq_threshold,
-                                     expire_steps, int(bf16), self.n_filter, bucket, max_kicks, hash_mode)
+                                     expire_steps, int(bf16), self.n_filter, bucket, max_kicks, hash_mode,
+                                     filter_hashes)
         if not self.h:
             raise ValueError("oracle: bad table parameters")
 
@@ -151,8 +154,8 @@ class Oracle:
         self.lib.orc_filter_read(self.h, first, count, _ptr(out))
         return out
 
-    def filter_index(self, key):
-        return self.lib.orc_filter_index(self.h, int(key))
+    def filter_index(self, key, j=0):
+        return self.lib.orc_filter_index_j(self.h, int(key), j)
 
     # -- maintenance operations --------------------------------------------------------------
 

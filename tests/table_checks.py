@@ -49,10 +49,11 @@ def bucket_of(side, keys, capacity, bucket, seed, generation=0):
     return top_bits(mix64(keys ^ salt(placement_seed(seed, generation), side)), lg)
 
 
-def filter_index(keys, n_filter, seed):
+def filter_index(keys, n_filter, seed, j=0):
+    """Counter j of each key: salt 2 for the first hash, salts 8, 9, 10 for the others."""
     lg = int(n_filter).bit_length() - 1
     keys = np.asarray(keys).astype(U64)
-    return top_bits(mix64(keys ^ salt(seed, 2)), lg)
+    return top_bits(mix64(keys ^ salt(seed, 2 if j == 0 else 7 + j)), lg)
 
 
 def init_rows(keys, dim, seed):
