@@ -74,6 +74,19 @@ int mono_table_create(mono_table** out, uint64_t capacity, uint32_t dim, uint64_
                       uint32_t expire_steps, uint32_t flags, uint64_t max_ids, uint64_t max_bags, void* d_arena,
                       size_t arena_bytes, void* stream);
 
+/* The same with the occurrence filter spelled out (section 2.1 names two filters: a threshold on
+ * occurrences and "a probabilistic filter" that saves memory; here both are one array of counters):
+ *   filter_hashes  counters per key, 1..4.  Every missed occurrence of a key bumps all of them and the
+ *                  key's count is their minimum (a counting filter with several hashes: it can
+ *                  over-count when keys share counters, never under-count).  1 = mono_table_create.
+ *   filter_log2    log2 of the number of counters (4..34), or 0 for 4 * capacity (mono_table_create).
+ * mono_table_bytes_ex is the matching size query; mono_filter_export / _import cover 2^filter_log2 words. */
+size_t mono_table_bytes_ex(uint64_t capacity, uint32_t dim, uint32_t flags, uint64_t max_ids, uint64_t max_bags,
+                           uint32_t filter_log2);
+int mono_table_create_ex(mono_table** out, uint64_t capacity, uint32_t dim, uint64_t seed, uint32_t freq_threshold,
+                         uint32_t expire_steps, uint32_t flags, uint64_t max_ids, uint64_t max_bags,
+                         uint32_t filter_hashes, uint32_t filter_log2, void* d_arena, size_t arena_bytes, void* stream);
+
 /* Frees the table (synchronises the device first).  The caller's arena, if any, is not freed. */
 int mono_table_destroy(mono_table* t);
 
@@ -145,7 +158,8 @@ int mono_filter_import(mono_table* t, const uint32_t* d_words, uint64_t first, u
 
 /* Rehash / grow (section 2.1: a rehash answers an insertion that runs into a cycle; the table is
  * meant to be adjusted elastically).  `dst` is a table just created with the same dim, flags, seed,
- * freq_threshold and expire_steps as `src`, a capacity >= src's, and not yet used.  Every key of
+ * freq_threshold, expire_steps and filter_hashes as `src`, a capacity >= src's with the number of
+ * counters grown by the same factor, and not yet used.  Every key of
  * src (its overflow stash included) is inserted into dst under the hash functions h0 / h1 of rehash
  * `generation` (0 = the functions a new table starts with; any other value gives fresh ones); rows
  * keep their indices, values, accumulators, last-seen steps and touched marks; the free-row stack
@@ -169,7 +183,7 @@ int mono_table_export(mono_table* t, int64_t* d_keys, int32_t* d_row, uint32_t* 
                       float* d_values, float* d_acc, uint64_t max_n, uint64_t* h_n, void* stream);
 
 /* Occurrence counters [first, first + count) in canonical form (step & 0xFFFFFF) << 8 | min(count, 255).
- * There are 4 * capacity counters. */
+ * There are 4 * capacity counters unless mono_table_create_ex said otherwise. */
 int mono_filter_export(mono_table* t, uint32_t* d_words, uint64_t first, uint64_t count, void* stream);
 
 /* Benchmark instrumentation.  While enabled, every kernel launched for this table is bracketed by

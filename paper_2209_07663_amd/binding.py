@@ -27,6 +27,9 @@ SYMBOLS = {
     "mono_table_bytes": (ctypes.c_size_t, [_u64, _u32, _u32, _u64, _u64]),
     "mono_table_create": (ctypes.c_int, [ctypes.POINTER(_vp), _u64, _u32, _u64, _u32, _u32, _u32, _u64, _u64, _vp,
                                          ctypes.c_size_t, _vp]),
+    "mono_table_bytes_ex": (ctypes.c_size_t, [_u64, _u32, _u32, _u64, _u64, _u32]),
+    "mono_table_create_ex": (ctypes.c_int, [ctypes.POINTER(_vp), _u64, _u32, _u64, _u32, _u32, _u32, _u64, _u64, _u32,
+                                            _u32, _vp, ctypes.c_size_t, _vp]),
     "mono_table_destroy": (ctypes.c_int, [_vp]),
     "mono_lookup_or_insert": (ctypes.c_int, [_vp, _vp, _u64, _u32, _vp, _vp]),
     "mono_gather_pool": (ctypes.c_int, [_vp, _vp, _u64, _vp, _u64, _vp, _vp]),
@@ -88,7 +91,7 @@ class Table:
     """One collisionless embedding table on the current device.  Methods carry the C-ABI names."""
 
     def __init__(self, capacity, dim, seed, freq_threshold=1, expire_steps=0, bf16=False, max_ids=1 << 20,
-                 max_bags=None, device="cuda:0"):
+                 max_bags=None, device="cuda:0", filter_hashes=1, filter_log2=0):
         self.lib = load_library()
         self.capacity, self.dim, self.bf16 = int(capacity), int(dim), bool(bf16)
         self.seed, self.freq_threshold, self.expire_steps = int(seed), int(freq_threshold), int(expire_steps)
@@ -96,15 +99,19 @@ class Table:
         self.max_bags = int(max_bags) if max_bags is not None else self.max_ids
         self.device = torch.device(device)
         flags = MONO_ROWS_BF16 if bf16 else MONO_ROWS_FP32
-        nbytes = self.lib.mono_table_bytes(self.capacity, self.dim, flags, self.max_ids, self.max_bags)
+        self.filter_hashes, self.filter_log2 = int(filter_hashes), int(filter_log2)
+        self.n_filter = (1 << self.filter_log2) if self.filter_log2 else 4 * self.capacity
+        nbytes = self.lib.mono_table_bytes_ex(self.capacity, self.dim, flags, self.max_ids, self.max_bags,
+                                              self.filter_log2)
         if nbytes == 0:
             raise MonoError("mono_table_bytes: invalid table shape")
         self.arena = torch.empty(nbytes, dtype=torch.uint8, device=self.device)  # torch owns the memory
         h = _vp()
         with torch.cuda.device(self.device):
-            _check(self.lib.mono_table_create(ctypes.byref(h), self.capacity, self.dim, seed, freq_threshold,
-                                              expire_steps, flags, self.max_ids, self.max_bags,
-                                              self.arena.data_ptr(), nbytes, _stream()), "mono_table_create")
+            _check(self.lib.mono_table_create_ex(ctypes.byref(h), self.capacity, self.dim, seed, freq_threshold,
+                                                 expire_steps, flags, self.max_ids, self.max_bags,
+                                                 self.filter_hashes, self.filter_log2, self.arena.data_ptr(), nbytes,
+                                                 _stream()), "mono_table_create_ex")
         self.h = h
 
     def close(self):
@@ -232,8 +239,10 @@ class Table:
 
     def rehashed(self, new_capacity, generation):
         """A new table of `new_capacity` >= capacity holding this table's contents (this one stays as it is)."""
+        grown = self.n_filter * (new_capacity // self.capacity)          # the counters grow with the table
         dst = Table(new_capacity, self.dim, self.seed, self.freq_threshold, self.expire_steps, self.bf16,
-                    max_ids=self.max_ids, max_bags=self.max_bags, device=self.device)
+                    max_ids=self.max_ids, max_bags=self.max_bags, device=self.device,
+                    filter_hashes=self.filter_hashes, filter_log2=grown.bit_length() - 1)
         dst.mono_table_migrate(self, generation)
         return dst
 
@@ -248,7 +257,7 @@ class Table:
         return {names[i].decode(): (ms[i], int(cnt[i])) for i in range(n.value)}
 
     def mono_filter_export(self, first=0, count=None):
-        count = 4 * self.capacity - first if count is None else count
+        count = self.n_filter - first if count is None else count
         words = torch.empty(count, dtype=torch.int32, device=self.device)
         _check(self.lib.mono_filter_export(self.h, _p(words), first, count, _stream()), "mono_filter_export")
         return words.cpu().numpy().view("uint32")

@@ -81,13 +81,15 @@ struct TableView {
   uint64_t n_buckets;        // per sub-table
   uint64_t n_filter;
   uint64_t dset_mask;
-  uint64_t s_h0, s_h1, s_filter, s_init, s_dedup;
+  uint64_t s_h0, s_h1, s_init, s_dedup;
+  uint64_t s_filter[4];      // one salt per counter hash
   uint32_t bucket_shift;     // 64 - log2(n_buckets)   (64 means: single bucket)
   uint32_t filter_shift;     // 64 - log2(n_filter)
   uint32_t dim;
   uint32_t freq_threshold;
   uint32_t expire_steps;
   uint32_t bf16;
+  uint32_t filter_hashes;    // counters per key (1..4); the key's count is their minimum
   uint32_t sync_epoch;       // current synchronisation window (>= 1); rows with touch == sync_epoch are "touched"
 };
 
@@ -107,8 +109,8 @@ __device__ inline uint64_t bucket_index(const TableView& t, int side, uint64_t k
   return shr_or_zero(h, t.bucket_shift) + (side == 0 ? 0 : t.n_buckets);
 }
 
-__device__ inline uint64_t filter_index(const TableView& t, uint64_t key) {
-  return shr_or_zero(mix64(key ^ t.s_filter), t.filter_shift);
+__device__ inline uint64_t filter_index(const TableView& t, uint64_t key, uint32_t j = 0) {
+  return shr_or_zero(mix64(key ^ t.s_filter[j]), t.filter_shift);
 }
 
 // Initial value of element j of the row of `key`: uniform on a 2^-27 grid in [-2^-4, 2^-4).

@@ -33,8 +33,8 @@
 
 namespace mono {
 
-__device__ inline void touch_counter(const TableView& t, uint64_t key, uint32_t step, uint32_t times) {
-  unsigned long long* w = &t.filter[filter_index(t, key)];
+// one counter word: `times` occurrences at `step`
+__device__ inline void touch_word(const TableView& t, unsigned long long* w, uint32_t step, uint32_t times) {
   if (t.expire_steps == 0) {
     // nothing ever ages: the stamp only moves forward and the count only grows, so two atomics
     // whose results nobody waits for do it (low half = count, high half = last step)
@@ -54,6 +54,12 @@ __device__ inline void touch_counter(const TableView& t, uint64_t key, uint32_t 
     cur = old;
   }
   atomicAdd(w, (unsigned long long)times);  // unsaturated; read as min(count, 255)
+}
+
+// every counter of the key (section 2.1's probabilistic filter read as a counting filter with
+// filter_hashes hashes; two hashes of a key that fall on one counter touch it twice, as the oracle does)
+__device__ inline void touch_counter(const TableView& t, uint64_t key, uint32_t step, uint32_t times) {
+  for (uint32_t j = 0; j < t.filter_hashes; ++j) touch_word(t, &t.filter[filter_index(t, key, j)], step, times);
 }
 
 // Cooperative probe.  A lane owns one key; the eight lanes of a group then visit the group's eight
@@ -120,7 +126,11 @@ __global__ __launch_bounds__(kProbeBlock) void probe_count_kernel(TableView t, c
   // err on the side of probing.
   bool maybe = live;
   if (t.expire_steps == 0 && live && !restore) {
-    const uint32_t cnt = reinterpret_cast<const uint32_t*>(&t.filter[filter_index(t, k)])[0];
+    uint32_t cnt = reinterpret_cast<const uint32_t*>(&t.filter[filter_index(t, k)])[0];
+    for (uint32_t j = 1; j < t.filter_hashes; ++j) {  // the key's count is the smallest of its counters
+      const uint32_t c = reinterpret_cast<const uint32_t*>(&t.filter[filter_index(t, k, j)])[0];
+      cnt = c < cnt ? c : cnt;
+    }
     maybe = cnt >= (t.freq_threshold > 1u ? t.freq_threshold : 1u);
   }
   const uint64_t b0 = bucket_index(t, 0, k), b1 = bucket_index(t, 1, k);
@@ -186,12 +196,15 @@ __global__ __launch_bounds__(256) void admit_elect_kernel(TableView t, const int
     const uint64_t k = (uint64_t)keys[i];
     uint32_t cnt = 255u;  // a snapshot record is admitted whatever its counter says
     if (!restore) {
-      unsigned long long* w = &t.filter[filter_index(t, k)];
-      const unsigned long long word = *w;
-      cnt = (uint32_t)word;
-      if (cnt > 255u) {  // keep the unsaturated count from ever wrapping
-        atomicMin(w, (word & 0xFFFFFFFF00000000ull) | 255ull);
-        cnt = 255u;
+      for (uint32_t j = 0; j < t.filter_hashes; ++j) {  // smallest of the key's counters
+        unsigned long long* w = &t.filter[filter_index(t, k, j)];
+        const unsigned long long word = *w;
+        uint32_t c = (uint32_t)word;
+        if (c > 255u) {  // keep the unsaturated count from ever wrapping
+          atomicMin(w, (word & 0xFFFFFFFF00000000ull) | 255ull);
+          c = 255u;
+        }
+        cnt = c < cnt ? c : cnt;
       }
     }
     if (cnt < t.freq_threshold) {

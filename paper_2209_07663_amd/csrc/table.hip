@@ -43,6 +43,15 @@ bool valid_shape(uint64_t capacity, uint32_t dim, uint32_t flags, uint64_t max_i
          flags <= MONO_ROWS_BF16 && max_ids >= 1 && max_ids <= (1ull << 28) && max_bags >= 1 && max_bags <= max_ids + 1;
 }
 
+// number of occurrence counters: 2^filter_log2, or 4 * capacity when filter_log2 == 0
+uint64_t filter_size(uint64_t capacity, uint32_t filter_log2) {
+  return filter_log2 ? 1ull << filter_log2 : 4 * capacity;
+}
+bool valid_filter(uint64_t capacity, uint32_t filter_hashes, uint32_t filter_log2) {
+  (void)capacity;
+  return filter_hashes >= 1 && filter_hashes <= 4 && (filter_log2 == 0 || (filter_log2 >= 4 && filter_log2 <= 34));
+}
+
 uint64_t dedup_size(uint64_t max_ids) {
   uint64_t s = 64;
   while (s < 2 * max_ids) s <<= 1;
@@ -51,14 +60,14 @@ uint64_t dedup_size(uint64_t max_ids) {
 
 // Carves the arena; with base == nullptr only measures.  Returns the bytes used.
 size_t layout(mono_table* t, char* base, uint64_t capacity, uint32_t dim, uint32_t flags, uint64_t max_ids,
-              uint64_t max_bags) {
+              uint64_t max_bags, uint64_t n_filter) {
   size_t off = 0;
   auto take = [&](size_t bytes) {
     char* p = base ? base + off : nullptr;
     off += align_up(bytes);
     return p;
   };
-  const uint64_t n_buckets = capacity / 2 / kBucket, n_filter = 4 * capacity, dset = dedup_size(max_ids);
+  const uint64_t n_buckets = capacity / 2 / kBucket, dset = dedup_size(max_ids);
   const size_t esize = flags == MONO_ROWS_BF16 ? 2 : 4;
   char* buckets = take(2 * n_buckets * sizeof(Bucket));
   char* filter = take(n_filter * sizeof(unsigned long long));
@@ -124,19 +133,33 @@ const char* mono_strerror(int err) {
   }
 }
 
+size_t mono_table_bytes_ex(uint64_t capacity, uint32_t dim, uint32_t flags, uint64_t max_ids, uint64_t max_bags,
+                           uint32_t filter_log2) {
+  if (!valid_shape(capacity, dim, flags, max_ids, max_bags) || !valid_filter(capacity, 1, filter_log2)) return 0;
+  return layout(nullptr, nullptr, capacity, dim, flags, max_ids, max_bags, filter_size(capacity, filter_log2));
+}
+
 size_t mono_table_bytes(uint64_t capacity, uint32_t dim, uint32_t flags, uint64_t max_ids, uint64_t max_bags) {
-  if (!valid_shape(capacity, dim, flags, max_ids, max_bags)) return 0;
-  return layout(nullptr, nullptr, capacity, dim, flags, max_ids, max_bags);
+  return mono_table_bytes_ex(capacity, dim, flags, max_ids, max_bags, 0);
 }
 
 int mono_table_create(mono_table** out, uint64_t capacity, uint32_t dim, uint64_t seed, uint32_t freq_threshold,
                       uint32_t expire_steps, uint32_t flags, uint64_t max_ids, uint64_t max_bags, void* d_arena,
                       size_t arena_bytes, void* stream) {
+  return mono_table_create_ex(out, capacity, dim, seed, freq_threshold, expire_steps, flags, max_ids, max_bags, 1, 0,
+                              d_arena, arena_bytes, stream);
+}
+
+int mono_table_create_ex(mono_table** out, uint64_t capacity, uint32_t dim, uint64_t seed, uint32_t freq_threshold,
+                         uint32_t expire_steps, uint32_t flags, uint64_t max_ids, uint64_t max_bags,
+                         uint32_t filter_hashes, uint32_t filter_log2, void* d_arena, size_t arena_bytes, void* stream) {
   if (!out) return MONO_EINVAL;
   *out = nullptr;
-  if (!valid_shape(capacity, dim, flags, max_ids, max_bags) || freq_threshold > 255 || expire_steps >= (1u << 24))
+  if (!valid_shape(capacity, dim, flags, max_ids, max_bags) || freq_threshold > 255 || expire_steps >= (1u << 24) ||
+      !valid_filter(capacity, filter_hashes, filter_log2))
     return MONO_EINVAL;
-  const size_t need = layout(nullptr, nullptr, capacity, dim, flags, max_ids, max_bags);
+  const uint64_t n_filter = filter_size(capacity, filter_log2);
+  const size_t need = layout(nullptr, nullptr, capacity, dim, flags, max_ids, max_bags, n_filter);
   if (d_arena && (arena_bytes < need || ((uintptr_t)d_arena & 255))) return MONO_EINVAL;
   mono_table* t = new (std::nothrow) mono_table();
   if (!t) return MONO_ENOMEM;
@@ -153,11 +176,12 @@ int mono_table_create(mono_table** out, uint64_t capacity, uint32_t dim, uint64_
     }
     t->owned_arena = base;
   }
-  layout(t, base, capacity, dim, flags, max_ids, max_bags);
+  layout(t, base, capacity, dim, flags, max_ids, max_bags, n_filter);
   TableView& v = t->view;
   v.capacity = capacity;
   v.n_buckets = capacity / 2 / kBucket;
-  v.n_filter = 4 * capacity;
+  v.n_filter = n_filter;
+  v.filter_hashes = filter_hashes;
   t->dset_size = dedup_size(max_ids);
   v.dset_mask = t->dset_size - 1;
   uint64_t s[5];
@@ -165,7 +189,8 @@ int mono_table_create(mono_table** out, uint64_t capacity, uint32_t dim, uint64_
   t->seed = seed;
   v.s_h0 = s[0];
   v.s_h1 = s[1];
-  v.s_filter = s[2];
+  v.s_filter[0] = s[2];
+  for (int j = 1; j < 4; ++j) v.s_filter[j] = salt(seed, 7 + j);
   v.s_init = s[3];
   v.s_dedup = s[4];
   v.bucket_shift = 64u - (uint32_t)log2u(v.n_buckets);
@@ -336,7 +361,9 @@ int mono_table_migrate(mono_table* dst, mono_table* src, uint32_t generation, vo
   const TableView& a = src->view;
   TableView& b = dst->view;
   if (b.capacity < a.capacity || b.dim != a.dim || b.bf16 != a.bf16 || dst->seed != src->seed ||
-      b.freq_threshold != a.freq_threshold || b.expire_steps != a.expire_steps || dst->epoch != 0 || dst->last_step != 0)
+      b.freq_threshold != a.freq_threshold || b.expire_steps != a.expire_steps || dst->epoch != 0 ||
+      dst->last_step != 0 || b.filter_hashes != a.filter_hashes ||
+      b.n_filter * a.capacity != a.n_filter * b.capacity)  // the counter array grows with the table
     return MONO_EINVAL;  // dst must be a fresh table with the same parameters
   hipStream_t s = (hipStream_t)stream;
   Control c;
