@@ -1,8 +1,9 @@
 """Full-size configurations on the device, in the launch configuration bench.py times.
 
-configs[1] runs whole against the oracle (it finishes a step in a few seconds).  configs[2] and
-configs[4] are too large for that, so they are checked on sampled outputs recomputed one by one
-in numpy from the device's own table dumps, plus the invariants that hold at any size.
+configs[1] runs whole against the oracle (it finishes a step in a few seconds).  configs[2],
+configs[3] (filled to load 0.9 first) and configs[4] are too large for that, so they are checked on
+sampled outputs recomputed one by one in numpy from the device's own table dumps, plus the invariants
+that hold at any size.
 """
 import numpy as np
 import pytest
@@ -128,4 +129,67 @@ def test_large_configs_sampled(name, samples):
         seen_before = set(tab.mono_table_export(with_values=False)["keys"].tolist())
         st = tab.mono_table_stats()
         assert st["n_insert_failed"] == 0 and st["n_lost"] == 0 and st["n_full"] == 0
+    tab.close()
+
+
+@pytest.mark.timeout(900)
+def test_config4_filled_to_load_09_then_streaming_steps():
+    """configs[3] at full size: the 0.9 * capacity hottest IDs are admitted first (threshold 5: each
+    is looked up five times), then drifting batches with a sweep every step.  30 M keys are too many
+    for the oracle, so: placement, uniqueness and conservation on the whole dump, the admission rule
+    and initial rows on samples, no failed eviction chain, and the same sampled checks per step."""
+    dev = torch.device("cuda:0")
+    wl, seed = synth.CONFIGS["cfg4"], 4
+    drift = synth.DriftMap(wl, seed)
+    hot = synth.hottest_ids(wl, int(0.9 * wl.capacity), drift)
+    assert np.unique(hot).shape[0] == hot.shape[0]
+    batches = [synth.make_batch(wl, seed, s, with_grad=True, drift=drift) for s in range(1, 4)]
+    max_ids = max(1 << 23, max(b["keys"].shape[0] for b in batches))
+    tab = _table(wl, seed, max_ids, dev)
+    rows = torch.empty(max_ids, dtype=torch.int32, device=dev)
+    for lo in range(0, hot.shape[0], max_ids):
+        chunk = torch.from_numpy(hot[lo:lo + max_ids]).to(dev)
+        for rep in range(wl.freq_threshold):
+            tab.mono_lookup_or_insert(chunk, 0, rows[: chunk.shape[0]])
+        # on the fifth sighting at the latest (keys that share a counter with others get there earlier)
+        assert int((rows[: chunk.shape[0]] >= 0).sum().item()) == chunk.shape[0]
+    print("config4: filled", flush=True)
+    st = tab.mono_table_stats()
+    assert st["size"] == hot.shape[0] and st["n_insert_failed"] == 0 and st["n_lost"] == 0 and st["n_full"] == 0
+    d = tab.mono_table_export(with_values=False)
+    assert (d["keys"].view(np.uint64) == np.sort(hot.view(np.uint64))).all()
+    tc.check_placement(d, wl.capacity, 8, seed)
+    rng = np.random.default_rng(0)
+    stored = d["keys"]
+    for b in batches:
+        step = b["step"]
+        print("config4 full size, step", step, flush=True)
+        keys_h, offs_h = b["keys"], b["offsets"]
+        keys, offs = torch.from_numpy(keys_h).to(dev), torch.from_numpy(offs_h).to(dev)
+        r = tab.mono_lookup_or_insert(keys, step)
+        r_h = r.cpu().numpy()
+        present = r_h >= 0
+        was_stored = np.isin(keys_h, stored)
+        assert present[was_stored].all()                      # a stored key is always found
+        # the others: present exactly if their counter word reached the threshold (sampled)
+        cand = np.unique(keys_h[~was_stored])
+        some = rng.choice(cand, size=min(300, cand.shape[0]), replace=False)
+        widx = tc.filter_index(some, 4 * wl.capacity, seed).astype(np.int64)
+        words = np.array([tab.mono_filter_export(int(i), 1)[0] for i in widx])
+        got_in = np.isin(some, keys_h[present])
+        assert (got_in == ((words & 255) >= wl.freq_threshold)).all()
+        pooled = tab.mono_gather_pool(r, offs)
+        tab.mono_apply_grad_adagrad(r, offs, torch.from_numpy(b["grad"]).to(dev), wl.lr, wl.eps)
+        assert bool(torch.isfinite(pooled).all().item())
+        n_exp = torch.zeros(1, dtype=torch.int64, device=dev)
+        tab.mono_expire_sweep(step, n_exp, None)
+        assert int(n_exp.item()) == 0                          # nothing is 20 steps old yet
+        d = tab.mono_table_export(with_values=False)
+        tc.check_placement(d, wl.capacity, 8, seed)
+        assert np.isin(stored, d["keys"]).all()
+        assert (d["last_seen"][np.isin(d["keys"], np.unique(keys_h[present]))] == step).all()
+        stored = d["keys"]
+        st = tab.mono_table_stats()
+        assert st["size"] == stored.shape[0] and st["n_insert_failed"] == 0 and st["n_lost"] == 0 and st["n_full"] == 0
+    assert stored.shape[0] > hot.shape[0]                      # keys keep being admitted at load 0.9
     tab.close()
