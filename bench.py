@@ -73,7 +73,8 @@ def cpu_baseline(wl, seed, batches, budget_s):
 
 
 def algorithmic_bytes(kernel, s, wl):
-    """Compulsory bytes of ONE launch of `kernel` for a batch with statistics `s`."""
+    """Compulsory bytes of ONE launch of `kernel` for a batch with statistics `s`: what the kernel must move
+    if duplicates of a key were served on chip (n occurrences, u_* distinct keys, S = 32-byte sector)."""
     e = 2 if wl.bf16 else 4
     row = wl.dim * e
     n, nb = s["n"], s["n_bags"]

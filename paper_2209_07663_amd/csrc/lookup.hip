@@ -14,7 +14,7 @@
 //   resolve       duplicates of an admitted key pick up the row of the elected occurrence; one
 //                 thread settles the counters
 //
-// The same four kernels restore snapshot records (`Restore` below): every record is a forced
+// The same four kernels restore snapshot records (RestoreSource): every record is a forced
 // admission whose row, accumulator and last-seen step come from the caller instead of from
 // init(seed, key) / the current step; a record whose key is already stored is refused.  The
 // migrate kernel re-inserts every stored element of one table into another (rehash / grow).

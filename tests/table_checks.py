@@ -1,6 +1,6 @@
 """Checks that work on any table dump (the oracle's or the device library's).
 
-The hash functions are written here a third time, in numpy, from the contract in the design doc
+The hash functions are written here a third time, in numpy, from the build's written contract
 (SplitMix64 output function; salt i = (i+1)-th SplitMix64 output for the table seed; bucket =
 top bits), so that the placement invariant of section 2.1 of the paper (every stored element is in
 T0[h0(x)] or T1[h1(x)]) is checked by code that shares nothing with either implementation.

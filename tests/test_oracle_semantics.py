@@ -1,6 +1,6 @@
 """Hand-reasoned timelines and invariants for the oracle (CPU only).
 
-Each expected value below follows from the reading of the paper's section 2.1 stated in the design doc
+Each expected value below follows from the build's reading of the paper's section 2.1
 (occurrence filter: a key is admitted once its counted occurrences reach the threshold; expiry: a
 key inactive for the configured number of steps is removed), not from running the oracle.
 """
