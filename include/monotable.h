@@ -167,7 +167,8 @@ int mono_filter_import(mono_table* t, const uint32_t* d_words, uint64_t first, u
  * value of the counter its keys shared before, so no count is lost.  src is left unchanged and can
  * be destroyed afterwards.  Synchronises `stream` once (to read src's counters).
  * A caller rehashes when mono_table_stats reports stash_size > 0 or a load factor it finds too high.
- * Errors: MONO_EINVAL if dst does not match src or has been used. */
+ * Errors: MONO_EINVAL if dst does not match src or has been used (nothing was done); after
+ * MONO_EHIP the contents of dst are undefined and it can only be destroyed. */
 int mono_table_migrate(mono_table* dst, mono_table* src, uint32_t generation, void* stream);
 
 /* ---- observability / test surface (not part of the timed path; these synchronise `stream`) ---- */

@@ -1,5 +1,6 @@
 // Expiry sweep (paper section 2.1, second heuristic: IDs inactive for a configured time are
-// removed), plus the untimed maintenance kernels: initialisation, table dump, counter dump.
+// removed), plus the untimed maintenance kernels: initialisation, table dump (all keys, or only the
+// keys trained in the current synchronisation window: section 2.2.3), counter dump and counter restore.
 #include "common.h"
 #include "kernels.h"
 

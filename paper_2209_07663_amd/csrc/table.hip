@@ -375,6 +375,7 @@ int mono_table_migrate(mono_table* dst, mono_table* src, uint32_t generation, vo
   b.sync_epoch = a.sync_epoch;
   dst->generation = generation;
   dst->last_step = src->last_step;
+  dst->epoch = 1;  // dst counts as used from here on (a second migration into it is refused)
   // rows and their state keep their indices: copied position for position up to the high-water mark
   const size_t esize = a.bf16 ? 2 : 4;
   if (c.hwm) {

@@ -15,6 +15,8 @@
 //                parallel, then across groups) and applies Adagrad
 // A hot ID with 10^5..10^6 occurrences is thus reduced as chunk sums -> tile sums -> total, never
 // serially, and everything is deterministic: no floating-point atomics.
+// The store that writes a row's new accumulator also carries the number of the current
+// synchronisation window: that is the row's "touched" mark (paper section 2.2.3), at no extra cost.
 //
 // Partial-slot convention (same at chunk level in LDS and at tile level in global memory): unit u
 // has slot A = 2u ("run that started before this unit and ends inside it") and slot B = 2u + 1
