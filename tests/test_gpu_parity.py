@@ -202,3 +202,48 @@ def test_hot_key_gradient_reduction_is_pairwise(dev):
         compare_step(tab, orc, {"keys": keys_h, "offsets": offs_h, "grad": grad_h, "step": step}, dev, RTOL_F32,
                      exact_rows=False, train=True)
     tab.close()
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_seeded_random_configurations(dev, case):
+    """Combinations that no named configuration covers: a seeded draw of dim, storage type, threshold,
+    expiry, number of counter hashes, counter array size, bag lengths, key skew and padding keys."""
+    from paper_2209_07663_amd.binding import Table
+    rng = np.random.default_rng(1000 + case)
+    dim = int(rng.choice([4, 8, 12, 32, 64, 100, 256]))
+    bf16 = bool(rng.integers(0, 2))
+    thr = int(rng.choice([0, 1, 2, 3, 7]))
+    expire = int(rng.choice([0, 0, 2, 5]))
+    hashes = int(rng.choice([1, 1, 2, 4]))
+    cap = 1 << int(rng.integers(12, 16))
+    filter_log2 = int(rng.choice([0, 10, 14]))
+    n_bags = int(rng.integers(50, 3000))
+    lam = float(rng.choice([0.0, 1.0, 6.0]))
+    universe = int(rng.choice([50, 2000, 1 << 40]))
+    seed = 500 + case
+    print("case", case, dict(dim=dim, bf16=bf16, thr=thr, expire=expire, hashes=hashes, cap=cap,
+                             filter_log2=filter_log2, n_bags=n_bags, lam=lam, universe=universe), flush=True)
+    max_ids = int(n_bags * (lam + 1) * 3) + 64
+    tab = Table(cap, dim, seed, thr, expire, bf16, max_ids=max_ids, max_bags=n_bags, device=dev,
+                filter_hashes=hashes, filter_log2=filter_log2)
+    _SEEDS[id(tab)] = seed
+    orc = Oracle(cap, dim, seed, thr, expire, bf16, kind="cuckoo", n_filter=tab.n_filter, filter_hashes=hashes)
+    rtol = RTOL_BF16 if bf16 else RTOL_F32
+    for step in range(5):
+        lens = (rng.poisson(lam, size=n_bags) + (0 if rng.random() < 0.3 else 1)).astype(np.int64)   # empty bags too
+        offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+        n = int(offs[-1])
+        if n > max_ids:
+            lens[:] = 1
+            offs = np.arange(n_bags + 1, dtype=np.int64)
+            n = n_bags
+        keys = (rng.zipf(1.3, size=n) % universe).astype(np.int64) * 0x9E3779B1 % (1 << 62)
+        keys[rng.random(n) < 0.02] = -1                                                                # padding
+        grad = (rng.standard_normal((n_bags, dim)) * 0.1).astype(np.float32)
+        # at most ~half the table: a full table is a different test
+        if np.unique(keys).shape[0] * (step + 1) > cap // 2:
+            keys = keys % 997
+        compare_step(tab, orc, {"keys": keys, "offsets": offs, "grad": grad, "step": 2 * step}, dev, rtol,
+                     exact_rows=False, train=True, sweep_at=2 * step if expire else None)
+        assert (tab.mono_filter_export() == orc.filter_words()).all(), "counter words differ at step %d" % step
+    tab.close()
