@@ -16,9 +16,9 @@ struct UpdateWorkspace {
   uint32_t* part_row;   // [2 * tiles] row (+ head flag) of each partial, kNoRow if unused
 };
 
-constexpr uint32_t kSortMaxBits = 11;              // widest radix digit
+constexpr uint32_t kSortMaxBits = 8;               // widest radix digit (one thread per bin in a block of the sort)
 constexpr uint32_t kSortMaxBins = 1u << kSortMaxBits;
-constexpr uint32_t kSortItemsPerBlock = 8192;      // consecutive elements owned by one block of the sort
+constexpr uint32_t kSortItemsPerBlock = 2048;      // consecutive elements owned by one block of the sort
 constexpr int kPairsPerLane = 16;                  // sorted pairs per lane of a lane group in seg_reduce
 constexpr uint32_t kReduceTile = 256 * kPairsPerLane;  // sorted pairs reduced by one block
 
@@ -35,7 +35,8 @@ __host__ __device__ inline SortPlan make_sort_plan(uint32_t hwm) {
   SortPlan s;
   s.hwm = hwm;
   s.bits = 1;
-  while (s.bits < 32 && (hwm >> s.bits) != 0) ++s.bits;  // keys lie in [0, hwm]
+  const uint32_t top = hwm > 0 ? hwm - 1 : 0;  // sorted keys are row indices below hwm (hwm itself marks "dropped")
+  while (s.bits < 32 && (top >> s.bits) != 0) ++s.bits;
   s.passes = (s.bits + kSortMaxBits - 1) / kSortMaxBits;
   s.per = (s.bits + s.passes - 1) / s.passes;
   return s;

@@ -2,9 +2,10 @@
 // row together before the gradient reduction.
 //
 // The key width is decided ON THE DEVICE: row indices are handed out in ascending order, so every
-// row in use is below the high-water mark `hwm` kept in the control block.  bit_length(hwm) bits
-// are sorted in the fewest passes of at most kSortMaxBits bits; the host launches the worst-case
-// number of passes and the superfluous ones return at once.  Pass p reads buffer (p even ? a : b)
+// row in use is below the high-water mark `hwm` kept in the control block.  bit_length(hwm - 1)
+// bits are sorted in the fewest passes of at most kSortMaxBits = 8 bits (a block's share of a bin is
+// then long enough to leave as whole lines); the host launches the worst-case number of passes
+// and the superfluous ones return at once.  Pass p reads buffer (p even ? a : b)
 // and writes the other one.  Dropped occurrences (row -1) are left out by pass 0, which also
 // publishes the number of pairs that remain (kValidPairs slot of the control block's scratch).
 //
@@ -13,10 +14,12 @@
 //   hist     per-unit digit histogram (LDS atomics), written bin-major: hist[bin * units + unit]
 //   scan     one block per bin: exclusive scan along the units; bin totals to `totals`
 //   scatter  the block loads its elements into registers (all loads independent), counts the digits
-//            per wave in LDS, turns the counts into per-wave start offsets (bin base + the unit's
-//            scanned histogram + the waves before), then every wave ranks its elements 64 at a time
-//            by digit matching with ballots (stable: rank = number of lower lanes with the same
-//            digit) and scatters the pairs.
+//            per wave in LDS, turns the counts into start offsets inside the block, then every wave
+//            ranks its elements 64 at a time by digit matching with ballots (stable: rank = number
+//            of lower lanes with the same digit) and puts them IN ORDER into an LDS copy of the
+//            block; the copy is then written out with neighbouring threads on neighbouring
+//            elements of a bin.  (Scattering straight from the registers sends one 8-byte write
+//            per element to the L2: measured, that request rate was what bounded the pass.)
 // No kernel spins or waits for another block.
 #include "common.h"
 #include "kernels.h"
@@ -59,7 +62,10 @@ __global__ __launch_bounds__(kSortBlock) void sort_hist_kernel(const Control* __
   for (uint32_t b = threadIdx.x; b < nbins; b += kSortBlock) hist[(uint64_t)b * units + unit] = cnt[b];
 }
 
-// exclusive scan of hist[bin * units + 0 .. units) in place; total of the bin to totals[bin]
+// exclusive scan of hist[bin * units + 0 .. units) in place; total of the bin to totals[bin].
+// One block per bin; thread t owns a run of consecutive units (loaded at once, summed serially),
+// the thread sums are scanned across the block, and the run is written back.
+constexpr uint32_t kScanPerThread = 16;  // units per thread and round
 __global__ __launch_bounds__(256) void sort_scan_kernel(const Control* __restrict__ ctl, uint32_t pass,
                                                         uint32_t* __restrict__ hist, uint64_t units,
                                                         uint32_t* __restrict__ totals) {
@@ -71,10 +77,16 @@ __global__ __launch_bounds__(256) void sort_scan_kernel(const Control* __restric
   const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (threadIdx.x == 0) carry_s = 0;
   __syncthreads();
-  for (uint64_t t0 = 0; t0 < units; t0 += 256) {
-    const uint64_t i = t0 + threadIdx.x;
-    const uint32_t v = i < units ? row[i] : 0;
-    uint32_t x = v;  // inclusive wave scan
+  for (uint64_t t0 = 0; t0 < units; t0 += 256ull * kScanPerThread) {
+    const uint64_t first = t0 + (uint64_t)threadIdx.x * kScanPerThread;
+    uint32_t v[kScanPerThread];
+    uint32_t sum = 0;
+#pragma unroll
+    for (uint32_t j = 0; j < kScanPerThread; ++j) {
+      v[j] = first + j < units ? row[first + j] : 0;
+      sum += v[j];
+    }
+    uint32_t x = sum;  // inclusive wave scan of the thread sums
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
       const uint32_t y = __shfl_up(x, d);
@@ -82,11 +94,15 @@ __global__ __launch_bounds__(256) void sort_scan_kernel(const Control* __restric
     }
     if (lane == 63) wave_sum[wave] = x;
     __syncthreads();
-    uint32_t before = carry_s;
-    for (uint32_t w = 0; w < wave; ++w) before += wave_sum[w];
-    if (i < units) row[i] = before + x - v;
+    uint32_t run = carry_s + x - sum;
+    for (uint32_t w = 0; w < wave; ++w) run += wave_sum[w];
+#pragma unroll
+    for (uint32_t j = 0; j < kScanPerThread; ++j) {
+      if (first + j < units) row[first + j] = run;
+      run += v[j];
+    }
     __syncthreads();
-    if (threadIdx.x == 255) carry_s = before + x;
+    if (threadIdx.x == 255) carry_s = run;
     __syncthreads();
   }
   if (threadIdx.x == 0) totals[blockIdx.x] = carry_s;
@@ -102,11 +118,15 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
                                                                   uint2* __restrict__ dst) {
   const SortPlan plan = make_sort_plan(ctl->hwm);
   if (pass >= plan.passes) return;
-  __shared__ uint32_t lds[kSortWaves][kSortMaxBins];  // per-wave digit counts, then start offsets
-  __shared__ uint32_t bin_base[kSortMaxBins];
+  __shared__ uint2 stage[kSortItemsPerBlock];          // the block's elements in sorted order
+  __shared__ uint32_t lds[kSortWaves][kSortMaxBins];   // per-wave digit counts, then local start offsets
+  __shared__ uint32_t local_start[kSortMaxBins];       // first position of a bin in `stage`
+  __shared__ uint32_t global_start[kSortMaxBins];      // where this block's part of a bin goes in dst
+  __shared__ uint32_t wave_sum[kSortWaves];
   const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const uint64_t unit = blockIdx.x;
   const uint32_t shift = plan.shift(pass), bits = plan.width(pass), nbins = 1u << bits, mask = nbins - 1;
+  static_assert(kSortMaxBins <= kSortBlock, "one thread per bin");
 
   // 1. this wave's elements -> registers (independent, coalesced loads)
   if (pass > 0) n = ctl->scratch[kValidPairs];
@@ -121,37 +141,9 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
     if (i < n) kv[r] = pass == 0 ? make_uint2(first_key(rows, i, plan.hwm), min(bag_of[i], last_bag)) : src[i];
     if (kv[r].x >= plan.hwm) kv[r].x = 0xFFFFFFFFu;  // dropped occurrence (or past the end): left out
   }
-  for (uint32_t b = threadIdx.x; b < nbins; b += kSortBlock) {
+  if (threadIdx.x < kSortMaxBins) {
 #pragma unroll
-    for (int w = 0; w < kSortWaves; ++w) lds[w][b] = 0;
-  }
-  // bin bases: exclusive scan of the totals over the bins by wave 0, `per` consecutive bins per lane
-  if (wave == 0) {
-    const uint32_t per = (nbins + 63) / 64;
-    uint32_t local[kSortMaxBins / 64];
-    uint32_t sum = 0;
-#pragma unroll
-    for (uint32_t q = 0; q < kSortMaxBins / 64; ++q) {
-      const uint32_t b = lane * per + q;
-      local[q] = (q < per && b < nbins) ? totals[b] : 0;
-      sum += local[q];
-    }
-    uint32_t x = sum;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      const uint32_t y = __shfl_up(x, d);
-      if ((int)lane >= d) x += y;
-    }
-    uint32_t run = x - sum;
-#pragma unroll
-    for (uint32_t q = 0; q < kSortMaxBins / 64; ++q) {
-      const uint32_t b = lane * per + q;
-      if (q < per && b < nbins) {
-        bin_base[b] = run;
-        run += local[q];
-      }
-    }
-    if (pass == 0 && blockIdx.x == 0 && lane == 63) ctl->scratch[kValidPairs] = x;  // pairs that remain
+    for (int w = 0; w < kSortWaves; ++w) lds[w][threadIdx.x] = 0;
   }
   __syncthreads();
   // 2. per-wave digit counts
@@ -160,18 +152,52 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
     if (kv[r].x != 0xFFFFFFFFu) atomicAdd(&lds[wave][(kv[r].x >> shift) & mask], 1u);
   }
   __syncthreads();
-  // 3. counts -> start offset of every (wave, bin)
-  for (uint32_t b = threadIdx.x; b < nbins; b += kSortBlock) {
-    uint32_t run = bin_base[b] + hist[(uint64_t)b * units + unit];
+  // 3. thread b owns bin b: exclusive scans of the bin totals, once within the block (positions in
+  //    `stage`) and once over all bins of the pass (start of the bin in dst)
+  {
+    const uint32_t b = threadIdx.x;
+    uint32_t mine = 0, tot = 0;
+    if (b < nbins) {
 #pragma unroll
-    for (int w = 0; w < kSortWaves; ++w) {
-      const uint32_t c = lds[w][b];
-      lds[w][b] = run;
-      run += c;
+      for (int w = 0; w < kSortWaves; ++w) mine += lds[w][b];
+      tot = totals[b];
     }
+    uint32_t x = mine, y = tot;  // inclusive wave scans
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const uint32_t xs = __shfl_up(x, d), ys = __shfl_up(y, d);
+      if ((int)lane >= d) {
+        x += xs;
+        y += ys;
+      }
+    }
+    __shared__ uint32_t wave_tot[kSortWaves];
+    if (lane == 63) {
+      wave_sum[wave] = x;
+      wave_tot[wave] = y;
+    }
+    __syncthreads();
+    uint32_t before = 0, before_tot = 0;
+    for (uint32_t w = 0; w < wave; ++w) {
+      before += wave_sum[w];
+      before_tot += wave_tot[w];
+    }
+    if (b < nbins) {
+      uint32_t run = before + x - mine;  // first position of bin b within the block
+      local_start[b] = run;
+      global_start[b] = before_tot + y - tot + hist[(uint64_t)b * units + unit];
+#pragma unroll
+      for (int w = 0; w < kSortWaves; ++w) {
+        const uint32_t c = lds[w][b];
+        lds[w][b] = run;
+        run += c;
+      }
+    }
+    if (pass == 0 && blockIdx.x == 0 && threadIdx.x == kSortBlock - 1)
+      ctl->scratch[kValidPairs] = before_tot + y;  // pairs that remain
   }
   __syncthreads();
-  // 4. rank (stable) and scatter, 64 elements at a time
+  // 4. rank (stable) into `stage`, 64 elements at a time
   volatile uint32_t* off = lds[wave];
 #pragma unroll
   for (uint32_t r = 0; r < kSortRounds; ++r) {
@@ -183,10 +209,18 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
       const uint64_t vote = __ballot(bit);
       peers &= bit ? vote : ~vote;
     }
-    if (valid) dst[off[digit] + (uint32_t)__popcll(peers & lanes_below())] = kv[r];
+    if (valid) stage[off[digit] + (uint32_t)__popcll(peers & lanes_below())] = kv[r];
     __builtin_amdgcn_wave_barrier();
     if (valid && (peers & lanes_below()) == 0) off[digit] += (uint32_t)__popcll(peers);
     __builtin_amdgcn_wave_barrier();
+  }
+  __syncthreads();
+  // 5. out: neighbouring threads write neighbouring elements of a bin
+  const uint32_t total = wave_sum[0] + wave_sum[1] + wave_sum[2] + wave_sum[3];
+  for (uint32_t p = threadIdx.x; p < total; p += kSortBlock) {
+    const uint2 e = stage[p];
+    const uint32_t digit = (e.x >> shift) & mask;
+    dst[global_start[digit] + (p - local_start[digit])] = e;
   }
 }
 
