@@ -31,6 +31,17 @@ constexpr int kSortWaves = kSortBlock / 64;
 constexpr uint32_t kSortPerWave = kSortItemsPerBlock / kSortWaves;
 constexpr uint32_t kSortRounds = kSortPerWave / 64;
 
+// Lanes of the wave that hold the same digit as this lane (among the lanes with valid == true).
+__device__ inline uint64_t same_digit_lanes(uint32_t digit, uint32_t bits, bool valid) {
+  uint64_t peers = __ballot(valid);
+  for (uint32_t b = 0; b < bits; ++b) {
+    const bool bit = (digit >> b) & 1u;
+    const uint64_t vote = __ballot(bit);
+    peers &= bit ? vote : ~vote;
+  }
+  return peers;
+}
+
 // key of occurrence i in pass 0: its row, or hwm if the occurrence was dropped
 __device__ inline uint32_t first_key(const int32_t* rows, uint64_t i, uint32_t hwm) {
   const uint32_t r = (uint32_t)rows[i];
@@ -203,12 +214,7 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
   for (uint32_t r = 0; r < kSortRounds; ++r) {
     const bool valid = kv[r].x != 0xFFFFFFFFu;
     const uint32_t digit = (kv[r].x >> shift) & mask;
-    uint64_t peers = __ballot(valid);
-    for (uint32_t b = 0; b < bits; ++b) {
-      const bool bit = (digit >> b) & 1u;
-      const uint64_t vote = __ballot(bit);
-      peers &= bit ? vote : ~vote;
-    }
+    const uint64_t peers = same_digit_lanes(digit, bits, valid);
     if (valid) stage[off[digit] + (uint32_t)__popcll(peers & lanes_below())] = kv[r];
     __builtin_amdgcn_wave_barrier();
     if (valid && (peers & lanes_below()) == 0) off[digit] += (uint32_t)__popcll(peers);
