@@ -50,6 +50,13 @@ struct alignas(8) RowState {
   uint32_t touch;
 };
 
+// An elected occurrence: its key travels with it, so that the insertion reads the list and nothing else.
+struct alignas(16) Winner {
+  uint64_t key;
+  uint32_t occ;   // occurrence index in the batch
+  uint32_t pos;   // position of the key in the per-call dedup set
+};
+
 // Counters that live on the device for the whole life of the table.
 struct Control {
   int32_t free_n;            // rows on the free stack
@@ -71,7 +78,7 @@ struct TableView {
   StashEntry* stash;         // [kStashCap]
   unsigned long long* dset;  // [dset_size] per-call dedup set: epoch << 32 | occurrence index
   int32_t* dset_row;         // [dset_size] row of the key that owns the dedup-set position
-  uint2* win_list;           // [kWinLists * win_cap] (occurrence, dedup-set position) of elected occurrences
+  Winner* win_list;          // [kWinLists * win_cap] elected occurrences
   uint32_t* win_cnt;         // [kWinLists * kWinStride] fill of each sub-list (zero between calls)
   uint64_t win_cap;
   uint32_t* sweep_list;      // [kWinLists * sweep_cap] slots found expired by the running sweep

@@ -245,7 +245,7 @@ __global__ __launch_bounds__(256) void admit_elect_kernel(TableView t, const int
   if (winner) {
     uint32_t p = block_base + (uint32_t)__popcll(wmask & lanes_below());
     for (uint32_t w = 0; w < wave; ++w) p += wave_cnt[w];
-    t.win_list[(uint64_t)list * t.win_cap + p] = make_uint2((uint32_t)i, (uint32_t)pos);
+    t.win_list[(uint64_t)list * t.win_cap + p] = Winner{(uint64_t)keys[i], (uint32_t)i, (uint32_t)pos};
   }
 }
 
@@ -331,8 +331,8 @@ __device__ inline void store_init4<uint16_t>(uint16_t* rows, uint64_t idx, float
 
 // Dense over the elected occurrences: winner number w of the call takes free_rows[free_n - 1 - w].
 template <typename E>
-__global__ __launch_bounds__(256) void insert_kernel(TableView t, const int64_t* __restrict__ keys, uint32_t step,
-                                                     int32_t* rows_out, RestoreSource src) {
+__global__ __launch_bounds__(256) void insert_kernel(TableView t, uint32_t step, int32_t* rows_out,
+                                                     RestoreSource src) {
   const uint32_t lane = lane_id();
   // inclusive prefix of the sub-list fills, one list per lane
   uint32_t inc = t.win_cnt[lane * kWinStride];
@@ -363,13 +363,13 @@ __global__ __launch_bounds__(256) void insert_kernel(TableView t, const int64_t*
     uint32_t row = kNoRow, occ = 0;
     if (valid) {
       const uint32_t p = w - (lo > 0 ? before : 0u);
-      const uint2 e = t.win_list[(uint64_t)lo * t.win_cap + p];
-      occ = e.x;
-      k = (uint64_t)keys[e.x];
+      const Winner e = t.win_list[(uint64_t)lo * t.win_cap + p];
+      occ = e.occ;
+      k = e.key;
       if ((int64_t)w < (int64_t)free0) row = t.free_rows[free0 - 1 - (int32_t)w];
-      t.dset_row[e.y] = row == kNoRow ? kRowAbsent : (int32_t)row;
-      rows_out[e.x] = row == kNoRow ? kRowAbsent : (int32_t)row;
-      if (row != kNoRow) cuckoo_insert(t, k, make_meta(row, src.seen ? src.seen[e.x] : step));
+      t.dset_row[e.pos] = row == kNoRow ? kRowAbsent : (int32_t)row;
+      rows_out[e.occ] = row == kNoRow ? kRowAbsent : (int32_t)row;
+      if (row != kNoRow) cuckoo_insert(t, k, make_meta(row, src.seen ? src.seen[e.occ] : step));
     }
     // the wave initialises its new rows together: a group of dim/4 lanes per row, four elements per
     // lane, 64/group rows at a time, stored as whole 16-byte (fp32) or 8-byte (bf16) pieces
@@ -438,9 +438,9 @@ hipError_t launch_lookup_or_insert(const TableView& t, const int64_t* d_keys, ui
               dim3(kProbeBlock), t, d_keys, n, step, d_rows_out, restore);
   MONO_LAUNCH(prof, K_ADMIT_ELECT, stream, admit_elect_kernel, grid, block, t, d_keys, n, epoch, d_rows_out, restore);
   if (t.bf16)
-    MONO_LAUNCH(prof, K_INSERT, stream, insert_kernel<uint16_t>, igrid, block, t, d_keys, step, d_rows_out, src);
+    MONO_LAUNCH(prof, K_INSERT, stream, insert_kernel<uint16_t>, igrid, block, t, step, d_rows_out, src);
   else
-    MONO_LAUNCH(prof, K_INSERT, stream, insert_kernel<float>, igrid, block, t, d_keys, step, d_rows_out, src);
+    MONO_LAUNCH(prof, K_INSERT, stream, insert_kernel<float>, igrid, block, t, step, d_rows_out, src);
   MONO_LAUNCH(prof, K_RESOLVE, stream, resolve_kernel, grid, block, t, n, d_rows_out);
   if (restore) hipLaunchKernelGGL(count_refused_kernel, grid, block, 0, stream, t, n, d_rows_out);
   return hipGetLastError();

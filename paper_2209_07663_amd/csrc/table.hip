@@ -80,7 +80,7 @@ size_t layout(mono_table* t, char* base, uint64_t capacity, uint32_t dim, uint32
   char* dset_row = take(dset * sizeof(int32_t));
   const uint64_t win_cap = ((max_ids + 255) / 256 + kWinLists - 1) / kWinLists * 256;
   const uint64_t sweep_cap = ((capacity + 255) / 256 + kWinLists - 1) / kWinLists * 256;
-  char* win_list = take(kWinLists * win_cap * sizeof(uint2));
+  char* win_list = take(kWinLists * win_cap * sizeof(Winner));
   char* win_cnt = take(kWinLists * kWinStride * sizeof(uint32_t));
   char* sweep_list = take(kWinLists * sweep_cap * sizeof(uint32_t));
   char* sweep_cnt = take(kWinLists * kWinStride * sizeof(uint32_t));
@@ -103,7 +103,7 @@ size_t layout(mono_table* t, char* base, uint64_t capacity, uint32_t dim, uint32
     v.stash = (StashEntry*)stash;
     v.dset = (unsigned long long*)dset_p;
     v.dset_row = (int32_t*)dset_row;
-    v.win_list = (uint2*)win_list;
+    v.win_list = (Winner*)win_list;
     v.win_cnt = (uint32_t*)win_cnt;
     v.win_cap = win_cap;
     v.sweep_list = (uint32_t*)sweep_list;
