@@ -16,7 +16,8 @@ struct UpdateWorkspace {
   uint32_t* part_row;   // [2 * tiles] row (+ head flag) of each partial, kNoRow if unused
 };
 
-constexpr uint32_t kSortMaxBits = 8;               // widest radix digit (one thread per bin in a block of the sort)
+constexpr uint32_t kSortMaxBits = 8;               // widest radix digit (measured: 9-bit passes save a pass above 16 M rows
+                                                   // and still lose, their writes come out in pieces of half a line)
 constexpr uint32_t kSortMaxBins = 1u << kSortMaxBits;
 constexpr uint32_t kSortItemsPerBlock = 2048;      // consecutive elements owned by one block of the sort
 constexpr int kPairsPerLane = 16;                  // sorted pairs per lane of a lane group in seg_reduce

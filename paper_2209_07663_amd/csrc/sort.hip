@@ -3,8 +3,8 @@
 //
 // The key width is decided ON THE DEVICE: row indices are handed out in ascending order, so every
 // row in use is below the high-water mark `hwm` kept in the control block.  bit_length(hwm - 1)
-// bits are sorted in the fewest passes of at most kSortMaxBits = 8 bits (a block's share of a bin is
-// then long enough to leave as whole lines); the host launches the worst-case number of passes
+// bits are sorted in the fewest passes of at most kSortMaxBits bits, of equal width (eight bits or fewer
+// up to 16 M rows: a block's share of a bin is then long enough to leave as whole lines); the host launches the worst-case number of passes
 // and the superfluous ones return at once.  Pass p reads buffer (p even ? a : b)
 // and writes the other one.  Dropped occurrences (row -1) are left out by pass 0, which also
 // publishes the number of pairs that remain (kValidPairs slot of the control block's scratch).
@@ -137,7 +137,7 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
   const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const uint64_t unit = blockIdx.x;
   const uint32_t shift = plan.shift(pass), bits = plan.width(pass), nbins = 1u << bits, mask = nbins - 1;
-  static_assert(kSortMaxBins <= kSortBlock, "one thread per bin");
+  static_assert(kSortMaxBins % kSortBlock == 0, "whole bins per thread");
 
   // 1. this wave's elements -> registers (independent, coalesced loads)
   if (pass > 0) n = ctl->scratch[kValidPairs];
@@ -152,9 +152,9 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
     if (i < n) kv[r] = pass == 0 ? make_uint2(first_key(rows, i, plan.hwm), min(bag_of[i], last_bag)) : src[i];
     if (kv[r].x >= plan.hwm) kv[r].x = 0xFFFFFFFFu;  // dropped occurrence (or past the end): left out
   }
-  if (threadIdx.x < kSortMaxBins) {
+  for (uint32_t b = threadIdx.x; b < kSortMaxBins; b += kSortBlock) {
 #pragma unroll
-    for (int w = 0; w < kSortWaves; ++w) lds[w][threadIdx.x] = 0;
+    for (int w = 0; w < kSortWaves; ++w) lds[w][b] = 0;
   }
   __syncthreads();
   // 2. per-wave digit counts
@@ -163,17 +163,26 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
     if (kv[r].x != 0xFFFFFFFFu) atomicAdd(&lds[wave][(kv[r].x >> shift) & mask], 1u);
   }
   __syncthreads();
-  // 3. thread b owns bin b: exclusive scans of the bin totals, once within the block (positions in
-  //    `stage`) and once over all bins of the pass (start of the bin in dst)
+  // 3. a thread owns kBinsPerThread neighbouring bins: exclusive scans of the bin totals, once within
+  //    the block (positions in `stage`) and once over all bins of the pass (start of the bin in dst)
   {
-    const uint32_t b = threadIdx.x;
-    uint32_t mine = 0, tot = 0;
-    if (b < nbins) {
+    constexpr uint32_t kBinsPerThread = kSortMaxBins / kSortBlock;
+    const uint32_t b0 = threadIdx.x * kBinsPerThread;
+    uint32_t mine[kBinsPerThread], tot[kBinsPerThread];
+    uint32_t sum = 0, sum_tot = 0;
 #pragma unroll
-      for (int w = 0; w < kSortWaves; ++w) mine += lds[w][b];
-      tot = totals[b];
+    for (uint32_t q = 0; q < kBinsPerThread; ++q) {
+      mine[q] = 0;
+      tot[q] = 0;
+      if (b0 + q < nbins) {
+#pragma unroll
+        for (int w = 0; w < kSortWaves; ++w) mine[q] += lds[w][b0 + q];
+        tot[q] = totals[b0 + q];
+      }
+      sum += mine[q];
+      sum_tot += tot[q];
     }
-    uint32_t x = mine, y = tot;  // inclusive wave scans
+    uint32_t x = sum, y = sum_tot;  // inclusive wave scans
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
       const uint32_t xs = __shfl_up(x, d), ys = __shfl_up(y, d);
@@ -188,24 +197,30 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
       wave_tot[wave] = y;
     }
     __syncthreads();
-    uint32_t before = 0, before_tot = 0;
+    uint32_t run = x - sum, run_tot = y - sum_tot;  // first position of bin b0 in the block / in dst
     for (uint32_t w = 0; w < wave; ++w) {
-      before += wave_sum[w];
-      before_tot += wave_tot[w];
+      run += wave_sum[w];
+      run_tot += wave_tot[w];
     }
-    if (b < nbins) {
-      uint32_t run = before + x - mine;  // first position of bin b within the block
-      local_start[b] = run;
-      global_start[b] = before_tot + y - tot + hist[(uint64_t)b * units + unit];
 #pragma unroll
-      for (int w = 0; w < kSortWaves; ++w) {
-        const uint32_t c = lds[w][b];
-        lds[w][b] = run;
-        run += c;
+    for (uint32_t q = 0; q < kBinsPerThread; ++q) {
+      const uint32_t bin = b0 + q;
+      if (bin < nbins) {
+        local_start[bin] = run;
+        global_start[bin] = run_tot + hist[(uint64_t)bin * units + unit];
+        uint32_t at = run;
+#pragma unroll
+        for (int w = 0; w < kSortWaves; ++w) {
+          const uint32_t c = lds[w][bin];
+          lds[w][bin] = at;
+          at += c;
+        }
       }
+      run += mine[q];
+      run_tot += tot[q];
     }
     if (pass == 0 && blockIdx.x == 0 && threadIdx.x == kSortBlock - 1)
-      ctl->scratch[kValidPairs] = before_tot + y;  // pairs that remain
+      ctl->scratch[kValidPairs] = run_tot;  // pairs that remain
   }
   __syncthreads();
   // 4. rank (stable) into `stage`, 64 elements at a time
