@@ -237,3 +237,48 @@ def test_growing_an_overfull_table_empties_its_stash_and_makes_room(dev):
     assert d["keys"].shape[0] == universe.shape[0] and np.unique(d["row"]).shape[0] == universe.shape[0]
     tc.check_placement(d, 2 * cap, 8, seed, generation=1)
     big.close()
+
+
+def test_long_stream_with_every_operation(dev):
+    """Forty steps of a drifting stream with expiry: lookup, pool, update and sweep every step, a
+    synchronisation every seventh, a grow under new hash functions at step 15, a snapshot + restore
+    into a fresh table at step 25 - device and oracle side by side throughout."""
+    from paper_2209_07663_amd.binding import Table
+    wl, seed, rtol = _small_cfg("cfg4"), 131, 1e-5
+    tab = Table(wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, max_ids=1 << 17,
+                max_bags=wl.n_bags, device=dev, filter_hashes=2)
+    orc = Oracle(wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, kind="cuckoo",
+                 n_filter=tab.n_filter, filter_hashes=2)
+    drift = synth.DriftMap(wl, seed)
+    generation = 0
+    for step in range(40):
+        b = synth.make_batch(wl, seed, step, with_grad=True, drift=drift)
+        _full_step(tab, orc, b, dev, wl, rtol, generation=generation, seed=seed)
+        if step % 7 == 6:
+            delta, want = tab.mono_export_touched(), orc.take_touched()
+            assert delta["n"] == want.shape[0] and (delta["keys"] == want).all(), "touched sets differ at step %d" % step
+        if step == 15:
+            generation = 5
+            new = tab.rehashed(wl.capacity * 2, generation)
+            orc.rehash(wl.capacity * 2, generation)
+            tab.close()
+            tab = new
+        if step == 25:
+            snap, words = tab.mono_table_export(), tab.mono_filter_export()
+            osnap, owords = orc.dump(), orc.filter_words()
+            fresh = Table(tab.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, max_ids=1 << 17,
+                          max_bags=wl.n_bags, device=dev, filter_hashes=2, filter_log2=tab.n_filter.bit_length() - 1)
+            to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+            assert fresh.mono_table_import(to_dev(snap["keys"]), to_dev(snap["rows"]), to_dev(snap["acc"]),
+                                           to_dev(snap["last_seen"].view(np.int32))) == 0
+            fresh.mono_filter_import(to_dev(words.view(np.int32)))
+            tab.close()
+            tab, generation = fresh, 0               # a restored table starts with the hash functions of a new one
+            orc2 = Oracle(orc.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, kind="cuckoo",
+                          n_filter=orc.n_filter, filter_hashes=2)
+            assert orc2.import_entries(osnap["keys"], osnap["rows"], osnap["acc"], osnap["last_seen"]) == 0
+            orc2.write_filter_words(owords)
+            orc.take_touched()                       # the restored pair starts a new synchronisation window
+            orc = orc2
+    assert tab.mono_table_stats()["n_insert_failed"] == 0
+    tab.close()
