@@ -190,8 +190,18 @@ class Model {
     out->assign(touched_.begin(), touched_.end());
     touched_.clear();
   }
-  // place a record; false (and nothing changes) if the key is already stored or is the reserved key
+  // place a record; false (and nothing changes) if the key is already stored or is the reserved key.
+  // A placed key's counters are raised to the admission threshold if they are below it: a stored
+  // key has been seen at least that often (records may be restored without their counters).
   virtual bool import_entry(uint64_t key, const Entry& e) = 0;
+  void raise_counters(uint64_t key) {
+    uint32_t least = p_.freq_threshold > 1 ? p_.freq_threshold : 1;
+    for (uint32_t j = 0; j < p_.filter_hashes; ++j) {
+      uint64_t i = filter_index(key, j);
+      uint32_t w = filter_word(i);
+      if ((w & 255u) < least) set_filter_word(i, (w & ~255u) | least);
+    }
+  }
   virtual void set_filter_word(uint64_t index, uint32_t word) = 0;
   // re-insert everything under generation `generation` in a table of `new_capacity` >= capacity
   virtual void rehash(uint64_t new_capacity, uint32_t generation) = 0;
@@ -315,6 +325,7 @@ class BruteForceModel final : public Model {
   bool import_entry(uint64_t key, const Entry& e) override {
     if (key == kEmptyKey || table_.count(key)) return false;
     table_[key] = e;
+    raise_counters(key);
     return true;
   }
   void set_filter_word(uint64_t index, uint32_t word) override { filter_[index] = word; }
@@ -530,6 +541,7 @@ class CuckooModel final : public Model {
     key_of_entry_[id] = key;
     insert(key, id);
     ++size_;
+    raise_counters(key);
     return true;
   }
   void set_filter_word(uint64_t index, uint32_t word) override { filter_[index] = word; }

@@ -231,3 +231,30 @@ def test_rehash_empties_the_overflow_stash_of_a_one_slot_cuckoo_table():
     assert (after["slot"] >= 0).all()
     tc.check_placement(after, cap * 2, 1, seed, generation=generation)
     assert o.lookup_or_insert(keys, 1).all()
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("thr,hashes", [(0, 1), (1, 2), (3, 1), (3, 3)])
+def test_restored_keys_count_as_seen_threshold_times(kind, thr, hashes):
+    """Records can be restored without their counters: a placed key's counters are raised to the
+    admission threshold (never lowered), so "stored implies counted" holds as after an admission."""
+    dim, seed, n_filter = 2, 29, 1 << 16
+    o = Oracle(1 << 10, dim, seed, freq_threshold=thr, kind=kind, n_filter=n_filter, filter_hashes=hashes)
+    for step in range(6):
+        o.lookup_or_insert(np.array([77, 78], dtype=np.int64), step)      # 77 and 78 get counted / admitted
+    keys = np.array([5, 6, 7], dtype=np.int64)
+    before = o.filter_words()
+    assert o.import_entries(keys, np.zeros((3, dim), np.float32), np.zeros(3, np.float32), np.zeros(3, np.uint32)) == 0
+    after = o.filter_words()
+    least = max(thr, 1)
+    touched = set()
+    for key in keys.tolist():
+        for j in range(hashes):
+            i = int(tc.filter_index(np.array([key]), n_filter, seed, j)[0])
+            touched.add(i)
+            assert after[i] & 255 == max(before[i] & 255, least) and after[i] >> 8 == before[i] >> 8
+    others = np.setdiff1d(np.arange(n_filter), np.array(sorted(touched)))
+    assert (after[others] == before[others]).all()
+    # a restored key is found without being counted again
+    assert o.lookup_or_insert(keys, 9).all()
+    assert (o.filter_words() == after).all()
