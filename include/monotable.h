@@ -145,6 +145,8 @@ int mono_export_touched(mono_table* t, int64_t* d_keys, int32_t* d_row, float* d
  * mono_table_export and mono_filter_export return; this call places n records (key, row values,
  * accumulator, last-seen step) into the table: each gets a free row, is inserted by the eviction-chain
  * insertion of section 2.1 without consulting the occurrence filter, and is not marked touched.
+ * The occurrence counters of a placed key are raised to freq_threshold if they are below it (a
+ * stored key has been seen at least that often), so records may be restored without their counters.
  *   d_keys[n], d_values[n * dim] (fp32; rounded to nearest-even for bf16 rows), d_acc[n], d_last_seen[n]
  *   n <= max_ids per call (call repeatedly for more)
  *   h_refused  nullable; receives the number of records not placed: key already stored, key -1,

@@ -369,7 +369,17 @@ __global__ __launch_bounds__(256) void insert_kernel(TableView t, uint32_t step,
       if ((int64_t)w < (int64_t)free0) row = t.free_rows[free0 - 1 - (int32_t)w];
       t.dset_row[e.pos] = row == kNoRow ? kRowAbsent : (int32_t)row;
       rows_out[e.occ] = row == kNoRow ? kRowAbsent : (int32_t)row;
-      if (row != kNoRow) cuckoo_insert(t, k, make_meta(row, src.seen ? src.seen[e.occ] : step));
+      if (row != kNoRow) {
+        cuckoo_insert(t, k, make_meta(row, src.seen ? src.seen[e.occ] : step));
+        if (src.values) {
+          // a restored key counts as seen freq_threshold times: its counters are raised to that
+          // (records may come without their counters, and a counter below the threshold would
+          // otherwise "prove" the key absent to the next lookup)
+          const uint32_t least = t.freq_threshold > 1u ? t.freq_threshold : 1u;
+          for (uint32_t j = 0; j < t.filter_hashes; ++j)
+            atomicMax(reinterpret_cast<uint32_t*>(&t.filter[filter_index(t, k, j)]), least);
+        }
+      }
     }
     // the wave initialises its new rows together: a group of dim/4 lanes per row, four elements per
     // lane, 64/group rows at a time, stored as whole 16-byte (fp32) or 8-byte (bf16) pieces

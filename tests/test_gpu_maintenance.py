@@ -282,3 +282,33 @@ def test_long_stream_with_every_operation(dev):
             orc = orc2
     assert tab.mono_table_stats()["n_insert_failed"] == 0
     tab.close()
+
+
+@pytest.mark.parametrize("hashes", [1, 3])
+def test_restore_without_counters_on_a_table_that_never_expires(dev, hashes):
+    """With expire_steps == 0 a lookup trusts a counter below the threshold as proof of absence; records
+    restored WITHOUT their counters must still be found, and the counters they raise match the oracle."""
+    from paper_2209_07663_amd.binding import Table
+    wl, seed = synth.scaled(synth.CONFIGS["cfg2"], samples=1024, capacity=1 << 17), 141
+    mk = lambda: (Table(wl.capacity, wl.dim, seed, wl.freq_threshold, 0, False, max_ids=1 << 18, max_bags=wl.n_bags,
+                        device=dev, filter_hashes=hashes),
+                  Oracle(wl.capacity, wl.dim, seed, wl.freq_threshold, 0, False, kind="cuckoo", filter_hashes=hashes))
+    tab_a, orc_a = mk()
+    batches = [synth.make_batch(wl, seed, s, with_grad=True) for s in range(6)]
+    for b in batches[:3]:
+        _full_step(tab_a, orc_a, b, dev, wl, 1e-5, seed=seed)
+    snap, osnap = tab_a.mono_table_export(), orc_a.dump()
+    assert snap["keys"].shape[0] > 1000
+    tab_b, orc_b = mk()                                   # records only: the counters start from zero
+    to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    assert tab_b.mono_table_import(to_dev(snap["keys"]), to_dev(snap["rows"]), to_dev(snap["acc"]),
+                                   to_dev(snap["last_seen"].view(np.int32))) == 0
+    assert orc_b.import_entries(osnap["keys"], osnap["rows"], osnap["acc"], osnap["last_seen"]) == 0
+    assert (tab_b.mono_filter_export() == orc_b.filter_words()).all()
+    rows = tab_b.mono_lookup_or_insert(to_dev(snap["keys"]), 3)
+    assert bool((rows >= 0).all().item())                  # every restored key is found
+    assert orc_b.lookup_or_insert(snap["keys"], 3).all()
+    for b in batches[3:]:
+        _full_step(tab_b, orc_b, b, dev, wl, 1e-5, seed=seed)
+    tab_a.close()
+    tab_b.close()
