@@ -155,7 +155,9 @@ int mono_export_touched(mono_table* t, int64_t* d_keys, int32_t* d_row, float* d
 int mono_table_import(mono_table* t, const int64_t* d_keys, const float* d_values, const float* d_acc,
                       const uint32_t* d_last_seen, uint64_t n, uint64_t* h_refused, void* stream);
 
-/* Writes occurrence counters [first, first + count) from canonical words (see mono_filter_export). */
+/* Writes occurrence counters [first, first + count) from canonical words (see mono_filter_export).
+ * Meant for the words of a snapshot: the counters of a stored key must not end up below
+ * freq_threshold (with expire_steps == 0 a lookup reads such a counter as "this key is not stored"). */
 int mono_filter_import(mono_table* t, const uint32_t* d_words, uint64_t first, uint64_t count, void* stream);
 
 /* Rehash / grow (section 2.1: a rehash answers an insertion that runs into a cycle; the table is
