@@ -57,7 +57,10 @@ typedef struct mono_stats {
 size_t mono_table_bytes(uint64_t capacity, uint32_t dim, uint32_t flags, uint64_t max_ids, uint64_t max_bags);
 
 /* Creates a table (section 2.1: cuckoo hashmap + occurrence filter + expiry).
- *   capacity        total slots = embedding rows; power of two in [16, 2^30]; each sub-table has half
+ *   capacity        total slots = embedding rows; power of two in [16, 2^30]; each sub-table has half.
+ *                   At most capacity - capacity/32 keys are stored at a time: beyond that load the
+ *                   eviction chains of section 2.1 become long enough to fail, so further admissible
+ *                   keys are refused (row -1, counted in n_full) until keys expire or the table grows
  *   dim             embedding dimension; multiple of 4 in [4, 256]
  *   seed            fixes h0, h1, the counter hash and the initial value of every row
  *   freq_threshold  a key is admitted once its occurrence counter reaches it; 0 and 1 admit on

@@ -9,7 +9,8 @@ namespace mono {
 constexpr uint64_t kEmptyKey = ~0ull;       // reserved key: padding / free slot
 constexpr uint32_t kNoRow = 0xFFFFFFFFu;    // slot has no published row: free, or being written
 constexpr int kBucket = 8;                  // slots per bucket
-constexpr int kMaxKicks = 128;              // bound of an eviction chain
+constexpr int kMaxKicks = 512;              // bound of an eviction chain
+constexpr int kReserveShift = 5;            // capacity >> 5 rows are never handed out: see rows_on_offer()
 constexpr uint32_t kStashCap = 4096;        // homeless elements kept aside after a failed chain
 constexpr int32_t kRowAbsent = -1;          // rows_out: key not in the table
 constexpr int32_t kRowMiss = -2;            // rows_out, between the kernels of one call: missed, undecided
@@ -107,6 +108,15 @@ __host__ __device__ inline uint64_t mix64(uint64_t z) {
   z *= 0x94D049BB133111EBull;
   z ^= z >> 31;
   return z;
+}
+
+// Rows that new keys may take when free_n rows are free.  The last 1/32 of the rows is held back:
+// with buckets of eight slots, eviction chains grow steeply past a load of ~0.97 (measured: chains
+// of 125 evictions at 0.965), and a chain that hits its bound costs a stash entry, then a resident.
+// A table therefore refuses new keys (counted in n_full) at load 31/32 instead of failing chains.
+__host__ __device__ inline int64_t rows_on_offer(uint64_t capacity, int32_t free_n) {
+  const int64_t offer = (int64_t)free_n - (int64_t)(capacity >> kReserveShift);
+  return offer > 0 ? offer : 0;
 }
 
 __device__ inline uint64_t shr_or_zero(uint64_t h, uint32_t shift) { return shift >= 64 ? 0 : h >> shift; }

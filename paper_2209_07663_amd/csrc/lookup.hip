@@ -366,7 +366,7 @@ __global__ __launch_bounds__(256) void insert_kernel(TableView t, uint32_t step,
       const Winner e = t.win_list[(uint64_t)lo * t.win_cap + p];
       occ = e.occ;
       k = e.key;
-      if ((int64_t)w < (int64_t)free0) row = t.free_rows[free0 - 1 - (int32_t)w];
+      if ((int64_t)w < rows_on_offer(t.capacity, free0)) row = t.free_rows[free0 - 1 - (int32_t)w];
       t.dset_row[e.pos] = row == kNoRow ? kRowAbsent : (int32_t)row;
       rows_out[e.occ] = row == kNoRow ? kRowAbsent : (int32_t)row;
       if (row != kNoRow) {
@@ -422,7 +422,8 @@ __global__ __launch_bounds__(256) void resolve_kernel(TableView t, uint64_t n, i
       t.win_cnt[l * kWinStride] = 0;
     }
     const int32_t free0 = t.ctl->free_n;
-    const uint32_t got = total < (uint32_t)free0 ? total : (uint32_t)free0;
+    const uint32_t offer = (uint32_t)rows_on_offer(t.capacity, free0);
+    const uint32_t got = total < offer ? total : offer;
     t.ctl->free_n = free0 - (int32_t)got;
     const uint32_t in_use = (uint32_t)t.capacity - (uint32_t)(free0 - (int32_t)got);
     if (in_use > t.ctl->hwm) t.ctl->hwm = in_use;  // rows are handed out in ascending order

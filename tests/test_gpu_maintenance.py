@@ -219,7 +219,7 @@ def test_growing_an_overfull_table_empties_its_stash_and_makes_room(dev):
         rows = tab.mono_lookup_or_insert(torch.from_numpy(chunk).to(dev), step).cpu().numpy()
         held.update({k: r for k, r in zip(chunk.tolist(), rows.tolist()) if r >= 0})
     st = tab.mono_table_stats()
-    assert st["size"] == len(held) and (st["n_full"] > 0 or st["stash_size"] > 0) and st["n_lost"] == 0
+    assert st["size"] == len(held) == cap - cap // 32 and st["n_full"] > 0 and st["n_lost"] == 0
     big = tab.rehashed(cap * 2, 1)
     tab.close()
     st = big.mono_table_stats()
