@@ -97,7 +97,8 @@ def _full_step(tab, orc, b, dev, wl, rtol, generation=0, seed=None):
     assert (tab.mono_filter_export() == orc.filter_words()).all(), "counter words differ"
     st = tab.mono_table_stats()
     assert st["n_lost"] == 0 and st["n_full"] == 0 and st["stash_size"] == 0
-    return d
+    assert st["size"] == st["n_admitted"] - st["n_expired"] == d["keys"].shape[0]      # conservation, also across
+    return d                                                                          # restore and rehash
 
 
 def _small_cfg(name):

@@ -49,6 +49,7 @@ def compare_step(tab, orc, batch, dev, rtol, exact_rows, train, lr=0.05, eps=1e-
     assert (d["row"][pos] == rows_h[present]).all()
     st = tab.mono_table_stats()
     assert st["n_insert_failed"] == 0 and st["n_lost"] == 0 and st["n_full"] == 0 and orc.insert_failures == 0
+    assert st["size"] == st["n_admitted"] - st["n_expired"] == d["keys"].shape[0]      # conservation
     tc.check_placement(d, tab.capacity, 8, tab_seed(tab))
     tc.assert_same_table(d, orc.dump(), exact_rows=exact_rows, rtol=rtol)
     pooled = tab.mono_gather_pool(rows, offs).cpu().numpy()
