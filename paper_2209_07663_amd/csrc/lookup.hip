@@ -184,16 +184,36 @@ __global__ __launch_bounds__(kProbeBlock) void probe_count_kernel(TableView t, c
 
 // ---- election ------------------------------------------------------------------------------------
 
+constexpr int kElectSlots = 512;  // slots of a block's LDS set of missing keys (256 keys at most)
+
 __global__ __launch_bounds__(256) void admit_elect_kernel(TableView t, const int64_t* __restrict__ keys, uint64_t n,
                                                           uint32_t epoch, int32_t* rows_out, int restore) {
   __shared__ uint32_t wave_cnt[4];
   __shared__ uint32_t block_base;
+  // The block's occurrences of one missing key are represented by one of them (the leader): a key
+  // that turns hot before it is admitted arrives here in thousands of occurrences, and each of them
+  // re-reading the counter and competing for the same position of the dedup set serialised.
+  __shared__ unsigned long long s_key[kElectSlots];
+  __shared__ int32_t s_res[kElectSlots];  // what the leader found: kRowAbsent, or the dedup-set position as -(pos) - 3
+  for (int s = threadIdx.x; s < kElectSlots; s += 256) s_key[s] = kEmptyKey;
+  __syncthreads();
   const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const bool miss = i < n && rows_out[i] == kRowMiss;
+  const uint64_t k = miss ? (uint64_t)keys[i] : kEmptyKey;
+  bool leader = false;
+  uint32_t ls = 0;
+  if (miss) {
+    ls = (uint32_t)(mix64(k ^ t.s_dedup) >> 32) & (kElectSlots - 1);
+    for (;;) {  // at most 256 keys in 512 slots: a free slot always turns up
+      const unsigned long long old = atomicCAS(&s_key[ls], (unsigned long long)kEmptyKey, (unsigned long long)k);
+      if (old == kEmptyKey) leader = true;
+      if (old == kEmptyKey || old == k) break;
+      ls = (ls + 1) & (kElectSlots - 1);
+    }
+  }
   bool winner = false;
   uint64_t pos = 0;
-  if (miss) {
-    const uint64_t k = (uint64_t)keys[i];
+  if (leader) {
     uint32_t cnt = 255u;  // a snapshot record is admitted whatever its counter says
     if (!restore) {
       for (uint32_t j = 0; j < t.filter_hashes; ++j) {  // smallest of the key's counters
@@ -207,9 +227,8 @@ __global__ __launch_bounds__(256) void admit_elect_kernel(TableView t, const int
         cnt = c < cnt ? c : cnt;
       }
     }
-    if (cnt < t.freq_threshold) {
-      rows_out[i] = kRowAbsent;
-    } else {
+    int32_t found = kRowAbsent;
+    if (cnt >= t.freq_threshold) {
       // one occurrence per distinct key wins its position of the per-call dedup set
       pos = mix64(k ^ t.s_dedup) & t.dset_mask;
       const unsigned long long mine = ((unsigned long long)epoch << 32) | (unsigned long long)i;
@@ -228,9 +247,13 @@ __global__ __launch_bounds__(256) void admit_elect_kernel(TableView t, const int
         pos = (pos + 1) & t.dset_mask;
       }
       // (a second record of the same key in one restore call is refused like a stored key)
-      if (!winner) rows_out[i] = restore ? kRowAbsent : -(int32_t)pos - 3;
+      found = restore ? kRowAbsent : -(int32_t)pos - 3;
     }
+    s_res[ls] = found;
+    if (!winner) rows_out[i] = found;  // the winner keeps kRowMiss until the insertion gives it its row
   }
+  __syncthreads();
+  if (miss && !leader) rows_out[i] = s_res[ls];
   // block-aggregated append to sub-list (blockIdx mod kWinLists)
   const uint32_t wave = threadIdx.x >> 6;
   const uint64_t wmask = __ballot(winner);
@@ -245,7 +268,7 @@ __global__ __launch_bounds__(256) void admit_elect_kernel(TableView t, const int
   if (winner) {
     uint32_t p = block_base + (uint32_t)__popcll(wmask & lanes_below());
     for (uint32_t w = 0; w < wave; ++w) p += wave_cnt[w];
-    t.win_list[(uint64_t)list * t.win_cap + p] = Winner{(uint64_t)keys[i], (uint32_t)i, (uint32_t)pos};
+    t.win_list[(uint64_t)list * t.win_cap + p] = Winner{k, (uint32_t)i, (uint32_t)pos};
   }
 }
 
