@@ -297,6 +297,34 @@ __device__ inline bool try_claim(Bucket* b, uint64_t k, unsigned long long meta)
   return false;
 }
 
+__device__ inline bool has_empty_key(const Bucket* b) {
+  const ulonglong2* kp = reinterpret_cast<const ulonglong2*>(b->key);
+  const ulonglong2 a0 = kp[0], a1 = kp[1], a2 = kp[2], a3 = kp[3];
+  return a0.x == kEmptyKey || a0.y == kEmptyKey || a1.x == kEmptyKey || a1.y == kEmptyKey || a2.x == kEmptyKey ||
+         a2.y == kEmptyKey || a3.x == kEmptyKey || a3.y == kEmptyKey;
+}
+
+// Which resident of the full bucket b (in sub-table `side`) to evict.  A victim whose OTHER bucket has
+// a free slot ends the chain after one move, so the other buckets of the eight residents are looked
+// at first (eight independent line reads) and the first such resident from `start` on is chosen;
+// if there is none, `start` itself.  Only a hint: the snapshot may be stale, the protocol decides.
+// Measured on the streaming configuration at load 0.92: a random victim gave chains of up to 20
+// evictions, each five dependent memory round trips long, and the slowest chain is the kernel's time.
+__device__ inline uint32_t pick_victim(const TableView& t, const Bucket* b, int side, uint32_t start) {
+  const ulonglong2* kp = reinterpret_cast<const ulonglong2*>(b->key);
+  const ulonglong2 a0 = kp[0], a1 = kp[1], a2 = kp[2], a3 = kp[3];
+  const uint64_t res[kBucket] = {a0.x, a0.y, a1.x, a1.y, a2.x, a2.y, a3.x, a3.y};
+  uint32_t good = 0;  // bit l: resident l could move out at once
+#pragma unroll
+  for (int l = 0; l < kBucket; ++l) {
+    if (res[l] == kEmptyKey) continue;
+    if (has_empty_key(&t.buckets[bucket_index(t, 1 - side, res[l])])) good |= 1u << l;
+  }
+  if (good == 0) return start;
+  const uint32_t rotated = ((good >> start) | (good << (kBucket - start))) & 0xFFu;  // bit 0 = slot `start`
+  return (start + (uint32_t)__ffs((int)rotated) - 1u) & (kBucket - 1);
+}
+
 // Inserts (k, meta); k is not in the table and no other thread inserts the same key.
 __device__ void cuckoo_insert(const TableView& t, uint64_t k, unsigned long long meta) {
   int side = 0;
@@ -307,7 +335,7 @@ __device__ void cuckoo_insert(const TableView& t, uint64_t k, unsigned long long
     if (try_claim(b, k, meta)) goto done;
     if (kick == 0 && try_claim(&t.buckets[bucket_index(t, 1, k)], k, meta)) goto done;
     // evict: take the lock of a published slot
-    const uint32_t v0 = (uint32_t)(mix64(k + (uint64_t)kick) >> 61);
+    const uint32_t v0 = pick_victim(t, b, side, (uint32_t)(mix64(k + (uint64_t)kick) >> 61));
 #pragma unroll 1
     for (int tries = 0; tries < kBucket; ++tries) {
       const int l = (int)((v0 + (uint32_t)tries) & (kBucket - 1));
@@ -335,7 +363,10 @@ __device__ void cuckoo_insert(const TableView& t, uint64_t k, unsigned long long
     }
   }
 done:
-  if (chain) atomicMax(&t.ctl->max_chain, (unsigned long long)chain);
+  // (read first: an atomic on this one word from every insertion that evicted serialises at ~12 ns each,
+  // which at load 0.8 was most of the kernel's time)
+  if (chain && (unsigned long long)chain > ld_agent(&t.ctl->max_chain))
+    atomicMax(&t.ctl->max_chain, (unsigned long long)chain);
 }
 
 template <typename E>
