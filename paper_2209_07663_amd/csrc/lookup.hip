@@ -44,16 +44,19 @@ __device__ inline void touch_word(const TableView& t, unsigned long long* w, uin
     return;
   }
   unsigned long long cur = ld_agent(w);
-  // first toucher of the batch ages the word and stamps the step; increments only ever follow it
-  while ((uint32_t)(cur >> 32) != step) {
+  for (;;) {
+    if ((uint32_t)(cur >> 32) == step) {  // already touched in this batch: increments only
+      atomicAdd(w, (unsigned long long)times);  // unsaturated; read as min(count, 255)
+      return;
+    }
+    // first toucher of the batch: ages the word, stamps the step and adds its occurrences in one exchange
     uint32_t last = (uint32_t)(cur >> 32), cnt = (uint32_t)cur;
     if (step - last >= t.expire_steps) cnt = 0;
-    unsigned long long want = ((unsigned long long)step << 32) | cnt;
-    unsigned long long old = atomicCAS(w, cur, want);
-    if (old == cur) break;
+    const unsigned long long want = ((unsigned long long)step << 32) | (unsigned long long)(cnt + times);
+    const unsigned long long old = atomicCAS(w, cur, want);
+    if (old == cur) return;
     cur = old;
   }
-  atomicAdd(w, (unsigned long long)times);  // unsaturated; read as min(count, 255)
 }
 
 // every counter of the key (section 2.1's probabilistic filter read as a counting filter with
