@@ -33,7 +33,9 @@ _lib = None
 def oracle_lib():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build_oracle())
+        # MONOLITH_ORACLE_LIB: a library built elsewhere from (a variant of) the same source; the
+        # test-suite uses it to check that the pins notice mistakes planted in the oracle
+        lib = ctypes.CDLL(os.environ.get("MONOLITH_ORACLE_LIB") or build_oracle())
         lib.orc_create.restype = _vp
         lib.orc_create.argtypes = [ctypes.c_int, _u64, _u32, _u64, _u32, _u32, ctypes.c_int, _u64, _u32, _u32,
                                    ctypes.c_int, _u32]

@@ -221,6 +221,7 @@ def test_seeded_random_configurations(dev, case):
     n_bags = int(rng.integers(50, 3000))
     lam = float(rng.choice([0.0, 1.0, 6.0]))
     universe = int(rng.choice([50, 2000, 1 << 40]))
+    lr, eps = float(rng.choice([0.05, 0.5])), float(rng.choice([1e-8, 0.1]))     # eps large enough to matter
     seed = 500 + case
     print("case", case, dict(dim=dim, bf16=bf16, thr=thr, expire=expire, hashes=hashes, cap=cap,
                              filter_log2=filter_log2, n_bags=n_bags, lam=lam, universe=universe), flush=True)
@@ -245,6 +246,6 @@ def test_seeded_random_configurations(dev, case):
         if np.unique(keys).shape[0] * (step + 1) > cap // 2:
             keys = keys % 997
         compare_step(tab, orc, {"keys": keys, "offsets": offs, "grad": grad, "step": 2 * step}, dev, rtol,
-                     exact_rows=False, train=True, sweep_at=2 * step if expire else None)
+                     exact_rows=False, train=True, lr=lr, eps=eps, sweep_at=2 * step if expire else None)
         assert (tab.mono_filter_export() == orc.filter_words()).all(), "counter words differ at step %d" % step
     tab.close()

@@ -1,0 +1,57 @@
+"""Do the pins notice a mistake?  Each case plants ONE plausible mistake in a copy of the oracle's
+source (a dropped term, a wrong comparison, a swapped rule), builds it, and runs the pins against
+that library in a child process: they must fail.  CPU only; nothing here touches the device path."""
+import os
+import subprocess
+import sys
+
+import pytest
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+SRC = os.path.join(ROOT, "oracle", "monolith_oracle.cpp")
+
+# (name, text in the source, replacement, pin tests that must notice)
+MUTATIONS = [
+    ("eps_inside_root", "double denom = std::sqrt(acc) + eps;", "double denom = std::sqrt(acc + eps);",
+     "tests/test_oracle_pins.py -k adagrad"),
+    ("sum_instead_of_mean_of_squares", "double acc = (double)e->acc + ss / (double)p.dim;",
+     "double acc = (double)e->acc + ss;", "tests/test_oracle_pins.py -k adagrad"),
+    ("expiry_strictly_greater", "if (now - it->second.last_seen >= p_.expire_steps) {",
+     "if (now - it->second.last_seen > p_.expire_steps) {", "tests/test_oracle_semantics.py -k expiry"),
+    ("counter_ageing_off_by_one", "if (expire_steps > 0 && step - last >= expire_steps) count = 0;",
+     "if (expire_steps > 0 && step - last > expire_steps) count = 0;", "tests/test_oracle_pins.py -k filter_word"),
+    ("bf16_truncates", "u += 0x7FFFu + lsb;", "u += 0u;", "tests/test_oracle_pins.py -k bf16"),
+    ("touched_survives_expiry", "        touched_.erase(it->first);\n", "", "tests/test_oracle_maintenance.py -k touched"),
+    ("grown_counters_by_low_bits", "grown[i] = filter_[i >> k];", "grown[i] = filter_[i & ((p_.n_filter >> k) - 1)];",
+     "tests/test_oracle_maintenance.py -k grow"),
+    ("salt_off_by_one", "return mix64(seed + (uint64_t)(i + 1) * 0x9E3779B97F4A7C15ull);",
+     "return mix64(seed + (uint64_t)(i + 2) * 0x9E3779B97F4A7C15ull);", "tests/test_oracle_pins.py -k mixer"),
+    ("mixer_shift", "z ^= z >> 27;", "z ^= z >> 26;", "tests/test_oracle_pins.py -k mixer"),
+    ("min_of_counters_becomes_first", "count = std::min(count, filter_[filter_index(k, j)] & 255u);",
+     "if (j == 0) count = filter_[filter_index(k, j)] & 255u;", "tests/test_oracle_filter.py"),
+    ("restore_ignores_last_seen", "    e.last_seen = last_seen[i];", "    e.last_seen = 0;",
+     "tests/test_oracle_maintenance.py -k restored_table"),
+    ("evicted_goes_to_same_table", "      side = 1 - side;  // the evicted element goes to its other sub-table",
+     "      side = side;", "tests/test_oracle_pins.py -k cuckoo"),
+]
+
+
+def test_the_unmodified_source_contains_every_mutation_site():
+    text = open(SRC).read()
+    for name, old, _new, _tests in MUTATIONS:
+        assert old in text, "mutation %s no longer matches the source" % name
+
+
+@pytest.mark.parametrize("name,old,new,tests", MUTATIONS, ids=[m[0] for m in MUTATIONS])
+def test_pins_fail_on_a_planted_mistake(tmp_path, name, old, new, tests):
+    text = open(SRC).read()
+    assert old in text
+    src = tmp_path / "mutant.cpp"
+    src.write_text(text.replace(old, new))
+    lib = tmp_path / "libmutant.so"
+    subprocess.check_call(["g++", "-O1", "-std=c++17", "-shared", "-fPIC", str(src), "-o", str(lib)])
+    env = dict(os.environ, MONOLITH_ORACLE_LIB=str(lib))
+    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider"] + tests.split(),
+                       cwd=ROOT, env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, timeout=300)
+    assert r.returncode == 1, "the pins did not notice %s:\n%s" % (name, r.stdout.decode()[-600:])

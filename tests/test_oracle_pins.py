@@ -193,8 +193,9 @@ def test_pool_equals_embedding_bag(kind):
 
 
 @pytest.mark.parametrize("kind", ["map", "cuckoo"])
-def test_update_equals_index_add_then_closed_form_adagrad(kind):
-    dim, lr, eps = 8, 0.05, 1e-8
+@pytest.mark.parametrize("eps", [1e-8, 0.25])               # a large eps tells "outside the root" from "inside"
+def test_update_equals_index_add_then_closed_form_adagrad(kind, eps):
+    dim, lr = 8, 0.05
     o, keys = _filled(kind, dim, 64)
     before = o.dump()
     rng = np.random.default_rng(6)
@@ -224,9 +225,10 @@ def test_update_equals_index_add_then_closed_form_adagrad(kind):
 
 
 @pytest.mark.parametrize("kind", ["map", "cuckoo"])
-def test_dim1_equals_torch_adagrad_over_several_steps(kind):
+@pytest.mark.parametrize("eps", [1e-8, 0.25])
+def test_dim1_equals_torch_adagrad_over_several_steps(kind, eps):
     """With one element per row, row-wise Adagrad is the textbook element-wise optimizer."""
-    lr, eps = 0.05, 1e-8
+    lr = 0.05
     o, keys = _filled(kind, 1, 32)
     d = o.dump()
     order = np.argsort(np.argsort(keys.astype(np.uint64)))  # position of keys[i] in the sorted dump
