@@ -2,6 +2,7 @@
 source (a dropped term, a wrong comparison, a swapped rule), builds it, and runs the pins against
 that library in a child process: they must fail.  CPU only; nothing here touches the device path."""
 import os
+import shlex
 import subprocess
 import sys
 
@@ -32,6 +33,18 @@ MUTATIONS = [
      "if (j == 0) count = filter_[filter_index(k, j)] & 255u;", "tests/test_oracle_filter.py"),
     ("restore_ignores_last_seen", "    e.last_seen = last_seen[i];", "    e.last_seen = 0;",
      "tests/test_oracle_maintenance.py -k restored_table"),
+    ("admission_strictly_above_threshold", "if (count >= p_.freq_threshold) init_entry(p_, k, step, &table_[k]);",
+     "if (count > p_.freq_threshold) init_entry(p_, k, step, &table_[k]);", "tests/test_oracle_semantics.py -k threshold"),
+    ("hits_are_counted_too", "      if (k == kEmptyKey || was_hit[i]) continue;\n      for (uint32_t j = 0; j < p_.filter_hashes; ++j) {  // one touch per counter of the key",
+     "      if (k == kEmptyKey) continue;\n      for (uint32_t j = 0; j < p_.filter_hashes; ++j) {  // one touch per counter of the key",
+     "tests/test_oracle_semantics.py tests/test_oracle_pins.py -k 'filter or counter or tiny'"),
+    ("misses_refresh_last_seen_of_nothing_hits_do_not", "if (it != table_.end() && was_hit[i]) it->second.last_seen = step;",
+     "if (it != table_.end() && !was_hit[i]) it->second.last_seen = step;", "tests/test_oracle_semantics.py -k 'expiry or last_seen'"),
+    ("init_from_wrong_bits", "uint32_t u24 = (uint32_t)(h >> 40);", "uint32_t u24 = (uint32_t)(h >> 39) & 0xFFFFFFu;",
+     "tests/test_oracle_pins.py -k init"),
+    ("stash_forgotten_by_rehash", "    for (auto& st : stash_) all.push_back(st);\n", "", "tests/test_oracle_maintenance.py -k stash"),
+    ("restored_keys_leave_counters_alone", "if ((w & 255u) < least) set_filter_word(i, (w & ~255u) | least);", "",
+     "tests/test_oracle_maintenance.py -k restored_keys"),
     ("evicted_goes_to_same_table", "      side = 1 - side;  // the evicted element goes to its other sub-table",
      "      side = side;", "tests/test_oracle_pins.py -k cuckoo"),
 ]
@@ -52,6 +65,6 @@ def test_pins_fail_on_a_planted_mistake(tmp_path, name, old, new, tests):
     lib = tmp_path / "libmutant.so"
     subprocess.check_call(["g++", "-O1", "-std=c++17", "-shared", "-fPIC", str(src), "-o", str(lib)])
     env = dict(os.environ, MONOLITH_ORACLE_LIB=str(lib))
-    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider"] + tests.split(),
+    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider"] + shlex.split(tests),
                        cwd=ROOT, env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, timeout=300)
     assert r.returncode == 1, "the pins did not notice %s:\n%s" % (name, r.stdout.decode()[-600:])
