@@ -79,12 +79,12 @@ def algorithmic_bytes(kernel, s, wl):
     row = wl.dim * e
     n, nb = s["n"], s["n_bags"]
     if kernel == "probe_count":
-        # hit: bucket line + stamp; miss: counter read-modify-write, plus both bucket lines when counters can
-        # age (with expire_steps == 0 a counter below the threshold proves absence; the counter word of a
-        # hit is then read too)
+        # keys in, row indices out, one bucket line and a 4-byte stamp per distinct stored key, the counter
+        # sector of a distinct missing key read and written; where counters age a miss must also read both
+        # of its bucket lines (with expire_steps == 0 a counter below the threshold proves absence)
         if wl.expire_steps == 0:
-            return 12 * n + (128 + 2 * SECTOR) * s["u_hit"] + 2 * SECTOR * s["u_miss"]
-        return 12 * n + (128 + SECTOR) * s["u_hit"] + (256 + 2 * SECTOR) * s["u_miss"]
+            return 12 * n + (128 + 4) * s["u_hit"] + 2 * SECTOR * s["u_miss"]
+        return 12 * n + (128 + 4) * s["u_hit"] + (256 + 2 * SECTOR) * s["u_miss"]
     if kernel == "admit_elect":
         return 4 * n + 8 * s["n_miss"] + SECTOR * s["u_miss"] + 16 * s["u_new"]
     if kernel == "insert":

@@ -16,7 +16,7 @@ def test_kernel_bytes_no_expiry_fp32_dim32():
     wl = synth.CONFIGS["cfg2"]                       # dim 32 fp32 -> 128-byte rows, nothing ages
     S = 32
     b = lambda k: bench.algorithmic_bytes(k, STATS, wl)
-    assert b("probe_count") == 12 * 1000 + (128 + 2 * S) * 100 + 2 * S * 300
+    assert b("probe_count") == 12 * 1000 + (128 + 4) * 100 + 2 * S * 300
     assert b("admit_elect") == 4 * 1000 + 8 * 600 + S * 300 + 16 * 50
     assert b("insert") == 50 * (128 + 128 + 24)
     assert b("resolve") == 4 * 1000
@@ -30,7 +30,7 @@ def test_kernel_bytes_no_expiry_fp32_dim32():
 def test_kernel_bytes_with_expiry_bf16_dim64():
     wl = synth.CONFIGS["cfg5"]                       # dim 64 bf16 -> 128-byte rows, counters age
     S = 32
-    assert bench.algorithmic_bytes("probe_count", STATS, wl) == 12 * 1000 + (128 + S) * 100 + (256 + 2 * S) * 300
+    assert bench.algorithmic_bytes("probe_count", STATS, wl) == 12 * 1000 + (128 + 4) * 100 + (256 + 2 * S) * 300
     assert bench.algorithmic_bytes("sweep_find", STATS, wl) == 8 * wl.capacity
     assert bench.algorithmic_bytes("seg_reduce", STATS, wl) == 8 * 1000 + 4 * 64 * 250 + 2 * 128 * 150 + 8 * 150
 
