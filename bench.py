@@ -124,7 +124,7 @@ def time_maintenance(tab, wl, seed, max_ids, dev):
     snapshot into a fresh table, rehash into a table twice the size.  Bytes are the payloads moved."""
     import ctypes
     import torch
-    from paper_2209_07663_amd.binding import Table, _check, _p, _stream
+    from paper_2209_07663_amd.binding import Table, check as _check, device_pointer as _p, current_stream as _stream
     size = tab.mono_table_stats()["size"]
     keys = torch.empty(size, dtype=torch.int64, device=dev)
     row = torch.empty(size, dtype=torch.int32, device=dev)

@@ -83,6 +83,10 @@ def _p(t):
     return None if t is None else t.data_ptr()
 
 
+# the same helpers under public names, for callers that pass their own buffers straight to the library
+check, device_pointer, current_stream = _check, _p, _stream
+
+
 def _dev(t, dtype):
     assert t.is_cuda and t.dtype == dtype and t.is_contiguous(), "need a contiguous CUDA tensor of %s" % dtype
 

@@ -9,7 +9,7 @@ import torch
 
 from oracle import Oracle
 from paper_2209_07663_amd import synth
-from tests.test_gpu_parity import _SEEDS, compare_step
+from tests.test_gpu_parity import compare_step
 
 pytestmark = pytest.mark.gpu
 
@@ -34,7 +34,6 @@ def test_multi_hash_filter_matches_the_oracle(dev, name, hashes, filter_log2):
     wl, seed = _workload(name), 101 + hashes
     tab = Table(wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, max_ids=1 << 18,
                 max_bags=wl.n_bags, device=dev, filter_hashes=hashes, filter_log2=filter_log2)
-    _SEEDS[id(tab)] = seed
     orc = Oracle(wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, kind="cuckoo",
                  n_filter=tab.n_filter, filter_hashes=hashes)
     drift = synth.DriftMap(wl, seed) if wl.drift_frac > 0 else None
@@ -58,13 +57,11 @@ def test_growing_a_table_with_a_multi_hash_filter(dev):
                  n_filter=1 << 12, filter_hashes=hashes)
     drift = synth.DriftMap(wl, seed)
     batches = [synth.make_batch(wl, seed, s, with_grad=True, drift=drift) for s in range(6)]
-    _SEEDS[id(tab)] = seed
     for b in batches[:3]:
         compare_step(tab, orc, b, dev, 1e-5, exact_rows=False, train=True, sweep_at=b["step"])
     big = tab.rehashed(wl.capacity * 2, 0)                  # same hash functions, twice the room
     orc.rehash(wl.capacity * 2, 0)
     tab.close()
-    _SEEDS[id(big)] = seed
     assert big.n_filter == 1 << 13 and (big.mono_filter_export() == orc.filter_words()).all()
     for b in batches[3:]:
         compare_step(big, orc, b, dev, 1e-5, exact_rows=False, train=True, sweep_at=b["step"])

@@ -50,7 +50,7 @@ def compare_step(tab, orc, batch, dev, rtol, exact_rows, train, lr=0.05, eps=1e-
     st = tab.mono_table_stats()
     assert st["n_insert_failed"] == 0 and st["n_lost"] == 0 and st["n_full"] == 0 and orc.insert_failures == 0
     assert st["size"] == st["n_admitted"] - st["n_expired"] == d["keys"].shape[0]      # conservation
-    tc.check_placement(d, tab.capacity, 8, tab_seed(tab))
+    tc.check_placement(d, tab.capacity, 8, tab.seed)
     tc.assert_same_table(d, orc.dump(), exact_rows=exact_rows, rtol=rtol)
     pooled = tab.mono_gather_pool(rows, offs).cpu().numpy()
     worst = tc.rows_close(pooled, orc.pool(keys_h, offs_h), rtol)
@@ -72,16 +72,8 @@ def compare_step(tab, orc, batch, dev, rtol, exact_rows, train, lr=0.05, eps=1e-
         log.append((step, int(present.sum()), d["keys"].shape[0], worst))
 
 
-_SEEDS = {}
-
-
-def tab_seed(tab):
-    return _SEEDS[id(tab)]
-
-
 def run_stream(wl, seed, steps, dev, train=False, sweep=False, check_filter=True):
     tab = make_table(wl, seed, max_ids=int(wl.n_bags * (wl.poisson_lam + 1) * 1.3) + 64, dev=dev)
-    _SEEDS[id(tab)] = seed
     orc = make_oracle(wl, seed)
     drift = synth.DriftMap(wl, seed) if wl.drift_frac > 0 else None
     rtol = RTOL_BF16 if wl.bf16 else RTOL_F32
@@ -142,7 +134,6 @@ def test_edge_cases(dev):
     from paper_2209_07663_amd.binding import Table, MonoError
     seed = 77
     tab = Table(1 << 10, 8, seed, freq_threshold=2, expire_steps=2, max_ids=1 << 12, max_bags=1 << 12, device=dev)
-    _SEEDS[id(tab)] = seed
     orc = Oracle(1 << 10, 8, seed, 2, 2, False, kind="cuckoo")
     # empty batch
     empty = torch.empty(0, dtype=torch.int64, device=dev)
@@ -174,7 +165,6 @@ def test_high_load_without_failed_chains(dev):
     from paper_2209_07663_amd.binding import Table
     seed, cap = 9, 1 << 16
     tab = Table(cap, 4, seed, freq_threshold=1, max_ids=1 << 16, device=dev)
-    _SEEDS[id(tab)] = seed
     orc = Oracle(cap, 4, seed, 1, 0, False, kind="cuckoo")
     rng = np.random.default_rng(1)
     all_keys = rng.permutation(1 << 24)[: int(0.9 * cap)].astype(np.int64) * 1000003
@@ -192,7 +182,6 @@ def test_hot_key_gradient_reduction_is_pairwise(dev):
     from paper_2209_07663_amd.binding import Table
     seed, dim, n_bags = 10, 32, 100000
     tab = Table(1 << 16, dim, seed, freq_threshold=1, max_ids=1 << 19, max_bags=n_bags, device=dev)
-    _SEEDS[id(tab)] = seed
     orc = Oracle(1 << 16, dim, seed, 1, 0, False, kind="cuckoo")
     rng = np.random.default_rng(2)
     offs_h = np.arange(0, 4 * n_bags + 1, 4, dtype=np.int64)
@@ -228,7 +217,6 @@ def test_seeded_random_configurations(dev, case):
     max_ids = int(n_bags * (lam + 1) * 3) + 64
     tab = Table(cap, dim, seed, thr, expire, bf16, max_ids=max_ids, max_bags=n_bags, device=dev,
                 filter_hashes=hashes, filter_log2=filter_log2)
-    _SEEDS[id(tab)] = seed
     orc = Oracle(cap, dim, seed, thr, expire, bf16, kind="cuckoo", n_filter=tab.n_filter, filter_hashes=hashes)
     rtol = RTOL_BF16 if bf16 else RTOL_F32
     for step in range(5):

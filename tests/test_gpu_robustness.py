@@ -12,7 +12,7 @@ import torch
 from oracle import Oracle
 from paper_2209_07663_amd import synth
 from tests import table_checks as tc
-from tests.test_gpu_parity import _SEEDS, compare_step, RTOL_F32
+from tests.test_gpu_parity import compare_step, RTOL_F32
 
 pytestmark = pytest.mark.gpu
 
@@ -91,7 +91,6 @@ def test_calls_on_a_side_stream(dev):
     with torch.cuda.stream(side):
         tab = Table(wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16,
                     max_ids=1 << 18, max_bags=wl.n_bags, device=dev)
-        _SEEDS[id(tab)] = seed
         orc = Oracle(wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, kind="cuckoo")
         for step in range(3):
             b = synth.make_batch(wl, seed, step, with_grad=True)
@@ -111,7 +110,6 @@ def test_two_tables_used_in_turn(dev):
     for wl, seed in zip(wls, seeds):
         tab = Table(wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, max_ids=1 << 18,
                     max_bags=wl.n_bags, device=dev)
-        _SEEDS[id(tab)] = seed
         tabs.append(tab)
         orcs.append(Oracle(wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, kind="cuckoo"))
     for step in range(3):
@@ -128,7 +126,6 @@ def test_batch_of_exactly_the_announced_maximum(dev):
     from paper_2209_07663_amd.binding import Table, MonoError
     seed, dim, max_ids, max_bags = 51, 16, 20000, 5000
     tab = Table(1 << 16, dim, seed, freq_threshold=1, max_ids=max_ids, max_bags=max_bags, device=dev)
-    _SEEDS[id(tab)] = seed
     orc = Oracle(1 << 16, dim, seed, 1, 0, False, kind="cuckoo")
     rng = np.random.default_rng(6)
     keys_h = rng.integers(0, 30000, size=max_ids).astype(np.int64)
