@@ -47,7 +47,7 @@ typedef struct mono_stats {
   uint64_t n_expired;       /* keys removed by expire_sweep since creation */
   uint64_t n_insert_failed; /* eviction chains that hit the kick bound (element went to the stash) */
   uint64_t n_lost;          /* elements dropped because the stash was full too (must stay 0) */
-  uint64_t n_full;          /* admissible keys refused because no row was free */
+  uint64_t n_full;          /* admissible keys refused because the table was at its fill limit (see capacity) */
   uint64_t stash_size;      /* elements currently in the stash */
   uint64_t max_chain;       /* longest eviction chain seen */
 } mono_stats;
@@ -67,7 +67,7 @@ size_t mono_table_bytes(uint64_t capacity, uint32_t dim, uint32_t flags, uint64_
  *                   first sight; at most 255
  *   expire_steps    a key unseen for this many steps is removed by mono_expire_sweep; 0 = never
  *   flags           MONO_ROWS_FP32 or MONO_ROWS_BF16
- *   max_ids/max_bags largest batch any later call will pass (1 <= max_ids < 2^31)
+ *   max_ids/max_bags largest batch any later call will pass (1 <= max_ids <= 2^28, 1 <= max_bags <= max_ids + 1)
  *   d_arena         NULL: the library allocates (and frees in destroy) its own device memory;
  *                   else caller-owned device memory of arena_bytes >= mono_table_bytes(...),
  *                   256-byte aligned, which must outlive the table
