@@ -24,6 +24,11 @@
  *    stored.  Every other int64 bit pattern is a legal key.
  *  - `step` / `now` are the caller's training-step counter: non-decreasing from call to call and
  *    below 2^24.
+ *  - The step and a per-call tag of the table travel to the kernels as launch arguments, and the
+ *    export / import / migrate / stats calls copy to the host and wait: a call recorded into a HIP
+ *    graph would replay stale values.  Do not capture these calls; issue them on a live stream.
+ *  - A table belongs to the device that was current when it was created; make that device current
+ *    for every later call on it.
  */
 #ifndef MONOTABLE_H_
 #define MONOTABLE_H_

@@ -34,6 +34,8 @@ __host__ __device__ inline unsigned long long make_meta(uint32_t row, uint32_t s
 constexpr int kWinLists = 64;               // sub-lists of elected occurrences (spreads the append counter)
 constexpr int kWinStride = 32;              // u32 words between two sub-list counters (one 128-byte line each)
 
+constexpr int kSweepRemoved = 0;            // Control::scratch slot: keys removed so far by the running sweep
+constexpr int kExportCount = 1;             // Control::scratch slot: elements found by the running export
 constexpr int kValidPairs = 2;              // Control::scratch slot: (row, bag) pairs kept by the sort
 constexpr int kRefusedRecords = 3;          // Control::scratch slot: records refused by the running restore call
 
@@ -65,7 +67,7 @@ struct Control {
   uint32_t hwm;              // every row index ever handed out is below this high-water mark
   uint32_t pad_;
   unsigned long long n_admitted, n_expired, n_insert_failed, n_lost, n_full, max_chain;
-  unsigned long long scratch[8];  // per-call scalars: [0] sweep count, [1] export count, [kValidPairs]
+  unsigned long long scratch[8];  // per-call scalars, indexed by the constants above
 };
 
 // Everything a kernel needs to know about a table; passed by value.

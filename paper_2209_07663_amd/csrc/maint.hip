@@ -11,7 +11,7 @@ __device__ inline bool is_expired(const TableView& t, uint32_t now, uint32_t see
 }
 
 // Sweep in three kernels:
-//   sweep_begin  one thread: walks the (normally empty) stash; scratch[0] = keys removed so far
+//   sweep_begin  one thread: walks the (normally empty) stash; scratch[kSweepRemoved] = keys removed so far
 //   sweep_find   one thread per slot, read-only: slots whose stamp is too old are appended to one of
 //                kWinLists lists (one atomic per block, spread over the lists)
 //   sweep_remove dense over the found slots: pushes the row on the free stack by rank, reports the
@@ -34,7 +34,7 @@ __global__ void sweep_begin_kernel(TableView t, uint32_t now, int64_t* expired_k
     }
   }
   c->stash_n = sn;
-  c->scratch[0] = removed;
+  c->scratch[kSweepRemoved] = removed;
 }
 
 __global__ __launch_bounds__(256) void sweep_find_kernel(TableView t, uint32_t now) {
@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void sweep_remove_kernel(TableView t, int64_t*
   }
   const uint32_t total = __shfl(inc, 63);
   const int32_t free0 = t.ctl->free_n;                     // constant during this kernel
-  const unsigned long long out0 = t.ctl->scratch[0];       // keys already reported from the stash
+  const unsigned long long out0 = t.ctl->scratch[kSweepRemoved];       // keys already reported from the stash
   const uint32_t stride = gridDim.x * blockDim.x;
   for (uint32_t w0 = blockIdx.x * blockDim.x + (threadIdx.x & ~63u); w0 < total; w0 += stride) {
     const uint32_t w = w0 + lane;
@@ -111,7 +111,7 @@ __global__ void sweep_end_kernel(TableView t, uint64_t* n_expired) {
     t.sweep_cnt[l * kWinStride] = 0;
   }
   t.ctl->free_n += (int32_t)total;
-  const unsigned long long removed = t.ctl->scratch[0] + total;
+  const unsigned long long removed = t.ctl->scratch[kSweepRemoved] + total;
   t.ctl->n_expired += removed;
   if (n_expired) *n_expired = removed;
 }
@@ -138,7 +138,7 @@ hipError_t launch_expire_sweep(const TableView& t, uint32_t now, uint64_t* d_n_e
 // ---- dump --------------------------------------------------------------------------------------
 
 __global__ void export_begin_kernel(TableView t) {
-  if (blockIdx.x == 0 && threadIdx.x == 0) t.ctl->scratch[1] = 0;
+  if (blockIdx.x == 0 && threadIdx.x == 0) t.ctl->scratch[kExportCount] = 0;
 }
 
 constexpr int kExportBlock = 1024;
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(kExportBlock) void export_kernel(TableView t, int64
   if (threadIdx.x == 0) {
     uint32_t found = 0;
     for (int w = 0; w < kExportBlock / 64; ++w) found += wave_cnt[w];
-    block_base = found ? atomicAdd(&t.ctl->scratch[1], (unsigned long long)found) : 0ull;
+    block_base = found ? atomicAdd(&t.ctl->scratch[kExportCount], (unsigned long long)found) : 0ull;
   }
   __syncthreads();
   if (live) {

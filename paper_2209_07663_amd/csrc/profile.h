@@ -48,7 +48,12 @@ class ProfScope {
   ProfScope(Profiler* p, int id, hipStream_t s) : p_(p && p->on ? p : nullptr), s_(s) {
     if (!p_) return;
     rec_.id = id;
-    if (hipEventCreate(&rec_.start) != hipSuccess || hipEventCreate(&rec_.stop) != hipSuccess) {
+    if (hipEventCreate(&rec_.start) != hipSuccess) {
+      p_ = nullptr;
+      return;
+    }
+    if (hipEventCreate(&rec_.stop) != hipSuccess) {
+      (void)hipEventDestroy(rec_.start);
       p_ = nullptr;
       return;
     }

@@ -216,6 +216,10 @@ int mono_table_destroy(mono_table* t) {
   int rc = MONO_OK;
   if (hipDeviceSynchronize() != hipSuccess) rc = MONO_EHIP;
   if (t->owned_arena && hipFree(t->owned_arena) != hipSuccess) rc = MONO_EHIP;
+  for (auto& r : t->prof.recs) {  // timings nobody read
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
+  }
   delete t;
   return rc;
 }
@@ -292,7 +296,7 @@ int mono_table_export(mono_table* t, int64_t* d_keys, int32_t* d_row, uint32_t* 
   hipStream_t s = (hipStream_t)stream;
   if (launch_export(t->view, d_keys, d_row, d_last_seen, d_slot, max_n, false, s) != hipSuccess) return MONO_EHIP;
   unsigned long long n = 0;
-  if (hipMemcpyAsync(&n, &t->view.ctl->scratch[1], sizeof(n), hipMemcpyDeviceToHost, s) != hipSuccess ||
+  if (hipMemcpyAsync(&n, &t->view.ctl->scratch[kExportCount], sizeof(n), hipMemcpyDeviceToHost, s) != hipSuccess ||
       hipStreamSynchronize(s) != hipSuccess)
     return MONO_EHIP;
   *h_n = n;
@@ -311,7 +315,7 @@ int mono_export_touched(mono_table* t, int64_t* d_keys, int32_t* d_row, float* d
   hipStream_t s = (hipStream_t)stream;
   if (launch_export(t->view, d_keys, d_row, nullptr, nullptr, max_n, true, s) != hipSuccess) return MONO_EHIP;
   unsigned long long n = 0;
-  if (hipMemcpyAsync(&n, &t->view.ctl->scratch[1], sizeof(n), hipMemcpyDeviceToHost, s) != hipSuccess ||
+  if (hipMemcpyAsync(&n, &t->view.ctl->scratch[kExportCount], sizeof(n), hipMemcpyDeviceToHost, s) != hipSuccess ||
       hipStreamSynchronize(s) != hipSuccess)
     return MONO_EHIP;
   *h_n = n;
@@ -363,7 +367,8 @@ int mono_table_migrate(mono_table* dst, mono_table* src, uint32_t generation, vo
   if (b.capacity < a.capacity || b.dim != a.dim || b.bf16 != a.bf16 || dst->seed != src->seed ||
       b.freq_threshold != a.freq_threshold || b.expire_steps != a.expire_steps || dst->epoch != 0 ||
       dst->last_step != 0 || b.filter_hashes != a.filter_hashes ||
-      b.n_filter * a.capacity != a.n_filter * b.capacity)  // the counter array grows with the table
+      b.n_filter < a.n_filter ||
+      b.n_filter / a.n_filter != b.capacity / a.capacity)  // the counter array grows with the table (powers of two)
     return MONO_EINVAL;  // dst must be a fresh table with the same parameters
   hipStream_t s = (hipStream_t)stream;
   Control c;

@@ -240,6 +240,43 @@ def test_growing_an_overfull_table_empties_its_stash_and_makes_room(dev):
     big.close()
 
 
+@pytest.mark.parametrize("cap", [1 << 12, 1 << 20])
+def test_rehash_at_the_fill_limit_loses_nothing(dev, cap):
+    """A table filled to its limit (31/32 of the rows) moves to new hash functions at the SAME size:
+    every element is re-inserted at once into an empty table, the hardest case for the eviction chains.
+    Nothing may be lost; an element whose chain hits the bound is kept in the stash and still found."""
+    from paper_2209_07663_amd.binding import Table
+    seed, dim, max_ids = 97, 4, 1 << 18
+    tab = Table(cap, dim, seed, freq_threshold=1, max_ids=max_ids, max_bags=1, device=dev)
+    universe = (np.random.default_rng(9).permutation(4 * cap)[: cap + cap // 8].astype(np.int64) + 1) * 7919
+    held = {}
+    for step, lo in enumerate(range(0, universe.shape[0], max_ids)):
+        chunk = universe[lo:lo + max_ids]
+        rows = tab.mono_lookup_or_insert(torch.from_numpy(chunk).to(dev), step).cpu().numpy()
+        held.update({k: r for k, r in zip(chunk.tolist(), rows.tolist()) if r >= 0})
+    limit = cap - cap // 32
+    st = tab.mono_table_stats()
+    assert st["size"] == len(held) == limit and st["n_lost"] == 0 and st["n_full"] > 0
+    keys_now = np.array(sorted(held), dtype=np.int64)
+    rows_now = np.array([held[k] for k in keys_now.tolist()])
+    for generation in (1, 2, 3):
+        print("rehash at the fill limit: capacity", cap, "generation", generation, flush=True)
+        new = tab.rehashed(cap, generation)
+        tab.close()
+        tab = new
+        st = tab.mono_table_stats()
+        assert st["n_lost"] == 0 and st["size"] == limit, st
+        d = tab.mono_table_export()
+        tc.check_placement(d, cap, 8, seed, generation)
+        assert d["keys"].tolist() == keys_now.tolist() and (d["row"] == rows_now).all()
+        assert int((d["slot"] < 0).sum()) == st["stash_size"] <= 16    # the stash is a last resort, not a shelf
+        assert (d["rows"] == tc.init_rows(d["keys"], dim, seed).astype(np.float32)).all()
+        for lo in range(0, limit, max_ids):                              # every key is found, at its row
+            got = tab.mono_lookup_or_insert(torch.from_numpy(keys_now[lo:lo + max_ids]).to(dev), 100 + generation)
+            assert (got.cpu().numpy() == rows_now[lo:lo + max_ids]).all()
+    tab.close()
+
+
 def test_long_stream_with_every_operation(dev):
     """Forty steps of a drifting stream with expiry: lookup, pool, update and sweep every step, a
     synchronisation every seventh, a grow under new hash functions at step 15, a snapshot + restore
