@@ -10,12 +10,13 @@ __device__ inline bool is_expired(const TableView& t, uint32_t now, uint32_t see
   return t.expire_steps > 0 && now >= seen && now - seen >= t.expire_steps;
 }
 
-// Sweep in three kernels:
+// Sweep in four kernels:
 //   sweep_begin  one thread: walks the (normally empty) stash; scratch[kSweepRemoved] = keys removed so far
 //   sweep_find   one thread per slot, read-only: slots whose stamp is too old are appended to one of
 //                kWinLists lists (one atomic per block, spread over the lists)
 //   sweep_remove dense over the found slots: pushes the row on the free stack by rank, reports the
-//                key, clears the slot; one thread settles the counters
+//                key, clears the slot
+//   sweep_end    one thread settles the counters
 __global__ void sweep_begin_kernel(TableView t, uint32_t now, int64_t* expired_keys, uint64_t max_expired) {
   if (blockIdx.x != 0 || threadIdx.x != 0) return;
   Control* c = t.ctl;
@@ -63,8 +64,7 @@ __global__ __launch_bounds__(256) void sweep_find_kernel(TableView t, uint32_t n
   }
 }
 
-__global__ __launch_bounds__(256) void sweep_remove_kernel(TableView t, int64_t* expired_keys, uint64_t max_expired,
-                                                           uint64_t* n_expired) {
+__global__ __launch_bounds__(256) void sweep_remove_kernel(TableView t, int64_t* expired_keys, uint64_t max_expired) {
   const uint32_t lane = lane_id();
   uint32_t inc = t.sweep_cnt[lane * kWinStride];
 #pragma unroll
@@ -99,8 +99,7 @@ __global__ __launch_bounds__(256) void sweep_remove_kernel(TableView t, int64_t*
       b->key[l] = kEmptyKey;
     }
   }
-  // the last block to get here cannot be known cheaply; the counters are settled by sweep_end
-  (void)n_expired;
+  // (which block finishes last cannot be known cheaply: the counters are settled by sweep_end)
 }
 
 __global__ void sweep_end_kernel(TableView t, uint64_t* n_expired) {
@@ -130,7 +129,7 @@ hipError_t launch_expire_sweep(const TableView& t, uint32_t now, uint64_t* d_n_e
   const dim3 block(256), grid((unsigned)((t.capacity + 255) / 256));
   MONO_LAUNCH(prof, K_SWEEP, stream, sweep_find_kernel, grid, block, t, now);
   MONO_LAUNCH(prof, K_SWEEP_REMOVE, stream, sweep_remove_kernel, dim3(grid.x < 2048u ? grid.x : 2048u), block, t,
-              d_expired_keys, max_expired, d_n_expired);
+              d_expired_keys, max_expired);
   MONO_LAUNCH(prof, K_SWEEP_END, stream, sweep_end_kernel, dim3(1), dim3(64), t, d_n_expired);
   return hipGetLastError();
 }
