@@ -193,3 +193,56 @@ def test_config4_filled_to_load_09_then_streaming_steps():
         assert st["size"] == stored.shape[0] and st["n_insert_failed"] == 0 and st["n_lost"] == 0 and st["n_full"] == 0
     assert stored.shape[0] > hot.shape[0]                      # keys keep being admitted at load 0.9
     tab.close()
+
+
+@pytest.mark.timeout(600)
+def test_update_with_more_than_16M_rows_in_use():
+    """Beyond 2^24 rows in use the backward's sort needs a fourth pass (25 bits in passes of seven).
+    17 M keys are admitted on both sides (threshold 1, dim 4 keeps the oracle small), then one batch
+    whose occurrences reach rows over the whole range — every 64th key once, the lowest and highest
+    rows many times, absent and padding keys — is trained and the whole table compared."""
+    from paper_2209_07663_amd.binding import Table
+    dev = torch.device("cuda:0")
+    seed, dim, cap, chunk_n = 13, 4, 1 << 25, 1 << 22
+    stored = (1 << 24) + 100_000
+    tab = Table(cap, dim, seed, freq_threshold=1, max_ids=chunk_n, max_bags=chunk_n, device=dev)
+    orc = Oracle(cap, dim, seed, 1, 0, False, kind="cuckoo")
+    rng = np.random.default_rng(17)
+    keys_all = (np.arange(stored, dtype=np.int64) * 2654435761 + 12345) ^ 0x5DEECE66D   # distinct (odd multiplier)
+    assert np.unique(keys_all).shape[0] == stored
+    top_key, low_key = None, None
+    for step, lo in enumerate(range(0, stored, chunk_n)):
+        print("17M rows: admitting chunk", step, flush=True)
+        chunk = keys_all[lo:lo + chunk_n]
+        r = tab.mono_lookup_or_insert(torch.from_numpy(chunk).to(dev), step).cpu().numpy()
+        assert orc.lookup_or_insert(chunk, step).all() and (r >= 0).all()
+        if lo == 0:
+            low_key = chunk[np.argmin(r)]
+        top_key = chunk[np.argmax(r)]
+    st = tab.mono_table_stats()
+    assert st["size"] == stored and st["n_insert_failed"] == 0 and st["n_full"] == 0
+    body = np.concatenate([keys_all[::64], np.repeat([low_key, top_key], 500),
+                           np.array([-1, -9, 4242], dtype=np.int64), keys_all[-3000:]])
+    keys_h = body[rng.permutation(body.shape[0])]
+    offs_h = np.arange(0, keys_h.shape[0] + 1, 3, dtype=np.int64)
+    offs_h[-1] = keys_h.shape[0]
+    grad_h = rng.standard_normal((offs_h.shape[0] - 1, dim)).astype(np.float32)
+    step = 10
+    print("17M rows: training step", flush=True)
+    rows = tab.mono_lookup_or_insert(torch.from_numpy(keys_h).to(dev), step)
+    present = orc.lookup_or_insert(keys_h, step)
+    rows_h = rows.cpu().numpy()
+    assert ((rows_h >= 0) == present).all()
+    assert rows_h.max() >= (1 << 24)                                   # the batch does reach the top rows
+    offs = torch.from_numpy(offs_h).to(dev)
+    pooled = tab.mono_gather_pool(rows, offs).cpu().numpy()
+    tc.rows_close(pooled, orc.pool(keys_h, offs_h), 1e-5)
+    tab.mono_apply_grad_adagrad(rows, offs, torch.from_numpy(grad_h).to(dev), 0.1, 1e-6)
+    orc.apply_grad_adagrad(keys_h, offs_h, grad_h, 0.1, 1e-6)
+    print("17M rows: comparing the tables", flush=True)
+    d = tab.mono_table_export()
+    tc.check_placement(d, cap, 8, seed)
+    tc.assert_same_table(d, orc.dump(), exact_rows=False, rtol=1e-5)
+    trained = np.isin(d["keys"], keys_h)
+    assert (d["acc"][trained] > 0).all() and (d["acc"][~trained] == 0).all()
+    tab.close()

@@ -194,6 +194,43 @@ def test_hot_key_gradient_reduction_is_pairwise(dev):
     tab.close()
 
 
+@pytest.mark.parametrize("stored", [255, 256, 257, 65535, 65536, 65537, 65538])
+def test_update_at_the_sort_width_boundaries(dev, stored):
+    """The backward sorts bit_length(highest row in use) bits, in passes of at most eight: with 256 /
+    257 and 65536 / 65537 rows in use the digit plan changes (one pass -> two -> three).  Exactly
+    `stored` keys are admitted, then a batch over all of them (every key once, the first and the
+    last rows many times, some absent keys) is trained and compared with the oracle."""
+    # stored = highest row + 1: 256 -> 8 bits, 257 -> 9 bits (two passes), 65536 -> 16, 65537 -> 17 (three)
+    from paper_2209_07663_amd.binding import Table
+    seed, dim, cap = 71, 4, 1 << 18
+    tab = Table(cap, dim, seed, freq_threshold=2, max_ids=1 << 17, max_bags=1 << 17, device=dev)
+    orc = Oracle(cap, dim, seed, 2, 0, False, kind="cuckoo")
+    rng = np.random.default_rng(stored)
+    keys_all = (rng.permutation(1 << 22)[:stored].astype(np.int64) + 3) * 1000003
+    rows_of = {}
+    for step, lo in enumerate(range(0, stored, 1 << 16)):
+        chunk = keys_all[lo:lo + (1 << 16)]
+        for _ in range(2):                                          # second sight admits (threshold 2)
+            r = tab.mono_lookup_or_insert(torch.from_numpy(chunk).to(dev), step).cpu().numpy()
+            orc.lookup_or_insert(chunk, step)
+        rows_of.update(zip(chunk.tolist(), r.tolist()))
+    assert sorted(rows_of.values()) == list(range(stored))          # rows are handed out in ascending order
+    by_row = np.array(sorted(rows_of, key=rows_of.get), dtype=np.int64)
+    first, last = by_row[0], by_row[-1]
+    absent = np.array([-5, -1, 12345, 777], dtype=np.int64)
+    body = np.concatenate([keys_all, np.repeat([first, last], 300), absent, by_row[-40:], by_row[:40]])
+    keys_h = body[rng.permutation(body.shape[0])]
+    lengths = rng.integers(0, 4, size=keys_h.shape[0])              # ragged bags, empty ones included
+    offs_h = np.concatenate([[0], np.cumsum(lengths)])
+    offs_h = offs_h[: np.searchsorted(offs_h, keys_h.shape[0]) + 1].astype(np.int64)
+    offs_h[-1] = keys_h.shape[0]
+    grad_h = rng.standard_normal((offs_h.shape[0] - 1, dim)).astype(np.float32)
+    batch = {"keys": keys_h, "offsets": offs_h, "grad": grad_h, "step": 10}
+    # (threshold 2: the absent keys of this batch are seen once and stay out, the mark stays at `stored`)
+    compare_step(tab, orc, batch, dev, RTOL_F32, exact_rows=True, train=True, lr=0.1, eps=1e-6)
+    tab.close()
+
+
 @pytest.mark.parametrize("case", range(12))
 def test_seeded_random_configurations(dev, case):
     """Combinations that no named configuration covers: a seeded draw of dim, storage type, threshold,
