@@ -131,7 +131,7 @@ def time_maintenance(tab, wl, seed, max_ids, dev):
     seen = torch.empty(size, dtype=torch.int32, device=dev)
     vals = torch.empty((size, wl.dim), dtype=torch.float32, device=dev)
     acc = torch.empty(size, dtype=torch.float32, device=dev)
-    words = torch.empty(4 * wl.capacity, dtype=torch.int32, device=dev)
+    words = torch.empty(tab.n_filter, dtype=torch.int32, device=dev)
     got = ctypes.c_uint64()
     rec = 8 + 4 * wl.dim + 4 + 4                     # key, fp32 row, accumulator, last-seen / row index
     res = {}
@@ -150,9 +150,9 @@ def time_maintenance(tab, wl, seed, max_ids, dev):
                              "window": "every update since the table was created"}
     ms = timed(lambda: (_check(tab.lib.mono_table_export(tab.h, _p(keys), _p(row), _p(seen), None, _p(vals), _p(acc),
                                                          size, ctypes.byref(got), _stream()), "mono_table_export"),
-                        _check(tab.lib.mono_filter_export(tab.h, _p(words), 0, 4 * wl.capacity, _stream()),
+                        _check(tab.lib.mono_filter_export(tab.h, _p(words), 0, tab.n_filter, _stream()),
                                "mono_filter_export")))
-    snap_bytes = size * rec + 4 * 4 * wl.capacity
+    snap_bytes = size * rec + 4 * tab.n_filter
     res["snapshot"] = {"keys": size, "ms": round(ms, 3), "payload_GBps": round(snap_bytes / ms / 1e6, 1)}
     fresh = Table(wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, max_ids=max_ids,
                   max_bags=wl.n_bags, device=dev)
@@ -315,7 +315,10 @@ def main():
         achieved = algorithmic_bytes(dom, mean, wl) / (prof[dom][0] / prof[dom][1]) / 1e6
         roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                    "traffic": MEASURED_TRAFFIC.get(wl.name, {}).get(dom)}
+                    "traffic": MEASURED_TRAFFIC.get(wl.name, {}).get(dom),
+                    "timing": "HIP events around every launch on the library's stream, over the %d steps that "
+                              "follow the timed ones on the same stream of batches (with events in the timed steps "
+                              "the step takes 15 % longer, so those run without)" % len(stats)}
         sb = step_bytes(mean, wl, sweep_every)
         step_roof = {"algorithmic_bytes_per_step": int(sb),
                      "achieved_GBps": round(sb / (np.median(step_ms) * 1e-3) / 1e9, 1),

@@ -75,8 +75,9 @@ def _check(rc, what):
         raise MonoError("%s: %s (%d)" % (what, load_library().mono_strerror(rc).decode(), rc))
 
 
-def _stream():
-    return torch.cuda.current_stream().cuda_stream
+def _stream(device=None):
+    """torch's current stream on `device` (default: the current device), as a hipStream_t."""
+    return torch.cuda.current_stream(device).cuda_stream
 
 
 def _p(t):
@@ -88,7 +89,8 @@ check, device_pointer, current_stream = _check, _p, _stream
 
 
 def _dev(t, dtype):
-    assert t.is_cuda and t.dtype == dtype and t.is_contiguous(), "need a contiguous CUDA tensor of %s" % dtype
+    if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError("need a contiguous CUDA tensor of %s" % dtype)
 
 
 class Table:
@@ -115,8 +117,11 @@ class Table:
             _check(self.lib.mono_table_create_ex(ctypes.byref(h), self.capacity, self.dim, seed, freq_threshold,
                                                  expire_steps, flags, self.max_ids, self.max_bags,
                                                  self.filter_hashes, self.filter_log2, self.arena.data_ptr(), nbytes,
-                                                 _stream()), "mono_table_create_ex")
+                                                 _stream(self.device)), "mono_table_create_ex")
         self.h = h
+
+    def _s(self):
+        return _stream(self.device)
 
     def close(self):
         if getattr(self, "h", None):
@@ -132,7 +137,7 @@ class Table:
         if rows_out is None:
             rows_out = torch.empty(keys.shape[0], dtype=torch.int32, device=keys.device)
         _dev(rows_out, torch.int32)
-        _check(self.lib.mono_lookup_or_insert(self.h, _p(keys), keys.shape[0], step, _p(rows_out), _stream()),
+        _check(self.lib.mono_lookup_or_insert(self.h, _p(keys), keys.shape[0], step, _p(rows_out), self._s()),
                "mono_lookup_or_insert")
         return rows_out
 
@@ -143,7 +148,7 @@ class Table:
         if out is None:
             out = torch.empty((n_bags, self.dim), dtype=torch.float32, device=rows.device)
         _dev(out, torch.float32)
-        _check(self.lib.mono_gather_pool(self.h, _p(rows), rows.shape[0], _p(offsets), n_bags, _p(out), _stream()),
+        _check(self.lib.mono_gather_pool(self.h, _p(rows), rows.shape[0], _p(offsets), n_bags, _p(out), self._s()),
                "mono_gather_pool")
         return out
 
@@ -152,9 +157,10 @@ class Table:
         _dev(offsets, torch.int64)
         _dev(grad, torch.float32)
         n_bags = offsets.shape[0] - 1
-        assert grad.numel() == n_bags * self.dim
+        if grad.numel() != n_bags * self.dim:
+            raise ValueError("grad must hold n_bags * dim elements")
         _check(self.lib.mono_apply_grad_adagrad(self.h, _p(rows), rows.shape[0], _p(offsets), n_bags, _p(grad), lr,
-                                                eps, _stream()), "mono_apply_grad_adagrad")
+                                                eps, self._s()), "mono_apply_grad_adagrad")
 
     def mono_expire_sweep(self, now, n_expired=None, expired_keys=None):
         max_expired = 0
@@ -163,12 +169,12 @@ class Table:
             max_expired = expired_keys.shape[0]
         if n_expired is not None:
             _dev(n_expired, torch.int64)
-        _check(self.lib.mono_expire_sweep(self.h, now, _p(n_expired), _p(expired_keys), max_expired, _stream()),
+        _check(self.lib.mono_expire_sweep(self.h, now, _p(n_expired), _p(expired_keys), max_expired, self._s()),
                "mono_expire_sweep")
 
     def mono_table_stats(self):
         st = mono_stats()
-        _check(self.lib.mono_table_stats(self.h, ctypes.byref(st), _stream()), "mono_table_stats")
+        _check(self.lib.mono_table_stats(self.h, ctypes.byref(st), self._s()), "mono_table_stats")
         return {n: int(getattr(st, n)) for n, _ in mono_stats._fields_}
 
     def mono_table_export(self, with_values=True):
@@ -183,7 +189,7 @@ class Table:
         acc = torch.empty(n, dtype=torch.float32, device=dev) if with_values else None
         got = _u64()
         _check(self.lib.mono_table_export(self.h, _p(keys), _p(row), _p(seen), _p(slot), _p(vals), _p(acc), n,
-                                          ctypes.byref(got), _stream()), "mono_table_export")
+                                          ctypes.byref(got), self._s()), "mono_table_export")
         if got.value != n:
             raise MonoError("mono_table_export: %d keys stored but %d rows in use" % (got.value, n))
         k = keys.cpu().numpy()
@@ -206,7 +212,7 @@ class Table:
         acc = torch.empty(max_n, dtype=torch.float32, device=dev) if with_values else None
         got = _u64()
         _check(self.lib.mono_export_touched(self.h, _p(keys), _p(row), _p(vals), _p(acc), max_n, ctypes.byref(got),
-                                            _stream()), "mono_export_touched")
+                                            self._s()), "mono_export_touched")
         n = got.value
         if n > max_n:
             return {"n": n}
@@ -223,23 +229,24 @@ class Table:
         max_ids at a time; returns how many were refused."""
         _dev(keys, torch.int64), _dev(values, torch.float32), _dev(acc, torch.float32), _dev(last_seen, torch.int32)
         n, refused = keys.shape[0], 0
-        assert values.shape == (n, self.dim) and acc.shape[0] == n and last_seen.shape[0] == n
+        if values.shape != (n, self.dim) or acc.shape[0] != n or last_seen.shape[0] != n:
+            raise ValueError("values [n, dim], acc [n] and last_seen [n] must match the n keys")
         for lo in range(0, n, self.max_ids):
             hi = min(n, lo + self.max_ids)
             r = _u64()
             _check(self.lib.mono_table_import(self.h, _p(keys[lo:hi]), _p(values[lo:hi]), _p(acc[lo:hi]),
-                                              _p(last_seen[lo:hi]), hi - lo, ctypes.byref(r), _stream()),
+                                              _p(last_seen[lo:hi]), hi - lo, ctypes.byref(r), self._s()),
                    "mono_table_import")
             refused += r.value
         return refused
 
     def mono_filter_import(self, words, first=0):
         _dev(words, torch.int32)
-        _check(self.lib.mono_filter_import(self.h, _p(words), first, words.shape[0], _stream()), "mono_filter_import")
+        _check(self.lib.mono_filter_import(self.h, _p(words), first, words.shape[0], self._s()), "mono_filter_import")
 
     def mono_table_migrate(self, src, generation):
         """Fills this (fresh) table with everything `src` holds, under the hash functions of `generation`."""
-        _check(self.lib.mono_table_migrate(self.h, src.h, generation, _stream()), "mono_table_migrate")
+        _check(self.lib.mono_table_migrate(self.h, src.h, generation, self._s()), "mono_table_migrate")
 
     def rehashed(self, new_capacity, generation):
         """A new table of `new_capacity` >= capacity holding this table's contents (this one stays as it is)."""
@@ -263,5 +270,5 @@ class Table:
     def mono_filter_export(self, first=0, count=None):
         count = self.n_filter - first if count is None else count
         words = torch.empty(count, dtype=torch.int32, device=self.device)
-        _check(self.lib.mono_filter_export(self.h, _p(words), first, count, _stream()), "mono_filter_export")
+        _check(self.lib.mono_filter_export(self.h, _p(words), first, count, self._s()), "mono_filter_export")
         return words.cpu().numpy().view("uint32")
