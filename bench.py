@@ -318,7 +318,7 @@ def main():
                     "traffic": MEASURED_TRAFFIC.get(wl.name, {}).get(dom),
                     "timing": "HIP events around every launch on the library's stream, over the %d steps that "
                               "follow the timed ones on the same stream of batches (with events in the timed steps "
-                              "the step takes 15 % longer, so those run without)" % len(stats)}
+                              "the step takes 15 %% longer, so those run without)" % len(stats)}
         sb = step_bytes(mean, wl, sweep_every)
         step_roof = {"algorithmic_bytes_per_step": int(sb),
                      "achieved_GBps": round(sb / (np.median(step_ms) * 1e-3) / 1e9, 1),
