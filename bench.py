@@ -29,7 +29,7 @@ SECTOR = 32             # bytes: smallest HBM access counted for a random 4/8-by
 # on the default workload, scaled by the factors a plain 1 GiB copy gives (2.0 and 1.0); the runs and
 # the table are in profiles/bench_cfg2_full_step.md.  Workloads that were not profiled report null.
 MEASURED_TRAFFIC = {
-    "cfg2": {"probe_count": 881.0e6, "seg_reduce": 986.5e6, "gather_pool": 502.8e6, "admit_elect": 361.5e6,
+    "cfg2": {"probe_count": 882.9e6, "seg_reduce": 985.7e6, "gather_pool": 503.1e6, "admit_elect": 361.5e6,
              "sort_scatter": 121.3e6, "sort_hist": 58.2e6, "insert": 103.8e6},
 }
 
