@@ -45,6 +45,17 @@ MUTATIONS = [
     ("stash_forgotten_by_rehash", "    for (auto& st : stash_) all.push_back(st);\n", "", "tests/test_oracle_maintenance.py -k stash"),
     ("restored_keys_leave_counters_alone", "if ((w & 255u) < least) set_filter_word(i, (w & ~255u) | least);", "",
      "tests/test_oracle_maintenance.py -k restored_keys"),
+    ("touched_set_is_never_emptied", "    touched_.clear();\n", "", "tests/test_oracle_maintenance.py -k touched"),
+    ("rehash_keeps_the_old_placement_salts", "    p_.s_h0 = salt(placement_seed(p_.seed, generation), 0);",
+     "    p_.s_h0 = salt(placement_seed(p_.seed, 0), 0);", "tests/test_oracle_maintenance.py -k rehash"),
+    ("gradient_of_the_neighbouring_bag", "(double)grad[b * p_.dim + j];", "(double)grad[(b ? b - 1 : 0) * p_.dim + j];",
+     "tests/test_oracle_pins.py -k update_equals"),
+    ("counter_index_from_the_low_bits", "    return top_bits(mix64(key ^ p_.s_filter[j]), p_.lg_filter);",
+     "    return mix64(key ^ p_.s_filter[j]) & (p_.n_filter - 1);",
+     "tests/test_oracle_maintenance.py tests/test_oracle_filter.py -k 'grow or count_min'"),
+    ("new_keys_are_stamped_with_step_zero", "  e->last_seen = step;", "  e->last_seen = 0;",
+     "tests/test_oracle_semantics.py -k expiry"),
+    ("accumulator_starts_at_one", "  e->acc = 0.0f;", "  e->acc = 1.0f;", "tests/test_oracle_pins.py -k 'update_equals or torch_adagrad'"),
     ("evicted_goes_to_same_table", "      side = 1 - side;  // the evicted element goes to its other sub-table",
      "      side = side;", "tests/test_oracle_pins.py -k cuckoo"),
 ]
