@@ -160,6 +160,29 @@ def test_edge_cases(dev):
     tab.close()
 
 
+@pytest.mark.parametrize("dim,bf16", [(4, False), (8, False), (32, False), (64, True), (100, False), (256, False)])
+def test_short_bags_of_zero_one_or_two_ids(dev, dim, bf16):
+    """Bags of at most two IDs take a path of their own in the pooling kernel (several rounds of row
+    reads in flight); a last stretch with one long bag sends the final waves down the general path."""
+    from paper_2209_07663_amd.binding import Table
+    seed, cap = 83, 1 << 14
+    tab = Table(cap, dim, seed, freq_threshold=1, bf16=bf16, max_ids=1 << 14, max_bags=1 << 14, device=dev)
+    orc = Oracle(cap, dim, seed, 1, 0, bf16, kind="cuckoo")
+    rng = np.random.default_rng(dim)
+    lengths = rng.integers(0, 3, size=5000)
+    lengths[-70:] = rng.integers(0, 3, size=70)
+    lengths[-20] = 11                                                # one long bag among short ones
+    n = int(lengths.sum())
+    keys_h = rng.integers(0, 3000, size=n).astype(np.int64)
+    keys_h[rng.integers(0, n, size=50)] = -1                         # padding keys: absent
+    offs_h = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
+    grad_h = rng.standard_normal((lengths.shape[0], dim)).astype(np.float32)
+    for step in range(2):
+        compare_step(tab, orc, {"keys": keys_h, "offsets": offs_h, "grad": grad_h, "step": step}, dev,
+                     RTOL_BF16 if bf16 else RTOL_F32, exact_rows=False, train=True)
+    tab.close()
+
+
 def test_high_load_without_failed_chains(dev):
     """Drive a table to load 0.9 (configs[3] asks for it) and check every invariant."""
     from paper_2209_07663_amd.binding import Table
