@@ -2,6 +2,7 @@
 import ctypes
 import os
 import re
+import subprocess
 
 import pytest
 
@@ -57,3 +58,33 @@ def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "missing.so"))
     with pytest.raises(RuntimeError):
         binding.load_library()
+
+
+C_PROGRAM = r"""
+#include <stdio.h>
+#include "monotable.h"
+int main(void) {
+  /* host-only calls: the size query validates its arguments, the error strings are static */
+  size_t ok = mono_table_bytes((uint64_t)1 << 16, 16, MONO_ROWS_FP32, 4096, 4096);
+  size_t bad = mono_table_bytes(1000, 16, MONO_ROWS_FP32, 4096, 4096);
+  mono_stats st;
+  st.capacity = 0;
+  printf("%zu %zu %s %d\n", ok, bad, mono_strerror(MONO_EINVAL), (int)sizeof(st));
+  return (ok > 0 && bad == 0) ? 0 : 1;
+}
+"""
+
+
+def test_header_is_plain_c_and_a_c_program_links_against_the_library(lib_path, tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 with every warning on, and a C program
+    that includes it links against the shared library and runs its host-only entry points."""
+    src = tmp_path / "abi_check.c"
+    src.write_text(C_PROGRAM)
+    exe = tmp_path / "abi_check"
+    inc = os.path.join(ROOT, "include")
+    libdir = os.path.dirname(lib_path)
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", inc, str(src),
+                           "-L", libdir, "-l:libmonotable.so", "-Wl,-rpath," + libdir, "-Wl,--allow-shlib-undefined",
+                           "-o", str(exe)])
+    out = subprocess.run([str(exe)], stdout=subprocess.PIPE, check=True).stdout.decode().split()
+    assert int(out[0]) > (1 << 16) * 16 * 4 and out[1] == "0" and out[2] == "invalid"
