@@ -33,6 +33,11 @@
 
 namespace mono {
 
+// Counts are kept unsaturated in the low half of a counter word and read as min(count, 255).  Where
+// counters age, the first touch of a batch cuts the count back to 255; where they do not, a reader
+// does so once the count has passed kCountGuard (a batch adds less than 2^28).
+constexpr uint32_t kCountGuard = 1u << 30;
+
 // one counter word: `times` occurrences at `step`
 __device__ inline void touch_word(const TableView& t, unsigned long long* w, uint32_t step, uint32_t times) {
   if (t.expire_steps == 0) {
@@ -51,6 +56,7 @@ __device__ inline void touch_word(const TableView& t, unsigned long long* w, uin
     }
     // first toucher of the batch: ages the word, stamps the step and adds its occurrences in one exchange
     uint32_t last = (uint32_t)(cur >> 32), cnt = (uint32_t)cur;
+    if (cnt > 255u) cnt = 255u;  // the unsaturated count is cut back once per batch: it can never wrap
     if (step - last >= t.expire_steps) cnt = 0;
     const unsigned long long want = ((unsigned long long)step << 32) | (unsigned long long)(cnt + times);
     const unsigned long long old = atomicCAS(w, cur, want);
@@ -138,9 +144,11 @@ __global__ __launch_bounds__(kProbeBlock) void probe_count_kernel(TableView t, c
   // err on the side of probing.
   bool maybe = live;
   if (t.expire_steps == 0 && live && !restore) {
-    uint32_t cnt = reinterpret_cast<const uint32_t*>(&t.filter[filter_index(t, k)])[0];
-    for (uint32_t j = 1; j < t.filter_hashes; ++j) {  // the key's count is the smallest of its counters
-      const uint32_t c = reinterpret_cast<const uint32_t*>(&t.filter[filter_index(t, k, j)])[0];
+    uint32_t cnt = 0xFFFFFFFFu;
+    for (uint32_t j = 0; j < t.filter_hashes; ++j) {  // the key's count is the smallest of its counters
+      uint32_t* w = reinterpret_cast<uint32_t*>(&t.filter[filter_index(t, k, j)]);
+      const uint32_t c = *w;
+      if (c > kCountGuard) atomicMin(w, 255u);  // an unsaturated count (read as min(count, 255)) must never wrap
       cnt = c < cnt ? c : cnt;
     }
     maybe = cnt >= (t.freq_threshold > 1u ? t.freq_threshold : 1u);
@@ -226,17 +234,13 @@ __global__ __launch_bounds__(256) void admit_elect_kernel(TableView t, const int
   bool winner = false;
   uint64_t pos = 0;
   if (leader) {
-    uint32_t cnt = 255u;  // a snapshot record is admitted whatever its counter says
-    if (!restore) {
+    // A snapshot record is admitted whatever its counter says, and with a threshold of 0 or 1 every
+    // missing key is admissible (its count is at least 1 by now): no counter is read for either.
+    uint32_t cnt = 255u;
+    if (!restore && t.freq_threshold > 1u) {
       for (uint32_t j = 0; j < t.filter_hashes; ++j) {  // smallest of the key's counters
-        unsigned long long* w = &t.filter[filter_index(t, k, j)];
-        const unsigned long long word = *w;
-        uint32_t c = (uint32_t)word;
-        if (c > 255u) {  // keep the unsaturated count from ever wrapping
-          atomicMin(w, (word & 0xFFFFFFFF00000000ull) | 255ull);
-          c = 255u;
-        }
-        cnt = c < cnt ? c : cnt;
+        const uint32_t c = reinterpret_cast<const uint32_t*>(&t.filter[filter_index(t, k, j)])[0];
+        cnt = c < cnt ? c : cnt;  // (counts are kept unsaturated and read as min(count, 255))
       }
     }
     int32_t found = kRowAbsent;

@@ -67,3 +67,31 @@ def test_growing_a_table_with_a_multi_hash_filter(dev):
         compare_step(big, orc, b, dev, 1e-5, exact_rows=False, train=True, sweep_at=b["step"])
         assert (big.mono_filter_export() == orc.filter_words()).all()
     big.close()
+
+
+@pytest.mark.parametrize("expire_steps", [0, 3])
+@pytest.mark.parametrize("thr,hashes", [(255, 1), (200, 2), (1, 1)])
+def test_counters_saturate_at_255_on_shared_words(dev, expire_steps, thr, hashes):
+    """Sixteen counters for forty keys, hundreds of occurrences per key and batch: every word runs far
+    past 255 (the device keeps counts unsaturated and reads them as min(count, 255)), keys below the
+    threshold keep missing on saturated words, later batches touch them again, and with expiry the
+    words age in between.  Words, presence and the expired sets must equal the oracle's every step."""
+    from paper_2209_07663_amd.binding import Table
+    seed, cap, dim = 131, 1 << 10, 4
+    tab = Table(cap, dim, seed, freq_threshold=thr, expire_steps=expire_steps, max_ids=1 << 15, max_bags=1 << 15,
+                device=dev, filter_hashes=hashes, filter_log2=4)
+    orc = Oracle(cap, dim, seed, thr, expire_steps, False, kind="cuckoo", n_filter=16, filter_hashes=hashes)
+    rng = np.random.default_rng(7)
+    universe = (np.arange(40, dtype=np.int64) + 11) * 104729
+    for step in (0, 1, 2, 3, 7, 8, 20):                          # gaps let words and keys age
+        reps = rng.integers(1, 400, size=universe.shape[0])      # some keys below any threshold, some far above
+        reps[rng.integers(0, 40, size=10)] = 0
+        keys_h = np.repeat(universe, reps)
+        keys_h = keys_h[rng.permutation(keys_h.shape[0])]
+        offs_h = np.arange(keys_h.shape[0] + 1, dtype=np.int64)
+        compare_step(tab, orc, {"keys": keys_h, "offsets": offs_h, "step": step}, dev, 1e-5, exact_rows=True,
+                     train=False, sweep_at=step if expire_steps else None)
+        words = tab.mono_filter_export()
+        assert (words == orc.filter_words()).all(), "counter words differ at step %d" % step
+    assert ((words & 255) == 255).any()
+    tab.close()
