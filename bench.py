@@ -4,7 +4,10 @@
 A step = one pass of the whole path over one fresh synthetic batch:
 lookup_or_insert -> gather_pool -> apply_grad_adagrad -> expire_sweep.
 Default workload: configs[1] of the benchmark spec (capacity 2^24, dim 32 fp32, 65536 samples x 26 slots,
-Poisson(3)+1 IDs per bag, Zipf(1.05) over 2^32, threshold 3).  Prints ONE JSON line.
+Poisson(3)+1 IDs per bag, Zipf(1.05) over 2^32, threshold 3) on a table that already holds the
+workload's hottest IDs up to load 0.5, so that a step admits few new keys (the state after a long run).
+Prints ONE JSON line; its `roofline` object is the WHOLE STEP against the HBM peak (compulsory bytes of
+the step over the median step time), with the kernel that takes most time as `dominant_kernel`.
 
     python bench.py --gpus 1 --steps 10 --warmup 3
 """
@@ -22,15 +25,22 @@ sys.path.insert(0, ROOT)
 
 from paper_2209_07663_amd import synth  # noqa: E402
 
+DEFAULT_FILL = {"cfg2": 0.5, "cfg4": 0.9}   # load factor the table is brought to before the untimed steps
+
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 SECTOR = 32             # bytes: smallest HBM access counted for a random 4/8-byte word
+KEY_LINE = 64           # bytes of the eight keys of a bucket (what a probe must read of it)
+BUCKET_LINE = 128       # bytes of a bucket as this library stores it (keys + row index / last-seen words)
 
-# HBM bytes per launch (read + written) from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this command
-# on the default workload, scaled by the factors a plain 1 GiB copy gives (2.0 and 1.0); the runs and
-# the table are in profiles/bench_cfg2_full_step.md.  Workloads that were not profiled report null.
-MEASURED_TRAFFIC = {
-    "cfg2": {"probe_count": 882.9e6, "seg_reduce": 985.7e6, "gather_pool": 503.1e6, "admit_elect": 361.5e6,
-             "sort_scatter": 121.3e6, "sort_hist": 58.2e6, "insert": 103.8e6},
+# HBM bytes (read + written) that rocprofv3's FETCH_SIZE / WRITE_SIZE counters gave for ONE run of this
+# script, scaled by the factors a plain 1 GiB copy gives; they are NOT measured by the run that prints
+# them.  The figure is attached to a bench line only when workload and fill load are those of the
+# profiled command, together with the name of the summary it comes from; otherwise `traffic` is null.
+TRAFFIC_FROM_PROFILE = {
+    "cfg2": {"profile": "profiles/bench_cfg2_full_step.md", "fill_load": 0.0,
+             "step": 3.47e9,
+             "kernels": {"probe_count": 882.9e6, "seg_reduce": 985.7e6, "gather_pool": 503.1e6,
+                         "admit_elect": 361.5e6, "sort_scatter": 121.3e6, "sort_hist": 58.2e6, "insert": 103.8e6}},
 }
 
 
@@ -51,30 +61,46 @@ def generate_batches(wl_name, seed, steps, workers):
         return pool.map(_gen, [(wl_name, seed, s) for s in steps], chunksize=1)
 
 
-def cpu_baseline(wl, seed, batches, budget_s):
-    """The oracle as it stands (single thread), full step on the first batches from an empty table."""
+def cpu_baseline(wl, seed, fill_chunks, untimed, timed, budget_s):
+    """The oracle as it stands (single thread) on the SAME batches the device is timed on: the fill and
+    the untimed batches are replayed first (not timed), then full steps are timed until the budget is used."""
     from oracle import Oracle
     o = Oracle(wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, kind="cuckoo")
-    ids, t0, used = 0, time.perf_counter(), 0
-    for b in batches:
+    t_replay = time.perf_counter()
+    for chunk in fill_chunks:
+        for _ in range(max(wl.freq_threshold, 1)):
+            o.lookup_or_insert(chunk, 0)
+
+    def full_step(b):
         o.lookup_or_insert(b["keys"], b["step"])
         o.pool(b["keys"], b["offsets"])
         o.apply_grad_adagrad(b["keys"], b["offsets"], b["grad"], wl.lr, wl.eps)
         o.expire_sweep(b["step"])
+
+    for b in untimed:
+        full_step(b)
+    t_replay = time.perf_counter() - t_replay
+    ids, t0, used = 0, time.perf_counter(), 0
+    for b in timed:
+        full_step(b)
         ids += b["keys"].shape[0]
         used += 1
         if time.perf_counter() - t0 > budget_s:
             break
     dt = time.perf_counter() - t0
     return {"value": ids / dt, "unit": "IDs/s", "cores": 1, "kind": "oracle",
-            "sample": "full step (lookup_or_insert+pool+adagrad+sweep) on the first %d batches of the same workload, "
-                      "from an empty table, %.1f s" % (used, dt),
+            "sample": "full step (lookup_or_insert+pool+adagrad+sweep) on the first %d of the %d timed batches, after "
+                      "the same fill and the same %d untimed batches as the device (replayed untimed in %.0f s); %.1f s"
+                      % (used, len(timed), len(untimed), t_replay, dt),
             "host_cpus_present": os.cpu_count()}
 
 
 def algorithmic_bytes(kernel, s, wl):
     """Compulsory bytes of ONE launch of `kernel` for a batch with statistics `s`: what the kernel must move
-    if duplicates of a key were served on chip (n occurrences, u_* distinct keys, S = 32-byte sector)."""
+    if duplicates of a key were served on chip (n occurrences, u_* distinct keys, S = 32-byte sector).  Sort
+    scratch and row-index arrays that only exist because of how the work is split into kernels are not counted:
+    seg_reduce is charged the backward's compulsory bytes (pooled gradients once, every distinct row and its
+    state read and written), not the sorted pairs it reads."""
     e = 2 if wl.bf16 else 4
     row = wl.dim * e
     n, nb = s["n"], s["n_bags"]
@@ -83,38 +109,37 @@ def algorithmic_bytes(kernel, s, wl):
         # sector of a distinct missing key read and written; where counters age a miss must also read both
         # of its bucket lines (with expire_steps == 0 a counter below the threshold proves absence)
         if wl.expire_steps == 0:
-            return 12 * n + (128 + 4) * s["u_hit"] + 2 * SECTOR * s["u_miss"]
-        return 12 * n + (128 + 4) * s["u_hit"] + (256 + 2 * SECTOR) * s["u_miss"]
+            return 12 * n + (BUCKET_LINE + 4) * s["u_hit"] + 2 * SECTOR * s["u_miss"]
+        return 12 * n + (BUCKET_LINE + 4) * s["u_hit"] + (2 * BUCKET_LINE + 2 * SECTOR) * s["u_miss"]
     if kernel == "admit_elect":
         return 4 * n + 8 * s["n_miss"] + SECTOR * s["u_miss"] + 16 * s["u_new"]
     if kernel == "insert":
-        return s["u_new"] * (row + 128 + 4 + 8 + 8 + 4)
+        return s["u_new"] * (row + BUCKET_LINE + 4 + 8 + 8 + 4)
     if kernel == "resolve":
         return 4 * n
     if kernel == "gather_pool":
         return 4 * n + 8 * (nb + 1) + row * s["u_present"] + 4 * wl.dim * nb
-    if kernel == "expand_bags":
-        return 8 * (nb + 1) + 4 * n
-    if kernel == "sort_hist":
-        return 4 * n
-    if kernel == "sort_scatter":
-        return 16 * n
     if kernel == "seg_reduce":
-        return 8 * n + 4 * wl.dim * nb + 2 * row * s["u_present"] + 8 * s["u_present"]
+        return 4 * wl.dim * nb + 2 * row * s["u_present"] + 8 * s["u_present"]
     if kernel == "sweep_find":
-        return 8 * wl.capacity
-    return 0
+        return 4 * wl.capacity
+    return 0   # expand_bags and the sort kernels move scratch only: no compulsory bytes
 
 
-def step_bytes(s, wl, sweep_every):
-    """Compulsory bytes of a whole step (forward + backward; the sweep's share when the table expires keys)."""
+def step_bytes(s, wl, sweep_every, bucket_bytes=KEY_LINE):
+    """Compulsory bytes of a whole step with perfect on-chip reuse of duplicates: keys, offsets, one bucket
+    line per distinct stored key and two per distinct missing key (a miss must look at both buckets), the
+    counter sector of a distinct missing key read and written, the stamp, every distinct row read once (and
+    written once if new), the pooled output; backward: the pooled gradients, every distinct row read and
+    written, its accumulator read and written; sweep: the last-seen word of every slot and the removed keys.
+    bucket_bytes = 64: the eight keys of a bucket; 128: the bucket line as this library stores it."""
     e = 2 if wl.bf16 else 4
     row = wl.dim * e
     n, nb = s["n"], s["n_bags"]
-    fwd = (8 * n + 8 * (nb + 1) + 128 * (s["u_hit"] + s["u_miss"]) + 2 * SECTOR * s["u_miss"] + 4 * s["u_present"]
-           + row * s["u_present"] + row * s["u_new"] + 4 * wl.dim * nb)
+    fwd = (8 * n + 8 * (nb + 1) + bucket_bytes * (s["u_hit"] + 2 * s["u_miss"]) + 2 * SECTOR * s["u_miss"]
+           + 4 * s["u_present"] + row * s["u_present"] + row * s["u_new"] + 4 * wl.dim * nb)
     bwd = 4 * wl.dim * nb + 2 * row * s["u_present"] + 8 * s["u_present"]
-    sweep = 8 * wl.capacity / sweep_every if wl.expire_steps else 0
+    sweep = (4 * wl.capacity / sweep_every + 8 * s.get("n_expired", 0)) if wl.expire_steps else 0
     return fwd + bwd + sweep
 
 
@@ -184,13 +209,14 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg2", choices=sorted(synth.CONFIGS))
-    ap.add_argument("--prefill", type=int, default=8, help="untimed steps that bring the table to a steady state")
+    ap.add_argument("--prefill", type=int, default=2, help="untimed steps before the warm-up steps")
     ap.add_argument("--profile-steps", type=int, default=4, help="extra steps run with per-kernel HIP events")
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--cpu-budget", type=float, default=12.0, help="seconds of oracle time; 0 = skip")
     ap.add_argument("--workers", type=int, default=min(16, os.cpu_count() or 8))
-    ap.add_argument("--fill-load", type=float, default=0.0,
-                    help="before anything else, admit the hottest IDs until this load factor (configs[3] asks for 0.9)")
+    ap.add_argument("--fill-load", type=float, default=-1.0,
+                    help="before anything else, admit the workload's hottest IDs until this load factor; default: "
+                         "0.5 for cfg2, 0.9 for cfg4 (what configs[3] asks for), 0 (empty table) for the others")
     ap.add_argument("--no-maintenance", action="store_true",
                     help="skip the timing of delta export, snapshot, restore and rehash after the timed steps")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -211,21 +237,31 @@ def main():
         sys.exit(2)
 
     wl = synth.CONFIGS[args.workload]
-    n_steps = args.prefill + args.warmup + args.steps + args.profile_steps
+    # Default state of the table: the workload's hottest IDs are admitted first (untimed) up to a load at
+    # which a step admits few new keys, as after a long run; --fill-load 0 starts from the empty table.
+    fill_load = args.fill_load if args.fill_load >= 0 else DEFAULT_FILL.get(wl.name, 0.0)
+    n_untimed = args.prefill + args.warmup
+    n_steps = n_untimed + args.steps + args.profile_steps
     t_gen = time.perf_counter()
     batches = generate_batches(args.workload, args.seed, list(range(n_steps)), args.workers)
     t_gen = time.perf_counter() - t_gen
     print("[bench] generated %d batches of %s in %.1f s" % (n_steps, wl.name, t_gen), file=sys.stderr, flush=True)
+    max_ids = max(b["keys"].shape[0] for b in batches)
+    fill_chunks = []
+    if fill_load > 0:
+        drift = synth.DriftMap(wl, args.seed) if wl.drift_frac > 0 else None
+        hot = synth.hottest_ids(wl, int(fill_load * wl.capacity), drift)
+        fill_chunks = [hot[lo:lo + max_ids] for lo in range(0, hot.shape[0], max_ids)]
 
     cpu = None
     if args.cpu_budget > 0:
-        cpu = cpu_baseline(wl, args.seed, batches, args.cpu_budget)
+        cpu = cpu_baseline(wl, args.seed, fill_chunks, batches[:n_untimed], batches[n_untimed:n_untimed + args.steps],
+                           args.cpu_budget)
         print("[bench] oracle: %.3g IDs/s" % cpu["value"], file=sys.stderr, flush=True)
 
     import torch
     from paper_2209_07663_amd.binding import Table
     dev = torch.device("cuda:0")
-    max_ids = max(b["keys"].shape[0] for b in batches)
     tab = Table(wl.capacity, wl.dim, args.seed, wl.freq_threshold, wl.expire_steps, wl.bf16, max_ids=max_ids,
                 max_bags=wl.n_bags, device=dev)
     dbatches = []
@@ -248,20 +284,19 @@ def main():
         if b["step"] % sweep_every == sweep_every - 1:
             tab.mono_expire_sweep(b["step"], n_exp, None)
 
-    if args.fill_load > 0:  # untimed: every hot ID is looked up often enough to pass the occurrence filter
-        drift = synth.DriftMap(wl, args.seed) if wl.drift_frac > 0 else None
-        hot = synth.hottest_ids(wl, int(args.fill_load * wl.capacity), drift)
-        for lo in range(0, hot.shape[0], max_ids):
-            chunk = torch.from_numpy(hot[lo:lo + max_ids]).to(dev)
-            for _ in range(max(wl.freq_threshold, 1)):
-                tab.mono_lookup_or_insert(chunk, 0, rows[: chunk.shape[0]])
+    for chunk_h in fill_chunks:  # untimed: every hot ID is looked up often enough to pass the occurrence filter
+        chunk = torch.from_numpy(chunk_h).to(dev)
+        for _ in range(max(wl.freq_threshold, 1)):
+            tab.mono_lookup_or_insert(chunk, 0, rows[: chunk.shape[0]])
+    if fill_chunks:
         torch.cuda.synchronize()
         print("[bench] filled to load %.3f" % (tab.mono_table_stats()["size"] / wl.capacity), file=sys.stderr, flush=True)
     it = iter(dbatches)
-    for _ in range(args.prefill + args.warmup):
+    for _ in range(n_untimed):
         run_step(next(it))
     torch.cuda.synchronize()
-    load_before = tab.mono_table_stats()["size"] / wl.capacity
+    st0 = tab.mono_table_stats()
+    load_before = st0["size"] / wl.capacity
 
     timed = [next(it) for _ in range(args.steps)]
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in timed]
@@ -276,7 +311,7 @@ def main():
     ids = sum(b["n"] for b in timed)
     step_ms = [e0.elapsed_time(e1) for e0, e1 in ev]
     st = tab.mono_table_stats()
-    assert st["n_insert_failed"] == 0 and st["n_lost"] == 0 and st["n_full"] == 0, st
+    admitted_per_step = (st["n_admitted"] - st0["n_admitted"]) / max(args.steps, 1)
 
     # per-kernel pass (HIP events inside the library, on the stream the kernels run on) + batch statistics
     stats, prof = [], {}
@@ -293,39 +328,50 @@ def main():
         u_new = tab.mono_table_stats()["n_admitted"] - adm0
         # miss occurrences = occurrences of keys absent before the call: absent now, or admitted in this call
         u_hit = u_present - u_new
-        stats.append({"n": b["n"], "n_bags": wl.n_bags, "u": u_all, "u_present": u_present, "u_new": u_new,
-                      "u_hit": u_hit, "u_miss": u_all - u_hit, "n_miss": int((~present).sum().item())})
+        one = {"n": b["n"], "n_bags": wl.n_bags, "u": u_all, "u_present": u_present, "u_new": u_new,
+               "u_hit": u_hit, "u_miss": u_all - u_hit, "n_miss": int((~present).sum().item()), "n_expired": 0}
         tab.mono_gather_pool(r, b["offsets"], pooled)
         tab.mono_apply_grad_adagrad(r, b["offsets"], b["grad"], wl.lr, wl.eps)
         if b["step"] % sweep_every == sweep_every - 1:
             tab.mono_expire_sweep(b["step"], n_exp, None)
+            one["n_expired"] = int(n_exp.item()) / sweep_every
+        stats.append(one)
     prof = tab.mono_profile_read()
     tab.mono_profile_enable(False)
+    end = tab.mono_table_stats()
 
-    roofline, kernels = None, {}
-    if prof and stats:
-        mean = {k: float(np.mean([s[k] for s in stats])) for k in stats[0]}
+    roofline, kernels, mean = None, {}, None
+    med_ms = float(np.median(step_ms))
+    if stats:
+        mean = {k: float(np.mean([x[k] for x in stats])) for k in stats[0]}
+        tp = TRAFFIC_FROM_PROFILE.get(wl.name)
+        tp = tp if tp and abs(tp["fill_load"] - fill_load) < 1e-9 else None
+        sb, sb_line = step_bytes(mean, wl, sweep_every, KEY_LINE), step_bytes(mean, wl, sweep_every, BUCKET_LINE)
+        roofline = {"bound": "hbm", "scope": "whole step: every kernel of lookup_or_insert + gather_pool + "
+                                             "apply_grad_adagrad + expire_sweep, compulsory bytes of the step "
+                                             "over the median step time (HIP events around each timed step)",
+                    "achieved": round(sb / (med_ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(sb / (med_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                    "traffic": tp["step"] if tp else None, "traffic_source": tp["profile"] if tp else None,
+                    "algorithmic_bytes_per_step": int(sb),
+                    "frac_with_128_byte_bucket_lines": round(sb_line / (med_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                    "batch_stats": {k: int(v) for k, v in mean.items()}}
         for name, (ms, launches) in prof.items():
             avg_ms = ms / launches
             ab = algorithmic_bytes(name, mean, wl)
             kernels[name] = {"avg_ms": round(avg_ms, 4), "launches_per_step": launches / len(stats),
                              "ms_per_step": round(ms / len(stats), 4),
                              "algo_GBps": round(ab / avg_ms / 1e6, 1) if ab else None}
-        dom = max(prof, key=lambda k: prof[k][0])
-        achieved = algorithmic_bytes(dom, mean, wl) / (prof[dom][0] / prof[dom][1]) / 1e6
-        roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                    "traffic": MEASURED_TRAFFIC.get(wl.name, {}).get(dom),
-                    "timing": "HIP events around every launch on the library's stream, over the %d steps that "
-                              "follow the timed ones on the same stream of batches (with events in the timed steps "
-                              "the step takes 15 %% longer, so those run without)" % len(stats)}
-        sb = step_bytes(mean, wl, sweep_every)
-        step_roof = {"algorithmic_bytes_per_step": int(sb),
-                     "achieved_GBps": round(sb / (np.median(step_ms) * 1e-3) / 1e9, 1),
-                     "frac_of_hbm_peak": round(sb / (np.median(step_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                     "batch_stats": {k: int(v) for k, v in mean.items()}}
-    else:
-        step_roof = None
+        if prof:
+            dom = max(prof, key=lambda k: prof[k][0])
+            achieved = algorithmic_bytes(dom, mean, wl) / (prof[dom][0] / prof[dom][1]) / 1e6
+            roofline["dominant_kernel"] = {
+                "kernel": dom, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "avg_launch_ms": round(prof[dom][0] / prof[dom][1], 4),
+                "traffic": tp["kernels"].get(dom) if tp else None, "traffic_source": tp["profile"] if tp else None,
+                "timing": "HIP events around every launch on the library's stream, over the %d steps that follow "
+                          "the timed ones on the same stream of batches (with events in the timed steps the step "
+                          "takes longer, so those run without)" % len(stats)}
 
     maintenance = None if args.no_maintenance else time_maintenance(tab, wl, args.seed, max_ids, dev)
 
@@ -338,13 +384,18 @@ def main():
                                % (wl.name, wl.capacity.bit_length() - 1, wl.dim, wl.samples, wl.slots,
                                   "Zipf(%.2f)" % wl.alpha if wl.dist == "zipf" else "uniform", wl.freq_threshold,
                                   wl.expire_steps),
-                   "ids_per_step": ids // args.steps, "prefill_steps": args.prefill,
-                   "load_factor": round(load_before, 4), "sweep_every_steps": sweep_every,
+                   "ids_per_step": ids // args.steps, "fill_load": fill_load, "prefill_steps": args.prefill,
+                   "load_factor": round(load_before, 4), "keys_admitted_per_step": round(admitted_per_step),
+                   "sweep_every_steps": sweep_every,
                    "step": "lookup_or_insert+gather_pool+apply_grad_adagrad+expire_sweep"},
-        "median_step_ms_events": float(np.median(step_ms)), "min_step_ms_events": float(np.min(step_ms)),
-        "roofline": roofline, "step_roofline": step_roof, "kernels": kernels, "maintenance": maintenance, "cpu_baseline": cpu,
+        "median_step_ms_events": med_ms, "min_step_ms_events": float(np.min(step_ms)),
+        "table_events": {k: end[k] for k in ("n_insert_failed", "n_lost", "n_full", "stash_size", "max_chain")},
+        "roofline": roofline, "kernels": kernels, "maintenance": maintenance, "cpu_baseline": cpu,
     }
     print(json.dumps(out))
+    if end["n_lost"]:
+        print("bench.py: %d stored elements were lost (stash overflow)" % end["n_lost"], file=sys.stderr)
+        sys.exit(1)
 
 
 if __name__ == "__main__":

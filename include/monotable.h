@@ -6,7 +6,7 @@
  * finds its cell occupied evicts the occupant, which is re-inserted in the other sub-table), with
  * the two memory-saving heuristics of the same section: IDs are filtered by their number of
  * occurrences before they are admitted, and IDs that stay inactive for a configured time expire.
- * "Look-ups and updates" are separate operations (end of section 2.1).  Pooling, duplicate-ID
+ * Lookups and updates are separate operations (end of section 2.1).  Pooling, duplicate-ID
  * gradient reduction and row-wise Adagrad are the build's own problem statement around that table.
  *
  * Conventions
@@ -66,7 +66,8 @@ size_t mono_table_bytes(uint64_t capacity, uint32_t dim, uint32_t flags, uint64_
  *                   At most capacity - capacity/32 keys are stored at a time: beyond that load the
  *                   eviction chains of section 2.1 become long enough to fail, so further admissible
  *                   keys are refused (row -1, counted in n_full) until keys expire or the table grows
- *   dim             embedding dimension; multiple of 4 in [4, 256]
+ *   dim             embedding dimension; a multiple of 4 up to 256, or 512, 768 or 1024 (section 3.2.2
+ *                   sizes its synchronisation example with 1024 fp32 elements = 4 KB per row)
  *   seed            fixes h0, h1, the counter hash and the initial value of every row
  *   freq_threshold  a key is admitted once its occurrence counter reaches it; 0 and 1 admit on
  *                   first sight; at most 255
@@ -83,7 +84,7 @@ int mono_table_create(mono_table** out, uint64_t capacity, uint32_t dim, uint64_
                       size_t arena_bytes, void* stream);
 
 /* The same with the occurrence filter spelled out (section 2.1 names two filters: a threshold on
- * occurrences and "a probabilistic filter" that saves memory; here both are one array of counters):
+ * occurrences and a probabilistic one that saves memory; here both are one array of counters):
  *   filter_hashes  counters per key, 1..4.  Every missed occurrence of a key bumps all of them and the
  *                  key's count is their minimum (a counting filter with several hashes: it can
  *                  over-count when keys share counters, never under-count).  1 = mono_table_create.
@@ -118,7 +119,21 @@ int mono_lookup_or_insert(mono_table* t, const int64_t* d_keys, uint64_t n, uint
 int mono_gather_pool(mono_table* t, const int32_t* d_rows, uint64_t n, const int64_t* d_offsets, uint64_t n_bags,
                      float* d_out, void* stream);
 
-/* Sparse update ("PS ... updates them according to gradients computed by Workers", section 2):
+/* The embedding of the quotient-remainder decomposition (section 3.1: the hashing baseline the paper
+ * compares the collisionless table with; an ID of a space of 2^(2m) values is split into ID_r = ID mod 2^m
+ * and ID_q = ID div 2^m, and its embedding is E_r[ID_r] + E_q[ID_q] from two dense tables of 2^m rows each,
+ * 2^(m+1) rows instead of 2^(2m); the paper uses m = 24), gathered and sum-pooled per bag exactly like
+ * mono_gather_pool: d_out[b, :] = sum over i in [d_offsets[b], d_offsets[b+1]) of E_r[..] + E_q[..].
+ * No table object, no hashing, no lookup: the no-hash yardstick of the pooling kernel.
+ *   d_table_r, d_table_q  [2^log2_rows * dim] each, fp32 or bf16 (flags), row-major, device, caller-owned
+ *   log2_rows             m, 1..30;  dim as in mono_table_create
+ *   d_ids[n]              int64; an ID outside [0, 2^(2m)) (e.g. the padding key -1) contributes zero
+ * d_out[n_bags * dim] is fp32.  Errors: MONO_EINVAL on a bad argument. */
+int mono_qr_gather_pool(const void* d_table_r, const void* d_table_q, uint32_t log2_rows, uint32_t dim, uint32_t flags,
+                        const int64_t* d_ids, uint64_t n, const int64_t* d_offsets, uint64_t n_bags, float* d_out,
+                        void* stream);
+
+/* Sparse update (section 2: the parameter side applies the gradients the workers computed):
  * the pooled gradient d_grad[n_bags * dim] (fp32) of bag b is the gradient of each of its
  * occurrences; gradients of occurrences of the same row are summed, then row-wise Adagrad is
  * applied once per distinct row: acc += mean_j g_j^2; w_j -= lr * g_j / (sqrt(acc) + eps).

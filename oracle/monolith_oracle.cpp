@@ -12,7 +12,7 @@
 //   kind 1  "R1"  the oracle proper: the cuckoo hashmap of the paper's section 2.1 (two
 //                 sub-tables T0/T1 with hash functions h0/h1, insertion by eviction chain),
 //                 taken in the paper's order: try T0[h0(A)], if occupied evict the occupant B,
-//                 put A there, and insert B into the other sub-table "with the same logic".
+//                 put A there, and insert B into the other sub-table by the same procedure.
 //
 // Both implement the same batch semantics (section 2.1's admission filter and expiry, plus the
 // pooling / gradient reduction / Adagrad steps that the build's problem statement adds):
@@ -41,6 +41,11 @@
 //      larger power-of-two capacity; when the number of counters grows by 2^k, a counter's value
 //      goes to all 2^k counters that its keys can now map to (never an under-count).
 //
+// Beside the table: the paper's hashing baseline (section 3.1, the production model's tables), the
+// quotient-remainder decomposition, as a pooling routine over two dense tables:
+//  13. ID_r = ID mod 2^m, ID_q = ID div 2^m, E = E_r[ID_r] + E_q[ID_q]; a bag's output is the fp64
+//      sum of E over its IDs, rounded once; an ID outside [0, 2^(2m)) contributes nothing.
+//
 // Parity unpinned: what happens when an eviction chain exceeds its bound (which key ends up in
 // the overflow stash depends on insertion order); graded runs must have zero such failures.
 //
@@ -60,7 +65,7 @@ namespace {
 constexpr uint64_t kEmptyKey = ~0ull;  // reserved key: padding, never stored
 
 // ---------------------------------------------------------------------------------------------
-// Hashing.  The paper only says "different hash functions h0, h1" (section 2.1); this build
+// Hashing.  The paper only asks for two different hash functions h0, h1 (section 2.1); this build
 // fixes one public 64-bit mixer (the SplitMix64 output function) and derives every hash from it.
 // ---------------------------------------------------------------------------------------------
 uint64_t mix64(uint64_t z) {
@@ -742,6 +747,26 @@ uint64_t orc_capacity(void* hv) { return ((Handle*)hv)->m->params().capacity; }
 uint64_t orc_n_filter(void* hv) { return ((Handle*)hv)->m->params().n_filter; }
 uint64_t orc_placement_salt(uint64_t seed, uint32_t generation, int side) {
   return salt(placement_seed(seed, generation), side);
+}
+
+// Quotient-remainder embedding (section 3.1): two dense tables of 2^m rows, E = E_r[id mod 2^m] +
+// E_q[id div 2^m], summed per bag in fp64 and rounded once.  table_r / table_q: [2^m * dim] fp32
+// (values already rounded to the storage type by the caller).
+void orc_qr_pool(const float* table_r, const float* table_q, uint32_t m, uint32_t dim, const int64_t* ids,
+                 const int64_t* offsets, uint64_t n_bags, float* out) {
+  std::vector<double> s(dim);
+  const uint64_t rows = 1ull << m;
+  for (uint64_t b = 0; b < n_bags; ++b) {
+    std::fill(s.begin(), s.end(), 0.0);
+    for (int64_t i = offsets[b]; i < offsets[b + 1]; ++i) {
+      if (ids[i] < 0) continue;
+      uint64_t id = (uint64_t)ids[i];
+      uint64_t id_r = id % rows, id_q = id / rows;
+      if (id_q >= rows) continue;  // outside the decomposed ID space
+      for (uint32_t j = 0; j < dim; ++j) s[j] += (double)table_r[id_r * dim + j] + (double)table_q[id_q * dim + j];
+    }
+    for (uint32_t j = 0; j < dim; ++j) out[b * dim + j] = (float)s[j];
+  }
 }
 
 // building blocks exposed so that tests can pin them separately

@@ -72,6 +72,7 @@ def oracle_lib():
         lib.orc_n_filter.argtypes = [_vp]
         lib.orc_placement_salt.restype = _u64
         lib.orc_placement_salt.argtypes = [_u64, _u32, ctypes.c_int]
+        lib.orc_qr_pool.argtypes = [_vp, _vp, _u32, _u32, _vp, _vp, _u64, _vp]
         lib.orc_mix64.restype = _u64
         lib.orc_mix64.argtypes = [_u64]
         lib.orc_salt.restype = _u64
@@ -88,6 +89,20 @@ def oracle_lib():
 
 def _ptr(a):
     return a.ctypes.data_as(_vp)
+
+
+def qr_pool(table_r, table_q, ids, offsets):
+    """Quotient-remainder embedding of the paper's hashing baseline, sum-pooled per bag: tables [2^m, dim] fp32."""
+    table_r = np.ascontiguousarray(table_r, dtype=np.float32)
+    table_q = np.ascontiguousarray(table_q, dtype=np.float32)
+    ids = np.ascontiguousarray(ids, dtype=np.int64)
+    offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+    rows, dim = table_r.shape
+    assert table_q.shape == table_r.shape and rows & (rows - 1) == 0
+    out = np.empty((offsets.shape[0] - 1, dim), dtype=np.float32)
+    oracle_lib().orc_qr_pool(_ptr(table_r), _ptr(table_q), rows.bit_length() - 1, dim, _ptr(ids), _ptr(offsets),
+                             offsets.shape[0] - 1, _ptr(out))
+    return out
 
 
 class Oracle:

@@ -33,6 +33,7 @@ SYMBOLS = {
     "mono_table_destroy": (ctypes.c_int, [_vp]),
     "mono_lookup_or_insert": (ctypes.c_int, [_vp, _vp, _u64, _u32, _vp, _vp]),
     "mono_gather_pool": (ctypes.c_int, [_vp, _vp, _u64, _vp, _u64, _vp, _vp]),
+    "mono_qr_gather_pool": (ctypes.c_int, [_vp, _vp, _u32, _u32, _u32, _vp, _u64, _vp, _u64, _vp, _vp]),
     "mono_apply_grad_adagrad": (ctypes.c_int, [_vp, _vp, _u64, _vp, _u64, _vp, _f32, _f32, _vp]),
     "mono_expire_sweep": (ctypes.c_int, [_vp, _u32, _vp, _vp, _u64, _vp]),
     "mono_table_stats": (ctypes.c_int, [_vp, ctypes.POINTER(mono_stats), _vp]),
@@ -91,6 +92,27 @@ check, device_pointer, current_stream = _check, _p, _stream
 def _dev(t, dtype):
     if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
         raise TypeError("need a contiguous CUDA tensor of %s" % dtype)
+
+
+def mono_qr_gather_pool(table_r, table_q, ids, offsets, out=None):
+    """Pooled embeddings E_r[id mod 2^m] + E_q[id div 2^m] from two dense tables [2^m, dim] (fp32 or bf16)."""
+    if table_r.shape != table_q.shape or table_r.dtype != table_q.dtype or table_r.dim() != 2:
+        raise ValueError("the two tables must have the same shape [2^m, dim] and type")
+    if table_r.dtype not in (torch.float32, torch.bfloat16):
+        raise TypeError("tables must be float32 or bfloat16")
+    _dev(table_r, table_r.dtype), _dev(table_q, table_q.dtype), _dev(ids, torch.int64), _dev(offsets, torch.int64)
+    rows, dim = table_r.shape
+    if rows & (rows - 1):
+        raise ValueError("the tables must hold a power-of-two number of rows")
+    n_bags = offsets.shape[0] - 1
+    if out is None:
+        out = torch.empty((n_bags, dim), dtype=torch.float32, device=ids.device)
+    _dev(out, torch.float32)
+    flags = MONO_ROWS_BF16 if table_r.dtype == torch.bfloat16 else MONO_ROWS_FP32
+    _check(load_library().mono_qr_gather_pool(_p(table_r), _p(table_q), rows.bit_length() - 1, dim, flags, _p(ids),
+                                              ids.shape[0], _p(offsets), n_bags, _p(out), _stream(ids.device)),
+           "mono_qr_gather_pool")
+    return out
 
 
 class Table:

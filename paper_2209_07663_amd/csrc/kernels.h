@@ -19,7 +19,10 @@ struct UpdateWorkspace {
 constexpr uint32_t kSortMaxBits = 8;               // widest radix digit (measured: 9-bit passes save a pass above 16 M rows
                                                    // and still lose, their writes come out in pieces of half a line)
 constexpr uint32_t kSortMaxBins = 1u << kSortMaxBits;
-constexpr uint32_t kSortItemsPerBlock = 2048;      // consecutive elements owned by one block of the sort
+#ifndef MONO_SORT_ITEMS
+#define MONO_SORT_ITEMS 2048
+#endif
+constexpr uint32_t kSortItemsPerBlock = MONO_SORT_ITEMS;      // consecutive elements owned by one block of the sort
 constexpr int kPairsPerLane = 16;                  // sorted pairs per lane of a lane group in seg_reduce
 constexpr uint32_t kReduceTile = 256 * kPairsPerLane;  // sorted pairs reduced by one block
 
@@ -60,6 +63,11 @@ hipError_t launch_migrate(const TableView& dst, const TableView& src, int32_t sr
 
 hipError_t launch_gather_pool(const TableView& t, const int32_t* d_rows, uint64_t n, const int64_t* d_offsets,
                               uint64_t n_bags, float* d_out, hipStream_t stream, Profiler* prof);
+
+// Pooled embeddings of the quotient-remainder decomposition: two dense tables of 2^log2_rows rows each.
+hipError_t launch_qr_gather_pool(const void* d_rem, const void* d_quot, uint32_t log2_rows, uint32_t dim, bool bf16,
+                                 const int64_t* d_ids, uint64_t n, const int64_t* d_offsets, uint64_t n_bags,
+                                 float* d_out, hipStream_t stream);
 
 hipError_t launch_apply_grad_adagrad(const TableView& t, const UpdateWorkspace& ws, const int32_t* d_rows, uint64_t n,
                                      const int64_t* d_offsets, uint64_t n_bags, const float* d_grad, float lr, float eps,

@@ -451,10 +451,11 @@ __global__ __launch_bounds__(256) void insert_kernel(TableView t, uint32_t step,
         }
       }
     }
-    // the wave initialises its new rows together: a group of dim/4 lanes per row, four elements per
-    // lane, 64/group rows at a time, stored as whole 16-byte (fp32) or 8-byte (bf16) pieces
+    // the wave initialises its new rows together: a group of dim/4 lanes per row (at most the whole
+    // wave, which then walks the row in pieces of 256 elements), four elements per lane, 64/group rows
+    // at a time, stored as whole 16-byte (fp32) or 8-byte (bf16) pieces
     uint32_t glog = 0;
-    while ((4u << glog) < t.dim) ++glog;
+    while (glog < 6 && (4u << glog) < t.dim) ++glog;
     const uint32_t group = 1u << glog, per_round = 64u >> glog, l = lane & (group - 1u), gi = lane >> glog;
     const int ok = valid && row != kNoRow;
     if (__ballot(ok) == 0) continue;  // wave-uniform
@@ -463,18 +464,19 @@ __global__ __launch_bounds__(256) void insert_kernel(TableView t, uint32_t step,
       const uint64_t kk = __shfl(k, from);
       const uint32_t rr = __shfl(row, from);
       const uint32_t oo = __shfl(occ, from);
-      if (__shfl(ok, from) && l * 4 < t.dim) {
+      if (!__shfl(ok, from)) continue;
+      for (uint32_t col = l * 4; col < t.dim; col += 256) {
         float4 v;
         if (src.values) {
-          v = *reinterpret_cast<const float4*>(src.values + (uint64_t)oo * t.dim + l * 4);
+          v = *reinterpret_cast<const float4*>(src.values + (uint64_t)oo * t.dim + col);
         } else {
           const uint64_t base_h = mix64(kk ^ t.s_init);
-          v = make_float4(init_value(base_h, l * 4), init_value(base_h, l * 4 + 1), init_value(base_h, l * 4 + 2),
-                          init_value(base_h, l * 4 + 3));
+          v = make_float4(init_value(base_h, col), init_value(base_h, col + 1), init_value(base_h, col + 2),
+                          init_value(base_h, col + 3));
         }
-        store_init4<E>(rows, (uint64_t)rr * t.dim + l * 4, v);
-        if (l == 0) t.state[rr] = RowState{src.acc ? src.acc[oo] : 0.0f, 0u};
+        store_init4<E>(rows, (uint64_t)rr * t.dim + col, v);
       }
+      if (l == 0) t.state[rr] = RowState{src.acc ? src.acc[oo] : 0.0f, 0u};
     }
   }
 }

@@ -26,8 +26,13 @@
 
 namespace mono {
 
-constexpr int kSortBlock = 256;
+#ifndef MONO_SORT_BLOCK
+#define MONO_SORT_BLOCK 256
+#endif
+constexpr int kSortBlock = MONO_SORT_BLOCK;
 constexpr int kSortWaves = kSortBlock / 64;
+constexpr int kScanWaves = kSortMaxBins / 64;  // the first kSortMaxBins threads of a block own one bin each
+static_assert(kSortBlock >= (int)kSortMaxBins && kSortBlock % 64 == 0, "one thread per bin");
 constexpr uint32_t kSortPerWave = kSortItemsPerBlock / kSortWaves;
 constexpr uint32_t kSortRounds = kSortPerWave / 64;
 
@@ -133,11 +138,9 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
   __shared__ uint32_t lds[kSortWaves][kSortMaxBins];   // per-wave digit counts, then local start offsets
   __shared__ uint32_t local_start[kSortMaxBins];       // first position of a bin in `stage`
   __shared__ uint32_t global_start[kSortMaxBins];      // where this block's part of a bin goes in dst
-  __shared__ uint32_t wave_sum[kSortWaves];
   const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const uint64_t unit = blockIdx.x;
   const uint32_t shift = plan.shift(pass), bits = plan.width(pass), nbins = 1u << bits, mask = nbins - 1;
-  static_assert(kSortMaxBins % kSortBlock == 0, "whole bins per thread");
 
   // 1. this wave's elements -> registers (independent, coalesced loads)
   if (pass > 0) n = ctl->scratch[kValidPairs];
@@ -163,26 +166,19 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
     if (kv[r].x != 0xFFFFFFFFu) atomicAdd(&lds[wave][(kv[r].x >> shift) & mask], 1u);
   }
   __syncthreads();
-  // 3. a thread owns kBinsPerThread neighbouring bins: exclusive scans of the bin totals, once within
-  //    the block (positions in `stage`) and once over all bins of the pass (start of the bin in dst)
+  // 3. thread b < kSortMaxBins owns bin b: exclusive scans of the bin totals, once within the block
+  //    (positions in `stage`) and once over all bins of the pass (start of the bin in dst)
+  __shared__ uint32_t scan_sum[kScanWaves], scan_tot[kScanWaves];
   {
-    constexpr uint32_t kBinsPerThread = kSortMaxBins / kSortBlock;
-    const uint32_t b0 = threadIdx.x * kBinsPerThread;
-    uint32_t mine[kBinsPerThread], tot[kBinsPerThread];
-    uint32_t sum = 0, sum_tot = 0;
+    const bool bin_thread = threadIdx.x < kSortMaxBins;
+    const uint32_t bin = threadIdx.x;
+    uint32_t mine = 0, tot = 0;
+    if (bin_thread && bin < nbins) {
 #pragma unroll
-    for (uint32_t q = 0; q < kBinsPerThread; ++q) {
-      mine[q] = 0;
-      tot[q] = 0;
-      if (b0 + q < nbins) {
-#pragma unroll
-        for (int w = 0; w < kSortWaves; ++w) mine[q] += lds[w][b0 + q];
-        tot[q] = totals[b0 + q];
-      }
-      sum += mine[q];
-      sum_tot += tot[q];
+      for (int w = 0; w < kSortWaves; ++w) mine += lds[w][bin];
+      tot = totals[bin];
     }
-    uint32_t x = sum, y = sum_tot;  // inclusive wave scans
+    uint32_t x = mine, y = tot;  // inclusive wave scans
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
       const uint32_t xs = __shfl_up(x, d), ys = __shfl_up(y, d);
@@ -191,20 +187,17 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
         y += ys;
       }
     }
-    __shared__ uint32_t wave_tot[kSortWaves];
-    if (lane == 63) {
-      wave_sum[wave] = x;
-      wave_tot[wave] = y;
+    if (bin_thread && lane == 63) {
+      scan_sum[wave] = x;
+      scan_tot[wave] = y;
     }
     __syncthreads();
-    uint32_t run = x - sum, run_tot = y - sum_tot;  // first position of bin b0 in the block / in dst
-    for (uint32_t w = 0; w < wave; ++w) {
-      run += wave_sum[w];
-      run_tot += wave_tot[w];
-    }
-#pragma unroll
-    for (uint32_t q = 0; q < kBinsPerThread; ++q) {
-      const uint32_t bin = b0 + q;
+    if (bin_thread) {
+      uint32_t run = x - mine, run_tot = y - tot;  // first position of the bin in the block / in dst
+      for (uint32_t w = 0; w < wave; ++w) {
+        run += scan_sum[w];
+        run_tot += scan_tot[w];
+      }
       if (bin < nbins) {
         local_start[bin] = run;
         global_start[bin] = run_tot + hist[(uint64_t)bin * units + unit];
@@ -216,11 +209,9 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
           at += c;
         }
       }
-      run += mine[q];
-      run_tot += tot[q];
+      if (pass == 0 && blockIdx.x == 0 && threadIdx.x == kSortMaxBins - 1)
+        ctl->scratch[kValidPairs] = run_tot + tot;  // pairs that remain
     }
-    if (pass == 0 && blockIdx.x == 0 && threadIdx.x == kSortBlock - 1)
-      ctl->scratch[kValidPairs] = run_tot;  // pairs that remain
   }
   __syncthreads();
   // 4. rank (stable) into `stage`, 64 elements at a time
@@ -237,7 +228,9 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
   }
   __syncthreads();
   // 5. out: neighbouring threads write neighbouring elements of a bin
-  const uint32_t total = wave_sum[0] + wave_sum[1] + wave_sum[2] + wave_sum[3];
+  uint32_t total = 0;
+#pragma unroll
+  for (int w = 0; w < kScanWaves; ++w) total += scan_sum[w];
   for (uint32_t p = threadIdx.x; p < total; p += kSortBlock) {
     const uint2 e = stage[p];
     const uint32_t digit = (e.x >> shift) & mask;

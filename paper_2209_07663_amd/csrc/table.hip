@@ -38,8 +38,12 @@ uint64_t placement_seed(uint64_t seed, uint32_t generation) {
   return seed + (uint64_t)generation * 0xD1B54A32D192ED03ull;
 }
 
+// embedding dimension: a multiple of 4 up to 256 (one lane group per row), or a multiple of 256 up to 1024
+// (the whole wave walks the row in segments of 256 elements)
+bool valid_dim(uint32_t dim) { return dim >= 4 && dim % 4 == 0 && (dim <= 256 || (dim <= 1024 && dim % 256 == 0)); }
+
 bool valid_shape(uint64_t capacity, uint32_t dim, uint32_t flags, uint64_t max_ids, uint64_t max_bags) {
-  return is_pow2(capacity) && capacity >= 16 && capacity <= (1ull << 30) && dim >= 4 && dim <= 256 && dim % 4 == 0 &&
+  return is_pow2(capacity) && capacity >= 16 && capacity <= (1ull << 30) && valid_dim(dim) &&
          flags <= MONO_ROWS_BF16 && max_ids >= 1 && max_ids <= (1ull << 28) && max_bags >= 1 && max_bags <= max_ids + 1;
 }
 
@@ -249,6 +253,18 @@ int mono_gather_pool(mono_table* t, const int32_t* d_rows, uint64_t n, const int
   if (!d_offsets || !d_out || (n && !d_rows)) return MONO_EINVAL;
   return launch_gather_pool(t->view, d_rows, n, d_offsets, n_bags, d_out, (hipStream_t)stream, &t->prof) == hipSuccess ? MONO_OK
                                                                                                            : MONO_EHIP;
+}
+
+int mono_qr_gather_pool(const void* d_table_r, const void* d_table_q, uint32_t log2_rows, uint32_t dim, uint32_t flags,
+                        const int64_t* d_ids, uint64_t n, const int64_t* d_offsets, uint64_t n_bags, float* d_out,
+                        void* stream) {
+  if (log2_rows < 1 || log2_rows > 30 || !valid_dim(dim) || flags > MONO_ROWS_BF16 || n > (1ull << 40)) return MONO_EINVAL;
+  if (n_bags == 0) return MONO_OK;
+  if (!d_table_r || !d_table_q || !d_offsets || !d_out || (n && !d_ids)) return MONO_EINVAL;
+  return launch_qr_gather_pool(d_table_r, d_table_q, log2_rows, dim, flags == MONO_ROWS_BF16, d_ids, n, d_offsets, n_bags,
+                               d_out, (hipStream_t)stream) == hipSuccess
+             ? MONO_OK
+             : MONO_EHIP;
 }
 
 int mono_apply_grad_adagrad(mono_table* t, const int32_t* d_rows, uint64_t n, const int64_t* d_offsets,

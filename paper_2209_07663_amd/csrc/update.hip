@@ -70,47 +70,105 @@ __device__ inline float step_scale(float acc, float lr, float eps) {
   return lr * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(acc) + eps);
 }
 
-// Row-wise Adagrad on one row by one lane group; g = this lane's four gradient elements (zero in
+// A lane's share of a row: SEG pieces of four elements, piece q at elements (q * 64 + l) * 4.  Rows of
+// at most 256 elements have one piece per lane (SEG = 1, lane groups of up to 64 lanes); wider rows
+// (512, 768, 1024 elements) are held by the whole wave with SEG = 2, 3, 4.
+template <int SEG>
+struct RowVec {
+  float4 v[SEG];
+  __device__ inline void zero() {
+#pragma unroll
+    for (int q = 0; q < SEG; ++q) v[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  __device__ inline void add(const RowVec& o) {
+#pragma unroll
+    for (int q = 0; q < SEG; ++q) {
+      v[q].x += o.v[q].x;
+      v[q].y += o.v[q].y;
+      v[q].z += o.v[q].z;
+      v[q].w += o.v[q].w;
+    }
+  }
+  __device__ inline float sum_sq() const {
+    float ss = 0.f;
+#pragma unroll
+    for (int q = 0; q < SEG; ++q) ss += v[q].x * v[q].x + v[q].y * v[q].y + v[q].z * v[q].z + v[q].w * v[q].w;
+    return ss;
+  }
+};
+
+// piece q of a vector of dim4 float4 (dim4 = dim / 4) held by lane l; `p` points at the vector
+template <int SEG>
+__device__ inline RowVec<SEG> load_vec(const float4* p, uint32_t l, bool active) {
+  RowVec<SEG> r;
+#pragma unroll
+  for (int q = 0; q < SEG; ++q) r.v[q] = active ? p[q * 64 + l] : make_float4(0.f, 0.f, 0.f, 0.f);
+  return r;
+}
+template <int SEG>
+__device__ inline void store_vec(float4* p, uint32_t l, bool active, const RowVec<SEG>& r) {
+#pragma unroll
+  for (int q = 0; q < SEG; ++q)
+    if (active) p[q * 64 + l] = r.v[q];
+}
+template <typename E, int SEG>
+__device__ inline RowVec<SEG> load_row(const E* rows, uint32_t row, uint32_t dim, uint32_t l, bool active) {
+  RowVec<SEG> r;
+#pragma unroll
+  for (int q = 0; q < SEG; ++q)
+    r.v[q] = active ? load_row4<E>(rows, row, dim, q * 64 + l) : make_float4(0.f, 0.f, 0.f, 0.f);
+  return r;
+}
+
+// w -= scale * g on the lane's share of row `row`
+template <typename E, int SEG>
+__device__ inline void update_row(E* rows, uint32_t row, uint32_t dim, uint32_t l, const RowVec<SEG>& w,
+                                  const RowVec<SEG>& g, float scale) {
+#pragma unroll
+  for (int q = 0; q < SEG; ++q) {
+    float4 nw = w.v[q];
+    nw.x = fmaf(-scale, g.v[q].x, nw.x);
+    nw.y = fmaf(-scale, g.v[q].y, nw.y);
+    nw.z = fmaf(-scale, g.v[q].z, nw.z);
+    nw.w = fmaf(-scale, g.v[q].w, nw.w);
+    store_row4<E>(rows, row, dim, q * 64 + l, nw);
+  }
+}
+
+// Row-wise Adagrad on one row by one lane group; g = this lane's share of the gradient (zero in
 // lanes beyond dim).  acc += mean_j g_j^2; w_j -= lr * g_j / (sqrt(acc) + eps).
-template <typename E>
-__device__ inline void adagrad_row(const TableView& t, uint32_t row, float4 g, bool active, uint32_t l,
+template <typename E, int SEG>
+__device__ inline void adagrad_row(const TableView& t, uint32_t row, const RowVec<SEG>& g, bool active, uint32_t l,
                                    uint32_t group, float lr, float eps) {
-  float ss = g.x * g.x + g.y * g.y + g.z * g.z + g.w * g.w;
+  float ss = g.sum_sq();
   for (uint32_t d = 1; d < group; d <<= 1) ss += __shfl_xor(ss, (int)d);
   const float acc = t.state[row].acc + ss / (float)t.dim;
   const float scale = step_scale(acc, lr, eps);
   if (active) {
     E* rows = reinterpret_cast<E*>(t.rows);
-    float4 w = load_row4<E>(rows, row, t.dim, l);
-    w.x = fmaf(-scale, g.x, w.x);
-    w.y = fmaf(-scale, g.y, w.y);
-    w.z = fmaf(-scale, g.z, w.z);
-    w.w = fmaf(-scale, g.w, w.w);
-    store_row4<E>(rows, row, t.dim, l, w);
+    const RowVec<SEG> w = load_row<E, SEG>(rows, row, t.dim, l, true);
+    update_row<E, SEG>(rows, row, t.dim, l, w, g, scale);
   }
   if (l == 0) t.state[row] = RowState{acc, t.sync_epoch};  // trained in this window
 }
 
-__device__ inline void acc4(float4& a, const float4& b) {
-  a.x += b.x;
-  a.y += b.y;
-  a.z += b.z;
-  a.w += b.w;
-}
-
-// GLOG = log2(lanes per row).  A group owns ppl << GLOG consecutive sorted pairs (ppl = pairs per
-// lane, at most kPairsPerLane), so a block of 256 threads always owns a tile of 256 * ppl pairs; the
-// host picks ppl so that small batches still fill the machine.
-template <typename E, int GLOG>
+// GLOG = log2(lanes per row), SEG = pieces of four elements per lane (1 unless GLOG == 6).  A group
+// owns ppl << GLOG consecutive sorted pairs (ppl = pairs per lane, at most kPairsPerLane), so a block of
+// 256 threads always owns a tile of 256 * ppl pairs; the host picks ppl so that small batches still
+// fill the machine.
+template <typename E, int GLOG, int SEG>
 __global__ __launch_bounds__(256) void seg_reduce_kernel(TableView t, const uint2* __restrict__ pair_a,
                                                          const uint2* __restrict__ pair_b, uint64_t n,
                                                          const float* __restrict__ grad, float lr, float eps,
                                                          float* __restrict__ part, uint32_t* __restrict__ part_row,
                                                          uint32_t ppl) {
+  static_assert(SEG == 1 || GLOG == 6, "rows wider than 256 elements are held by a whole wave");
   extern __shared__ float4 s_mem[];  // [2 * groups_per_block][dim / 4] vectors, then the slot rows
+  using Vec = RowVec<SEG>;
   constexpr uint32_t group = 1u << GLOG, gpb = 256u >> GLOG;  // groups (= chunks) per block
   const uint32_t chunk = ppl << GLOG, tile = 256u * ppl;
-  constexpr int kBatch = group < 8 ? (int)group : 8;          // gradient rows in flight per lane
+  constexpr int kWide = (int)group < 8 ? (int)group : 8;
+  constexpr int kBatch = kWide / SEG > 0 ? kWide / SEG : 1;   // gradient rows in flight per lane
   const SortPlan plan = make_sort_plan(t.ctl->hwm);
   const uint2* __restrict__ sp = plan.passes % 2 ? pair_b : pair_a;  // where the sort left its result
   const uint32_t hwm = plan.hwm;
@@ -124,11 +182,10 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(TableView t, const uint
   const uint64_t c = c0 + g;
   const uint32_t chunks_here = (uint32_t)(n_chunks - c0 < gpb ? n_chunks - c0 : gpb);
   const bool active = l < dim4;
-  const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
   const float4* g4 = reinterpret_cast<const float4*>(grad);
 
   // ---- phase 0: the tile's sorted pairs -> LDS (coalesced) ---------------------------------------
-  __shared__ uint2 s_pairs[kReduceTile];
+  __shared__ uint2 s_pairs[SEG > 1 ? kReduceTile / 2 : kReduceTile];  // (wide rows: half the pairs, see the launcher)
   {
     const uint64_t t0 = (uint64_t)blockIdx.x * tile;
 #pragma unroll
@@ -151,64 +208,56 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(TableView t, const uint
     const bool first_head_in = cs == 0 || before != first;
     uint32_t run = first;
     bool head_in = first_head_in;
-    float4 sum = zero;
+    Vec sum;
+    sum.zero();
     E* rows = reinterpret_cast<E*>(t.rows);
     const float inv_dim = 1.0f / (float)t.dim;
     for (uint32_t p0 = 0; p0 < count; p0 += kBatch) {  // position of the batch in the chunk
-      {
-        uint32_t kx[kBatch + 1], ky[kBatch];
-        float4 v[kBatch], w[kBatch];
-        float a[kBatch];
-        bool tail[kBatch], apply[kBatch];
+      uint32_t kx[kBatch + 1], ky[kBatch];
+      Vec v[kBatch], w[kBatch];
+      float a[kBatch];
+      bool tail[kBatch], apply[kBatch];
 #pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-          const uint2 kv = p0 + (uint32_t)u < chunk ? mine[p0 + u] : make_uint2(kNoRow, 0u);
-          kx[u] = kv.x;
-          ky[u] = kv.y;
-        }
-        kx[kBatch] = p0 + kBatch < count ? mine[p0 + kBatch].x : after;
-        // everything the batch needs from memory is requested before anything is consumed: the
-        // gradient row of every pair and, for every run that ends in the batch and lies inside the
-        // chunk, its embedding row and accumulator
+      for (int u = 0; u < kBatch; ++u) {
+        const uint2 kv = p0 + (uint32_t)u < chunk ? mine[p0 + u] : make_uint2(kNoRow, 0u);
+        kx[u] = kv.x;
+        ky[u] = kv.y;
+      }
+      kx[kBatch] = p0 + kBatch < count ? mine[p0 + kBatch].x : after;
+      // everything the batch needs from memory is requested before anything is consumed: the
+      // gradient row of every pair and, for every run that ends in the batch and lies inside the
+      // chunk, its embedding row and accumulator
 #pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-          const bool in = p0 + (uint32_t)u < count;
-          const uint32_t next = p0 + (uint32_t)u + 1 < count ? kx[u + 1] : after;
-          tail[u] = in && next != kx[u];
-          apply[u] = tail[u] && kx[u] < hwm && (kx[u] != first || first_head_in);
-          v[u] = (in && kx[u] < hwm && active) ? g4[(uint64_t)ky[u] * dim4 + l] : zero;
-          w[u] = (apply[u] && active) ? load_row4<E>(rows, kx[u], t.dim, l) : zero;
-          a[u] = apply[u] ? t.state[kx[u]].acc : 0.f;
-        }
+      for (int u = 0; u < kBatch; ++u) {
+        const bool in = p0 + (uint32_t)u < count;
+        const uint32_t next = p0 + (uint32_t)u + 1 < count ? kx[u + 1] : after;
+        tail[u] = in && next != kx[u];
+        apply[u] = tail[u] && kx[u] < hwm && (kx[u] != first || first_head_in);
+        v[u] = load_vec<SEG>(g4 + (uint64_t)ky[u] * dim4, l, in && kx[u] < hwm && active);
+        w[u] = load_row<E, SEG>(rows, kx[u], t.dim, l, apply[u] && active);
+        a[u] = apply[u] ? t.state[kx[u]].acc : 0.f;
+      }
 #pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-          if (p0 + (uint32_t)u < count) {
-            if (kx[u] != run) {
-              run = kx[u];
-              head_in = true;
-              sum = zero;
-            }
-            acc4(sum, v[u]);
-            if (tail[u]) {
-              if (apply[u]) {  // the run lies inside the chunk: row-wise Adagrad at once
-                float ss = sum.x * sum.x + sum.y * sum.y + sum.z * sum.z + sum.w * sum.w;
+      for (int u = 0; u < kBatch; ++u) {
+        if (p0 + (uint32_t)u < count) {
+          if (kx[u] != run) {
+            run = kx[u];
+            head_in = true;
+            sum.zero();
+          }
+          sum.add(v[u]);
+          if (tail[u]) {
+            if (apply[u]) {  // the run lies inside the chunk: row-wise Adagrad at once
+              float ss = sum.sum_sq();
 #pragma unroll
-                for (uint32_t d = 1; d < group; d <<= 1) ss += __shfl_xor(ss, (int)d);
-                const float acc = a[u] + ss * inv_dim;
-                const float scale = step_scale(acc, lr, eps);
-                if (active) {
-                  float4 nw = w[u];
-                  nw.x = fmaf(-scale, sum.x, nw.x);
-                  nw.y = fmaf(-scale, sum.y, nw.y);
-                  nw.z = fmaf(-scale, sum.z, nw.z);
-                  nw.w = fmaf(-scale, sum.w, nw.w);
-                  store_row4<E>(rows, run, t.dim, l, nw);
-                }
-                if (l == 0) t.state[run] = RowState{acc, t.sync_epoch};
-              } else if (run < hwm) {  // started in an earlier chunk, ends here
-                a_row = run;
-                if (active) s_vec[(2 * g) * dim4 + l] = sum;
-              }
+              for (uint32_t d = 1; d < group; d <<= 1) ss += __shfl_xor(ss, (int)d);
+              const float acc = a[u] + ss * inv_dim;
+              const float scale = step_scale(acc, lr, eps);
+              if (active) update_row<E, SEG>(rows, run, t.dim, l, w[u], sum, scale);
+              if (l == 0) t.state[run] = RowState{acc, t.sync_epoch};
+            } else if (run < hwm) {  // started in an earlier chunk, ends here
+              a_row = run;
+              store_vec<SEG>(s_vec + (2 * g) * dim4, l, active, sum);
             }
           }
         }
@@ -216,7 +265,7 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(TableView t, const uint
     }
     if (after == run && run < hwm) {  // the last run continues in the next chunk
       b_row = run | (head_in ? kHeadFlag : 0u);
-      if (active) s_vec[(2 * g + 1) * dim4 + l] = sum;
+      store_vec<SEG>(s_vec + (2 * g + 1) * dim4, l, active, sum);
     }
   }
   if (l == 0) {
@@ -231,44 +280,46 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(TableView t, const uint
 
   // ---- phase 2: join the chunk partials of runs inside this tile -------------------------------
   // The group holding the first piece of a run within the tile walks the following chunks.
+  float4* part4 = reinterpret_cast<float4*>(part);
   const bool walker = c < n_chunks && b_row != kNoRow && ((b_row & kHeadFlag) || g == 0);
   if (walker) {
     const uint32_t row = b_row & ~kHeadFlag;
     const bool head_in_tile = (b_row & kHeadFlag) != 0;
-    float4 sum = active ? s_vec[(2 * g + 1) * dim4 + l] : zero;
+    Vec sum = load_vec<SEG>(s_vec + (2 * g + 1) * dim4, l, active);
     uint32_t cc = g + 1;
     bool tail = false;
     while (cc < chunks_here) {
       if (s_row[2 * cc] == row) {  // the run ends in chunk cc
-        if (active) acc4(sum, s_vec[(2 * cc) * dim4 + l]);
+        sum.add(load_vec<SEG>(s_vec + (2 * cc) * dim4, l, active));
         tail = true;
         break;
       }
       if (s_row[2 * cc + 1] != row) break;  // (cannot happen for consistent slots)
-      if (active) acc4(sum, s_vec[(2 * cc + 1) * dim4 + l]);
+      sum.add(load_vec<SEG>(s_vec + (2 * cc + 1) * dim4, l, active));
       ++cc;
     }
     if (tail && head_in_tile) {
-      adagrad_row<E>(t, row, sum, active, l, group, lr, eps);
+      adagrad_row<E, SEG>(t, row, sum, active, l, group, lr, eps);
     } else {
       const uint64_t slot = 2 * (uint64_t)blockIdx.x + (tail ? 0 : 1);
-      if (active) *reinterpret_cast<float4*>(part + slot * t.dim + l * 4) = sum;
+      store_vec<SEG>(part4 + slot * dim4, l, active, sum);
       if (l == 0) part_row[slot] = tail ? row : (row | (head_in_tile ? kHeadFlag : 0u));
     }
   }
   // a run that entered the tile from before and ends in chunk 0 is the tile's A partial as it stands
   if (g == 0 && c < n_chunks && a_row != kNoRow) {
-    if (active) *reinterpret_cast<float4*>(part + (2 * (uint64_t)blockIdx.x) * t.dim + l * 4) = s_vec[l];
+    store_vec<SEG>(part4 + (2 * (uint64_t)blockIdx.x) * dim4, l, active, load_vec<SEG>(s_vec, l, active));
     if (l == 0) part_row[2 * (uint64_t)blockIdx.x] = a_row;
   }
 }
 
 // One block per tile; only the block whose tile holds the head of a border-crossing run works.
-template <typename E>
+template <typename E, int SEG>
 __global__ __launch_bounds__(256) void combine_kernel(TableView t, uint64_t n_tiles, const float* __restrict__ part,
                                                       const uint32_t* __restrict__ part_row, float lr, float eps,
                                                       uint32_t group_log2) {
   extern __shared__ float4 s_mem[];  // [groups_per_block][dim / 4]
+  using Vec = RowVec<SEG>;
   const uint64_t c = blockIdx.x;
   const uint32_t head = part_row[2 * c + 1];
   if (head == kNoRow || !(head & kHeadFlag)) return;  // block-uniform
@@ -293,20 +344,21 @@ __global__ __launch_bounds__(256) void combine_kernel(TableView t, uint64_t n_ti
   const uint32_t g = threadIdx.x >> group_log2, l = threadIdx.x & (group - 1u);
   const uint32_t dim4 = t.dim >> 2;
   const bool active = l < dim4;
-  float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (active)
-    for (uint64_t p = g; p < pieces; p += gpb) {
-      const uint64_t slot = p <= mid ? 2 * (c + p) + 1 : 2 * tail;
-      acc4(sum, *reinterpret_cast<const float4*>(part + slot * t.dim + l * 4));
-    }
-  if (active) s_mem[g * dim4 + l] = sum;
+  const float4* part4 = reinterpret_cast<const float4*>(part);
+  Vec sum;
+  sum.zero();
+  for (uint64_t p = g; p < pieces; p += gpb) {
+    const uint64_t slot = p <= mid ? 2 * (c + p) + 1 : 2 * tail;
+    sum.add(load_vec<SEG>(part4 + slot * dim4, l, active));
+  }
+  store_vec<SEG>(s_mem + g * dim4, l, active, sum);
   __syncthreads();
   if (g == 0) {
-    float4 total = make_float4(0.f, 0.f, 0.f, 0.f);
+    Vec total;
+    total.zero();
     const uint32_t used = pieces < gpb ? (uint32_t)pieces : gpb;
-    if (active)
-      for (uint32_t q = 0; q < used; ++q) acc4(total, s_mem[q * dim4 + l]);
-    adagrad_row<E>(t, row, total, active, l, group, lr, eps);
+    for (uint32_t q = 0; q < used; ++q) total.add(load_vec<SEG>(s_mem + q * dim4, l, active));
+    adagrad_row<E, SEG>(t, row, total, active, l, group, lr, eps);
   }
 }
 
@@ -319,36 +371,46 @@ hipError_t launch_apply_grad_adagrad(const TableView& t, const UpdateWorkspace& 
   hipError_t e = launch_sort_pairs(t, ws, d_rows, n, n_bags, stream, prof);
   if (e != hipSuccess) return e;
   uint32_t group_log2 = 0;
-  while ((4u << group_log2) < t.dim) ++group_log2;
+  while (group_log2 < 6 && (4u << group_log2) < t.dim) ++group_log2;
+  const uint32_t seg = t.dim > 256 ? t.dim / 256 : 1;  // pieces of four elements per lane
   const uint32_t gpb = 256u >> group_log2;
-  uint32_t ppl = kPairsPerLane;  // fewer pairs per lane for small batches: at least ~2048 tiles
+  // pairs per lane: fewer for small batches (at least ~2048 tiles), and at most half the maximum for rows wider
+  // than 256 elements, whose partial sums take the LDS that the pairs would
+  uint32_t ppl = seg > 1 ? kPairsPerLane / 2 : kPairsPerLane;
   while (ppl > 1 && (n + 256ull * ppl - 1) / (256ull * ppl) < 2048) ppl >>= 1;
   const uint64_t n_tiles = (n + 256ull * ppl - 1) / (256ull * ppl);
   const dim3 block(256), grid((unsigned)n_tiles);
   const size_t lds_reduce = 2 * gpb * (t.dim / 4) * sizeof(float4) + 2 * gpb * sizeof(uint32_t);
   const size_t lds_combine = gpb * (t.dim / 4) * sizeof(float4);
-#define MONO_SEG_REDUCE(E, GLOG)                                                                                  \
-  MONO_LAUNCH_SMEM(prof, K_SEG_REDUCE, stream, (seg_reduce_kernel<E, GLOG>), grid, block, lds_reduce, t, ws.pair_a, \
+#define MONO_SEG_REDUCE(E, GLOG, SEG)                                                                                  \
+  MONO_LAUNCH_SMEM(prof, K_SEG_REDUCE, stream, (seg_reduce_kernel<E, GLOG, SEG>), grid, block, lds_reduce, t, ws.pair_a, \
                    ws.pair_b, n, d_grad, lr, eps, ws.part, ws.part_row, ppl)
-#define MONO_SEG_REDUCE_ALL(E)                   \
-  switch (group_log2) {                          \
-    case 0: MONO_SEG_REDUCE(E, 0); break;        \
-    case 1: MONO_SEG_REDUCE(E, 1); break;        \
-    case 2: MONO_SEG_REDUCE(E, 2); break;        \
-    case 3: MONO_SEG_REDUCE(E, 3); break;        \
-    case 4: MONO_SEG_REDUCE(E, 4); break;        \
-    case 5: MONO_SEG_REDUCE(E, 5); break;        \
-    default: MONO_SEG_REDUCE(E, 6); break;       \
+#define MONO_COMBINE(E, SEG)                                                                                     \
+  MONO_LAUNCH_SMEM(prof, K_COMBINE, stream, (combine_kernel<E, SEG>), grid, block, lds_combine, t, n_tiles, ws.part, \
+                   ws.part_row, lr, eps, group_log2)
+#define MONO_SEG_REDUCE_ALL(E)                                          \
+  switch (seg) {                                                        \
+    case 2: MONO_SEG_REDUCE(E, 6, 2); MONO_COMBINE(E, 2); break;        \
+    case 3: MONO_SEG_REDUCE(E, 6, 3); MONO_COMBINE(E, 3); break;        \
+    case 4: MONO_SEG_REDUCE(E, 6, 4); MONO_COMBINE(E, 4); break;        \
+    default:                                                            \
+      switch (group_log2) {                                             \
+        case 0: MONO_SEG_REDUCE(E, 0, 1); break;                        \
+        case 1: MONO_SEG_REDUCE(E, 1, 1); break;                        \
+        case 2: MONO_SEG_REDUCE(E, 2, 1); break;                        \
+        case 3: MONO_SEG_REDUCE(E, 3, 1); break;                        \
+        case 4: MONO_SEG_REDUCE(E, 4, 1); break;                        \
+        case 5: MONO_SEG_REDUCE(E, 5, 1); break;                        \
+        default: MONO_SEG_REDUCE(E, 6, 1); break;                       \
+      }                                                                 \
+      MONO_COMBINE(E, 1);                                               \
   }
   if (t.bf16) {
     MONO_SEG_REDUCE_ALL(uint16_t)
-    MONO_LAUNCH_SMEM(prof, K_COMBINE, stream, combine_kernel<uint16_t>, grid, block, lds_combine, t, n_tiles, ws.part,
-                     ws.part_row, lr, eps, group_log2);
   } else {
     MONO_SEG_REDUCE_ALL(float)
-    MONO_LAUNCH_SMEM(prof, K_COMBINE, stream, combine_kernel<float>, grid, block, lds_combine, t, n_tiles, ws.part,
-                     ws.part_row, lr, eps, group_log2);
   }
+#undef MONO_COMBINE
 #undef MONO_SEG_REDUCE_ALL
 #undef MONO_SEG_REDUCE
   return hipGetLastError();

@@ -50,6 +50,10 @@ CONFIGS = {
     "cfg5": Workload("cfg5", 5, 1 << 28, 64, True, 2, 50, 262144, 4, 0.0, "zipf", 1.2, 63),
 }
 
+# The batch shape of cfg2 over the 2^48 ID space of the paper's production model (section 3.1), for the
+# quotient-remainder embedding (two dense tables of 2^24 rows; no table object, so capacity etc. are unused).
+QR_WORKLOAD = Workload("qr", 6, 1 << 25, 32, False, 0, 0, 65536, 26, 3.0, "zipf", 1.05, 48)
+
 
 def scaled(wl, samples, capacity, drift_ranks=None):
     """Same distributions, smaller batch and table: parity-test sized variants of a configuration."""

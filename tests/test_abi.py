@@ -48,6 +48,9 @@ def test_size_query_validates_arguments_on_the_host(lib_path):
     assert lib.mono_table_bytes(1000, 16, 0, 4096, 4096) == 0                   # not a power of two
     assert lib.mono_table_bytes(1 << 16, 6, 0, 4096, 4096) == 0                 # dim not a multiple of 4
     assert lib.mono_table_bytes(1 << 16, 16, 2, 4096, 4096) == 0                # unknown storage flag
+    assert lib.mono_table_bytes(1 << 16, 1024, 0, 4096, 4096) > 0               # the paper's 4 KB rows
+    assert lib.mono_table_bytes(1 << 16, 260, 0, 4096, 4096) == 0               # beyond 256: multiples of 256 only
+    assert lib.mono_table_bytes(1 << 16, 1280, 0, 4096, 4096) == 0
     assert lib.mono_table_bytes(1 << 16, 16, 0, 0, 0) == 0
     assert lib.mono_strerror(-1) == b"invalid argument"
 

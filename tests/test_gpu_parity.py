@@ -123,11 +123,42 @@ def test_train_step_bf16_rows(dev):
     run_stream(wl, seed=5, steps=4, dev=dev, train=True, sweep=True)
 
 
-@pytest.mark.parametrize("dim", [4, 24, 128, 256])
-def test_other_dims(dev, dim):
+@pytest.mark.parametrize("dim,bf16", [(4, False), (24, False), (128, False), (256, False), (512, False), (768, True),
+                                      (1024, False), (1024, True)])
+def test_other_dims(dev, dim, bf16):
+    """Rows from 4 elements to the 1024 of the paper's synchronisation example (section 3.2.2: 4 KB rows);
+    beyond 256 elements a whole wave walks the row in pieces."""
     from dataclasses import replace
-    wl = replace(synth.scaled(synth.CONFIGS["cfg3"], samples=512, capacity=1 << 16), dim=dim, slots=8)
+    wl = replace(synth.scaled(synth.CONFIGS["cfg3"], samples=512, capacity=1 << 16), dim=dim, slots=8, bf16=bf16)
     run_stream(wl, seed=6 + dim, steps=3, dev=dev, train=True)
+
+
+def test_wide_rows_hot_key_snapshot_and_delta(dev):
+    """dim 1024: a key with 60 000 occurrences (its run crosses tiles and blocks), then the touched-keys
+    export, a snapshot and a restore into a fresh table, all against the oracle."""
+    from paper_2209_07663_amd.binding import Table
+    seed, dim, n_bags, cap = 31, 1024, 30000, 1 << 12
+    tab = Table(cap, dim, seed, freq_threshold=1, max_ids=1 << 17, max_bags=n_bags, device=dev)
+    orc = Oracle(cap, dim, seed, 1, 0, False, kind="cuckoo")
+    rng = np.random.default_rng(3)
+    offs_h = np.arange(0, 4 * n_bags + 1, 4, dtype=np.int64)
+    keys_h = rng.integers(0, 700, size=4 * n_bags).astype(np.int64)
+    keys_h[rng.random(4 * n_bags) < 0.5] = 987654321
+    grad_h = (rng.standard_normal((n_bags, dim)) * 0.1).astype(np.float32)
+    compare_step(tab, orc, {"keys": keys_h, "offsets": offs_h, "grad": grad_h, "step": 0}, dev, RTOL_F32,
+                 exact_rows=False, train=True)
+    t = tab.mono_export_touched()
+    assert (t["keys"] == orc.take_touched()).all() and t["rows"].shape == (t["n"], dim)
+    snap = tab.mono_table_export()
+    fresh = Table(cap, dim, seed, freq_threshold=1, max_ids=1 << 17, max_bags=n_bags, device=dev)
+    to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    assert fresh.mono_table_import(to_dev(snap["keys"]), to_dev(snap["rows"]), to_dev(snap["acc"]),
+                                   to_dev(snap["last_seen"].view(np.int32))) == 0
+    d = fresh.mono_table_export()
+    assert (d["keys"] == snap["keys"]).all() and (d["rows"].view(np.uint32) == snap["rows"].view(np.uint32)).all()
+    assert (d["acc"].view(np.uint32) == snap["acc"].view(np.uint32)).all()
+    tab.close()
+    fresh.close()
 
 
 def test_edge_cases(dev):
@@ -260,7 +291,7 @@ def test_seeded_random_configurations(dev, case):
     expiry, number of counter hashes, counter array size, bag lengths, key skew and padding keys."""
     from paper_2209_07663_amd.binding import Table
     rng = np.random.default_rng(1000 + case)
-    dim = int(rng.choice([4, 8, 12, 32, 64, 100, 256]))
+    dim = int(rng.choice([4, 8, 12, 32, 64, 100, 256, 512]))
     bf16 = bool(rng.integers(0, 2))
     thr = int(rng.choice([0, 1, 2, 3, 7]))
     expire = int(rng.choice([0, 0, 2, 5]))

@@ -56,6 +56,10 @@ MUTATIONS = [
     ("new_keys_are_stamped_with_step_zero", "  e->last_seen = step;", "  e->last_seen = 0;",
      "tests/test_oracle_semantics.py -k expiry"),
     ("accumulator_starts_at_one", "  e->acc = 0.0f;", "  e->acc = 1.0f;", "tests/test_oracle_pins.py -k 'update_equals or torch_adagrad'"),
+    ("quotient_and_remainder_swapped", "uint64_t id_r = id % rows, id_q = id / rows;",
+     "uint64_t id_q = id % rows, id_r = id / rows;", "tests/test_oracle_quotient_remainder.py"),
+    ("quotient_remainder_product_instead_of_sum", "(double)table_r[id_r * dim + j] + (double)table_q[id_q * dim + j];",
+     "(double)table_r[id_r * dim + j] * (double)table_q[id_q * dim + j];", "tests/test_oracle_quotient_remainder.py"),
     ("evicted_goes_to_same_table", "      side = 1 - side;  // the evicted element goes to its other sub-table",
      "      side = side;", "tests/test_oracle_pins.py -k cuckoo"),
 ]
