@@ -44,21 +44,24 @@ TRAFFIC_FROM_PROFILE = {
 }
 
 
+def _workload(name):
+    return synth.QR_WORKLOAD if name == "qr" else synth.CONFIGS[name]
+
+
 def _gen(args):
-    wl_name, seed, step = args
-    wl = synth.CONFIGS[wl_name]
-    return synth.make_batch(wl, seed, step, with_grad=True)
+    wl_name, seed, step, with_grad = args
+    return synth.make_batch(_workload(wl_name), seed, step, with_grad=with_grad)
 
 
-def generate_batches(wl_name, seed, steps, workers):
-    wl = synth.CONFIGS[wl_name]
+def generate_batches(wl_name, seed, steps, workers, with_grad=True):
+    wl = _workload(wl_name)
     if wl.drift_frac > 0:  # the rotating rank->ID map is sequential state
         drift = synth.DriftMap(wl, seed)
-        return [synth.make_batch(wl, seed, s, with_grad=True, drift=drift) for s in steps]
+        return [synth.make_batch(wl, seed, s, with_grad=with_grad, drift=drift) for s in steps]
     if workers <= 0:  # in-process (used under profilers, which have initialised the GPU already)
-        return [_gen((wl_name, seed, s)) for s in steps]
+        return [_gen((wl_name, seed, s, with_grad)) for s in steps]
     with mp.get_context("fork").Pool(workers) as pool:
-        return pool.map(_gen, [(wl_name, seed, s) for s in steps], chunksize=1)
+        return pool.map(_gen, [(wl_name, seed, s, with_grad) for s in steps], chunksize=1)
 
 
 def cpu_baseline(wl, seed, fill_chunks, untimed, timed, budget_s):
@@ -203,12 +206,80 @@ def time_maintenance(tab, wl, seed, max_ids, dev):
     return res
 
 
+def bench_quotient_remainder(args):
+    """Second workload: the quotient-remainder embedding of the paper's hashing baseline (section 3.1) through
+    the same pooling kernel: no table, no hashing, two dense tables of 2^24 rows.  A step = one pooled
+    gather over a fresh batch of the cfg2 shape with IDs of a 2^48 space."""
+    import torch
+    from paper_2209_07663_amd.binding import mono_qr_gather_pool
+    wl = synth.QR_WORKLOAD
+    n_steps = args.warmup + args.steps
+    batches = generate_batches("qr", args.seed, list(range(n_steps)), args.workers, with_grad=False)
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(args.seed)
+    tabs = [torch.randn((1 << 24, wl.dim), generator=gen, device=dev, dtype=torch.float32) * 0.05 for _ in range(2)]
+    cpu = None
+    if args.cpu_budget > 0:
+        from oracle import qr_pool
+        host = [t.cpu().numpy() for t in tabs]
+        ids, t0, used = 0, time.perf_counter(), 0
+        for b in batches[args.warmup:]:
+            qr_pool(host[0], host[1], b["keys"], b["offsets"])
+            ids += b["keys"].shape[0]
+            used += 1
+            if time.perf_counter() - t0 > args.cpu_budget:
+                break
+        dt = time.perf_counter() - t0
+        cpu = {"value": ids / dt, "unit": "IDs/s", "cores": 1, "kind": "oracle",
+               "sample": "pooled two-table sum on the first %d of the timed batches, %.1f s" % (used, dt),
+               "host_cpus_present": os.cpu_count()}
+        del host
+    dbat = [{"keys": torch.from_numpy(b["keys"]).to(dev), "offsets": torch.from_numpy(b["offsets"]).to(dev)}
+            for b in batches]
+    out = torch.empty((wl.n_bags, wl.dim), dtype=torch.float32, device=dev)
+    for b in dbat[:args.warmup]:
+        mono_qr_gather_pool(tabs[0], tabs[1], b["keys"], b["offsets"], out)
+    timed = dbat[args.warmup:]
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in timed]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for b, (e0, e1) in zip(timed, ev):
+        e0.record()
+        mono_qr_gather_pool(tabs[0], tabs[1], b["keys"], b["offsets"], out)
+        e1.record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ids = sum(b["keys"].shape[0] for b in timed)
+    ms = [e0.elapsed_time(e1) for e0, e1 in ev]
+    # compulsory bytes of a launch: IDs, offsets, every distinct row of either table once, the pooled output
+    algo = []
+    for b in timed:
+        k = b["keys"]
+        u = torch.unique(k & ((1 << 24) - 1)).numel() + torch.unique(k >> 24).numel()
+        algo.append(8 * k.shape[0] + 8 * (wl.n_bags + 1) + 4 * wl.dim * u + 4 * wl.dim * wl.n_bags)
+    achieved = float(np.mean(algo)) / (float(np.mean(ms)) * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "sparse IDs/sec per pooled gather (quotient-remainder embedding, no table)",
+        "value": ids / elapsed, "unit": "IDs/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "qr: two dense tables of 2^24 rows, dim 32 fp32, E = E_r[ID mod 2^24] + E_q[ID div 2^24], "
+                               "%d samples x %d slots, Zipf(%.2f) IDs over 2^48" % (wl.samples, wl.slots, wl.alpha),
+                   "ids_per_step": ids // args.steps, "step": "qr_gather_pool"},
+        "median_step_ms_events": float(np.median(ms)),
+        "roofline": {"bound": "hbm", "kernel": "gather_pool (quotient-remainder rows)", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None},
+        "cpu_baseline": cpu}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg2", choices=sorted(synth.CONFIGS))
+    ap.add_argument("--workload", default="cfg2", choices=sorted(synth.CONFIGS) + ["qr"],
+                    help="cfg1..cfg5: the table's training step; qr: the quotient-remainder embedding (pooled gather only)")
     ap.add_argument("--prefill", type=int, default=2, help="untimed steps before the warm-up steps")
     ap.add_argument("--profile-steps", type=int, default=4, help="extra steps run with per-kernel HIP events")
     ap.add_argument("--seed", type=int, default=1)
@@ -236,6 +307,8 @@ def main():
               file=sys.stderr)
         sys.exit(2)
 
+    if args.workload == "qr":
+        return bench_quotient_remainder(args)
     wl = synth.CONFIGS[args.workload]
     # Default state of the table: the workload's hottest IDs are admitted first (untimed) up to a load at
     # which a step admits few new keys, as after a long run; --fill-load 0 starts from the empty table.

@@ -52,7 +52,7 @@ typedef struct mono_stats {
   uint64_t n_expired;       /* keys removed by expire_sweep since creation */
   uint64_t n_insert_failed; /* eviction chains that hit the kick bound (element went to the stash) */
   uint64_t n_lost;          /* elements dropped because the stash was full too (must stay 0) */
-  uint64_t n_full;          /* admissible keys refused because the table was at its fill limit (see capacity) */
+  uint64_t n_full;          /* admissible keys refused because their call would have passed the fill limit (see capacity) */
   uint64_t stash_size;      /* elements currently in the stash */
   uint64_t max_chain;       /* longest eviction chain seen */
 } mono_stats;
@@ -64,8 +64,11 @@ size_t mono_table_bytes(uint64_t capacity, uint32_t dim, uint32_t flags, uint64_
 /* Creates a table (section 2.1: cuckoo hashmap + occurrence filter + expiry).
  *   capacity        total slots = embedding rows; power of two in [16, 2^30]; each sub-table has half.
  *                   At most capacity - capacity/32 keys are stored at a time: beyond that load the
- *                   eviction chains of section 2.1 become long enough to fail, so further admissible
- *                   keys are refused (row -1, counted in n_full) until keys expire or the table grows
+ *                   eviction chains of section 2.1 become long enough to fail.  A lookup_or_insert (or
+ *                   import) call whose new keys would take the table past that limit places NONE of its
+ *                   new keys (row -1, each counted in n_full; which keys are refused thus never depends
+ *                   on an order); they are admitted by a later call once keys have expired or the table
+ *                   has grown (their counters stay at or above the threshold)
  *   dim             embedding dimension; a multiple of 4 up to 256, or 512, 768 or 1024 (section 3.2.2
  *                   sizes its synchronisation example with 1024 fp32 elements = 4 KB per row)
  *   seed            fixes h0, h1, the counter hash and the initial value of every row
@@ -168,19 +171,25 @@ int mono_export_touched(mono_table* t, int64_t* d_keys, int32_t* d_row, float* d
  * mono_table_export and mono_filter_export return; this call places n records (key, row values,
  * accumulator, last-seen step) into the table: each gets a free row, is inserted by the eviction-chain
  * insertion of section 2.1 without consulting the occurrence filter, and is not marked touched.
- * The occurrence counters of a placed key are raised to freq_threshold if they are below it (a
- * stored key has been seen at least that often), so records may be restored without their counters.
+ * On a table that never expires keys (expire_steps == 0) the occurrence counters of a placed key are
+ * raised to freq_threshold if they are below it (there a stored key has been seen at least that often
+ * at all times), so records may be restored without their counters; counters that age are left alone.
  *   d_keys[n], d_values[n * dim] (fp32; rounded to nearest-even for bf16 rows), d_acc[n], d_last_seen[n]
  *   n <= max_ids per call (call repeatedly for more)
  *   h_refused  nullable; receives the number of records not placed: key already stored, key -1,
- *              second record of a key within the call, or no free row.  Non-NULL synchronises `stream`.
+ *              second record of a key within the call, or every record of a call that would take the
+ *              table past its fill limit.  Non-NULL synchronises `stream`.
  * Later lookups need step >= the largest restored last-seen step for expiry to be meaningful. */
 int mono_table_import(mono_table* t, const int64_t* d_keys, const float* d_values, const float* d_acc,
                       const uint32_t* d_last_seen, uint64_t n, uint64_t* h_refused, void* stream);
 
-/* Writes occurrence counters [first, first + count) from canonical words (see mono_filter_export).
- * Meant for the words of a snapshot: the counters of a stored key must not end up below
- * freq_threshold (with expire_steps == 0 a lookup reads such a counter as "this key is not stored"). */
+/* Writes occurrence counters [first, first + count) from canonical words (see mono_filter_export), as
+ * when the counters of a snapshot are restored (section 2.3).  On a table that never expires keys a
+ * stored key stays counted: each of its counters among the written ones that would end up below
+ * freq_threshold is raised to it, as mono_table_import does for a record that comes without its
+ * counters; so the two calls can be made in either order, and no words, not even all zeros, can hide a
+ * stored key from a later lookup (that costs one scan of the table, 16 bytes per slot, after the words
+ * are written).  On a table with expiry the words are stored as given. */
 int mono_filter_import(mono_table* t, const uint32_t* d_words, uint64_t first, uint64_t count, void* stream);
 
 /* Rehash / grow (section 2.1: a rehash answers an insertion that runs into a cycle; the table is

@@ -19,7 +19,9 @@
 //   1. occurrences are split into hits and misses against the table as it was BEFORE the batch;
 //   2. every miss occurrence bumps its key's occurrence counter (saturating at 255);
 //   3. every distinct missing key whose counter is now >= freq_threshold is admitted with a
-//      row that is a pure function of (seed, key), accumulator 0 and last_seen = step;
+//      row that is a pure function of (seed, key), accumulator 0 and last_seen = step - unless
+//      that would take the table past its fill limit of capacity - capacity/32 keys: then none
+//      of the batch's new keys is admitted (the rule does not depend on any order of the keys);
 //   4. every hit key gets last_seen = step;
 //   5. an occurrence is "present" iff its key is in the table after step 3;
 //   6. pooling sums the rows of the present occurrences of each bag (fp64 accumulate);
@@ -196,10 +198,16 @@ class Model {
     touched_.clear();
   }
   // place a record; false (and nothing changes) if the key is already stored or is the reserved key.
-  // A placed key's counters are raised to the admission threshold if they are below it: a stored
-  // key has been seen at least that often (records may be restored without their counters).
+  // Where counters never age (expire_steps == 0) a stored key's counters are at or above the admission
+  // threshold at all times, so a placed key's counters are raised to it if they are below (records may be
+  // restored without their counters).  Where counters age there is no such invariant - the counter of a
+  // stored key may have restarted since - and a restore must give back the snapshot as it was: nothing is raised.
   virtual bool import_entry(uint64_t key, const Entry& e) = 0;
+  virtual bool is_stored(uint64_t key) const = 0;
+  virtual uint64_t size() const = 0;
+  void count_refused_full(uint64_t n) { refused_full_ += n; }
   void raise_counters(uint64_t key) {
+    if (p_.expire_steps != 0) return;
     uint32_t least = p_.freq_threshold > 1 ? p_.freq_threshold : 1;
     for (uint32_t j = 0; j < p_.filter_hashes; ++j) {
       uint64_t i = filter_index(key, j);
@@ -208,11 +216,34 @@ class Model {
     }
   }
   virtual void set_filter_word(uint64_t index, uint32_t word) = 0;
+  // Counter words [first, first + count) are replaced (restore of the counters of a snapshot).  Where
+  // counters never age a stored key stays counted: any of its counters among the written ones that is
+  // now below the admission threshold is raised to it, exactly as when a record is restored without
+  // its counters (for the words of a consistent snapshot that changes nothing).
+  void write_filter_words(uint64_t first, uint64_t count, const uint32_t* words) {
+    for (uint64_t i = 0; i < count; ++i) set_filter_word(first + i, words[i]);
+    if (p_.expire_steps != 0) return;
+    std::vector<Exported> stored;
+    dump(&stored);
+    uint32_t least = p_.freq_threshold > 1 ? p_.freq_threshold : 1;
+    for (const Exported& x : stored)
+      for (uint32_t j = 0; j < p_.filter_hashes; ++j) {
+        uint64_t i = filter_index(x.key, j);
+        if (i < first || i - first >= count) continue;
+        uint32_t w = filter_word(i);
+        if ((w & 255u) < least) set_filter_word(i, (w & ~255u) | least);
+      }
+  }
   // re-insert everything under generation `generation` in a table of `new_capacity` >= capacity
   virtual void rehash(uint64_t new_capacity, uint32_t generation) = 0;
   virtual uint64_t insert_failures() const { return 0; }
   virtual uint64_t max_chain() const { return 0; }
   const Params& params() const { return p_; }
+  // Fill limit: a table of `capacity` slots stores at most capacity - capacity/32 keys (with buckets of
+  // eight, eviction chains grow steeply beyond that load).  A call whose new keys would take the table
+  // past the limit places NONE of them (whatever their order); they are counted as refused.
+  uint64_t fill_limit() const { return p_.capacity - p_.capacity / 32; }
+  uint64_t refused_full() const { return refused_full_; }
   // counter j of a key (j < filter_hashes); every hash addresses the whole array
   uint64_t filter_index(uint64_t key, uint32_t j = 0) const {
     return top_bits(mix64(key ^ p_.s_filter[j]), p_.lg_filter);
@@ -231,6 +262,7 @@ class Model {
   }
   Params p_;
   std::set<uint64_t> touched_;
+  uint64_t refused_full_ = 0;
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -257,12 +289,18 @@ class BruteForceModel final : public Model {
       }
     }
     // ... then admission: the key's count is the smallest of its counters
+    std::set<uint64_t> admissible;
     for (uint64_t i = 0; i < n; ++i) {
       uint64_t k = (uint64_t)keys[i];
-      if (k == kEmptyKey || was_hit[i] || table_.count(k)) continue;
+      if (k == kEmptyKey || was_hit[i]) continue;
       uint32_t count = 255u;
       for (uint32_t j = 0; j < p_.filter_hashes; ++j) count = std::min(count, filter_[filter_index(k, j)] & 255u);
-      if (count >= p_.freq_threshold) init_entry(p_, k, step, &table_[k]);
+      if (count >= p_.freq_threshold) admissible.insert(k);
+    }
+    if (table_.size() + admissible.size() > fill_limit()) {
+      refused_full_ += admissible.size();  // the batch would overfill the table: none of its new keys gets in
+    } else {
+      for (uint64_t k : admissible) init_entry(p_, k, step, &table_[k]);
     }
     for (uint64_t i = 0; i < n; ++i) {
       uint64_t k = (uint64_t)keys[i];
@@ -333,6 +371,8 @@ class BruteForceModel final : public Model {
     raise_counters(key);
     return true;
   }
+  bool is_stored(uint64_t key) const override { return table_.count(key) != 0; }
+  uint64_t size() const override { return table_.size(); }
   void set_filter_word(uint64_t index, uint32_t word) override { filter_[index] = word; }
   void rehash(uint64_t new_capacity, uint32_t generation) override {
     int k = regrow_params(new_capacity, generation);  // the map itself has no positions to redo
@@ -442,18 +482,29 @@ class CuckooModel final : public Model {
         w = filter_touch(w, step, p_.expire_steps);
       }
     }
-    for (uint64_t i = 0; i < n; ++i) {  // ascending first-occurrence order
-      uint64_t k = (uint64_t)keys[i];
-      if (k == kEmptyKey || was_hit[i] || find(k)) continue;
-      uint32_t count = 255u;
-      for (uint32_t j = 0; j < p_.filter_hashes; ++j) count = std::min(count, filter_[filter_index(k, j)] & 255u);
-      if (count < p_.freq_threshold) continue;
-      if (size_ >= p_.capacity) { ++insert_failures_; continue; }  // no row left
-      int32_t e = alloc_entry();
-      init_entry(p_, k, step, &pool_[e]);
-      key_of_entry_[e] = k;
-      insert(k, e);
-      ++size_;
+    std::vector<uint64_t> admissible;  // distinct, in ascending first-occurrence order
+    {
+      std::set<uint64_t> seen;
+      for (uint64_t i = 0; i < n; ++i) {
+        uint64_t k = (uint64_t)keys[i];
+        if (k == kEmptyKey || was_hit[i] || seen.count(k)) continue;
+        uint32_t count = 255u;
+        for (uint32_t j = 0; j < p_.filter_hashes; ++j) count = std::min(count, filter_[filter_index(k, j)] & 255u);
+        if (count < p_.freq_threshold) continue;
+        seen.insert(k);
+        admissible.push_back(k);
+      }
+    }
+    if (size_ + admissible.size() > fill_limit()) {
+      refused_full_ += admissible.size();  // the batch would overfill the table: none of its new keys gets in
+    } else {
+      for (uint64_t k : admissible) {
+        int32_t e = alloc_entry();
+        init_entry(p_, k, step, &pool_[e]);
+        key_of_entry_[e] = k;
+        insert(k, e);
+        ++size_;
+      }
     }
     for (uint64_t i = 0; i < n; ++i) {
       uint64_t k = (uint64_t)keys[i];
@@ -540,7 +591,6 @@ class CuckooModel final : public Model {
 
   bool import_entry(uint64_t key, const Entry& e) override {
     if (key == kEmptyKey || find(key)) return false;
-    if (size_ >= p_.capacity) { ++insert_failures_; return false; }  // no row left
     int32_t id = alloc_entry();
     pool_[id] = e;
     key_of_entry_[id] = key;
@@ -549,6 +599,8 @@ class CuckooModel final : public Model {
     raise_counters(key);
     return true;
   }
+  bool is_stored(uint64_t key) const override { return find(key) != nullptr; }
+  uint64_t size() const override { return size_; }
   void set_filter_word(uint64_t index, uint32_t word) override { filter_[index] = word; }
 
   // Every stored element is taken out and inserted again, slots in ascending order and then the
@@ -698,6 +750,8 @@ uint64_t orc_filter_index_j(void* hv, int64_t key, uint32_t j) {
 }
 
 uint64_t orc_insert_failures(void* hv) { return ((Handle*)hv)->m->insert_failures(); }
+// admissible keys (or restore records) refused because their call would have overfilled the table
+uint64_t orc_refused_full(void* hv) { return ((Handle*)hv)->m->refused_full(); }
 uint64_t orc_max_chain(void* hv) { return ((Handle*)hv)->m->max_chain(); }
 
 // -- maintenance operations -------------------------------------------------------------------
@@ -714,12 +768,22 @@ void orc_touched_keys(void* hv, int64_t* out) {
 }
 
 // restore: records are placed in the order given; rows[n * dim] are rounded to the storage type.
-// Returns the number of records NOT placed (key already stored, reserved key, or no row left).
+// Returns the number of records NOT placed: key already stored, reserved key, second record of a key
+// within the call, or - for every record of the call - a call that would take the table past its fill limit.
 uint64_t orc_import(void* hv, const int64_t* keys, const float* rows, const float* acc,
                     const uint32_t* last_seen, uint64_t n) {
   Handle* h = (Handle*)hv;
   const Params& p = h->m->params();
   uint64_t rejected = 0;
+  {
+    std::set<uint64_t> fresh;  // distinct keys of the call that are not stored yet
+    for (uint64_t i = 0; i < n; ++i)
+      if ((uint64_t)keys[i] != kEmptyKey && !h->m->is_stored((uint64_t)keys[i])) fresh.insert((uint64_t)keys[i]);
+    if (h->m->size() + fresh.size() > h->m->fill_limit()) {
+      h->m->count_refused_full(fresh.size());
+      return n;
+    }
+  }
   for (uint64_t i = 0; i < n; ++i) {
     Entry e;
     e.w.resize(p.dim);
@@ -731,8 +795,7 @@ uint64_t orc_import(void* hv, const int64_t* keys, const float* rows, const floa
   return rejected;
 }
 void orc_filter_write(void* hv, uint64_t first, uint64_t count, const uint32_t* words) {
-  Handle* h = (Handle*)hv;
-  for (uint64_t i = 0; i < count; ++i) h->m->set_filter_word(first + i, words[i]);
+  ((Handle*)hv)->m->write_filter_words(first, count, words);
 }
 
 // rehash / grow: new_capacity a power of two >= the current one; 0 on success, -1 on a bad argument

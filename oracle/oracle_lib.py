@@ -56,6 +56,8 @@ def oracle_lib():
         lib.orc_filter_index_j.argtypes = [_vp, ctypes.c_int64, _u32]
         lib.orc_insert_failures.restype = _u64
         lib.orc_insert_failures.argtypes = [_vp]
+        lib.orc_refused_full.restype = _u64
+        lib.orc_refused_full.argtypes = [_vp]
         lib.orc_max_chain.restype = _u64
         lib.orc_max_chain.argtypes = [_vp]
         lib.orc_take_touched.restype = _u64
@@ -205,6 +207,12 @@ class Oracle:
     @property
     def insert_failures(self):
         return self.lib.orc_insert_failures(self.h)
+
+    @property
+    def refused_full(self):
+        """Admissible keys (or restore records) refused because their call would have taken the table past
+        its fill limit of capacity - capacity/32 keys."""
+        return self.lib.orc_refused_full(self.h)
 
     @property
     def max_chain(self):

@@ -115,7 +115,9 @@ __host__ __device__ inline uint64_t mix64(uint64_t z) {
 // Rows that new keys may take when free_n rows are free.  The last 1/32 of the rows is held back:
 // with buckets of eight slots, eviction chains grow steeply past a load of ~0.97 (measured: chains
 // of 125 evictions at 0.965), and a chain that hits its bound costs a stash entry, then a resident.
-// A table therefore refuses new keys (counted in n_full) at load 31/32 instead of failing chains.
+// A table therefore stores at most capacity - capacity/32 keys: a call whose new keys do not ALL fit
+// under that limit places none of them (counted in n_full), so that which keys are refused does not
+// depend on the order in which the kernels happen to see them.
 __host__ __device__ inline int64_t rows_on_offer(uint64_t capacity, int32_t free_n) {
   const int64_t offer = (int64_t)free_n - (int64_t)(capacity >> kReserveShift);
   return offer > 0 ? offer : 0;

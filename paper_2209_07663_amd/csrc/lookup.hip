@@ -413,6 +413,8 @@ __global__ __launch_bounds__(256) void insert_kernel(TableView t, uint32_t step,
   }
   const uint32_t total = __shfl(inc, 63);
   const int32_t free0 = t.ctl->free_n;  // settled by the resolve kernel, constant here
+  // all of the call's new keys fit under the fill limit, or none of them is placed
+  const bool room = (int64_t)total <= rows_on_offer(t.capacity, free0);
   E* rows = reinterpret_cast<E*>(t.rows);
   const uint32_t stride = gridDim.x * blockDim.x;
   for (uint32_t w0 = blockIdx.x * blockDim.x + (threadIdx.x & ~63u); w0 < total; w0 += stride) {
@@ -436,15 +438,17 @@ __global__ __launch_bounds__(256) void insert_kernel(TableView t, uint32_t step,
       const Winner e = t.win_list[(uint64_t)lo * t.win_cap + p];
       occ = e.occ;
       k = e.key;
-      if ((int64_t)w < rows_on_offer(t.capacity, free0)) row = t.free_rows[free0 - 1 - (int32_t)w];
+      if (room) row = t.free_rows[free0 - 1 - (int32_t)w];
       t.dset_row[e.pos] = row == kNoRow ? kRowAbsent : (int32_t)row;
       rows_out[e.occ] = row == kNoRow ? kRowAbsent : (int32_t)row;
       if (row != kNoRow) {
         cuckoo_insert(t, k, make_meta(row, src.seen ? src.seen[e.occ] : step));
-        if (src.values) {
+        if (src.values && t.expire_steps == 0) {
           // a restored key counts as seen freq_threshold times: its counters are raised to that
           // (records may come without their counters, and a counter below the threshold would
-          // otherwise "prove" the key absent to the next lookup)
+          // otherwise "prove" the key absent to the next lookup).  Counters that age prove nothing
+          // and are left as they are: the restored table is then the snapshot, whatever the order
+          // in which records and counter words arrive
           const uint32_t least = t.freq_threshold > 1u ? t.freq_threshold : 1u;
           for (uint32_t j = 0; j < t.filter_hashes; ++j)
             atomicMax(reinterpret_cast<uint32_t*>(&t.filter[filter_index(t, k, j)]), least);
@@ -495,7 +499,7 @@ __global__ __launch_bounds__(256) void resolve_kernel(TableView t, uint64_t n, i
     }
     const int32_t free0 = t.ctl->free_n;
     const uint32_t offer = (uint32_t)rows_on_offer(t.capacity, free0);
-    const uint32_t got = total < offer ? total : offer;
+    const uint32_t got = total <= offer ? total : 0u;  // all of the call's new keys or none
     t.ctl->free_n = free0 - (int32_t)got;
     const uint32_t in_use = (uint32_t)t.capacity - (uint32_t)(free0 - (int32_t)got);
     if (in_use > t.ctl->hwm) t.ctl->hwm = in_use;  // rows are handed out in ascending order

@@ -270,11 +270,38 @@ __global__ __launch_bounds__(256) void filter_import_kernel(TableView t, const u
   t.filter[first + g] = ((unsigned long long)(w >> 8) << 32) | (unsigned long long)(w & 255u);
 }
 
+// Tables that never expire keys: a stored key stays counted.  Each of its counters inside
+// [first, first + count) that the import left below the admission threshold is raised to it (a lookup
+// of such a table reads a counter below the threshold as proof that the key is absent).  One thread
+// per slot, then the stash.
+__global__ __launch_bounds__(256) void filter_raise_kernel(TableView t, uint64_t first, uint64_t count) {
+  const uint64_t g = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  uint64_t key = kEmptyKey;
+  if (g < t.capacity) {
+    const Bucket* b = &t.buckets[g >> 3];
+    if (meta_row(b->meta[g & 7]) != kNoRow) key = b->key[g & 7];
+  } else if (g < t.capacity + kStashCap) {
+    const uint32_t s = (uint32_t)(g - t.capacity);
+    const uint32_t sn = t.ctl->stash_n < kStashCap ? t.ctl->stash_n : kStashCap;
+    if (s < sn) key = t.stash[s].key;
+  }
+  if (key == kEmptyKey) return;
+  const uint32_t least = t.freq_threshold > 1u ? t.freq_threshold : 1u;
+  for (uint32_t j = 0; j < t.filter_hashes; ++j) {
+    const uint64_t i = filter_index(t, key, j);
+    if (i >= first && i - first < count) atomicMax(reinterpret_cast<uint32_t*>(&t.filter[i]), least);
+  }
+}
+
 hipError_t launch_filter_import(const TableView& t, const uint32_t* d_words, uint64_t first, uint64_t count,
                                 hipStream_t stream) {
   if (count == 0) return hipSuccess;
   hipLaunchKernelGGL(filter_import_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, stream, t, d_words,
                      first, count);
+  if (t.expire_steps == 0) {  // (counters that age prove nothing about stored keys and stay as written)
+    const uint64_t total = t.capacity + kStashCap;
+    hipLaunchKernelGGL(filter_raise_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, t, first, count);
+  }
   return hipGetLastError();
 }
 

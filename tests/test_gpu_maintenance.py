@@ -215,12 +215,14 @@ def test_growing_an_overfull_table_empties_its_stash_and_makes_room(dev):
     tab = Table(cap, dim, seed, freq_threshold=1, max_ids=4096, max_bags=4096, device=dev)
     rng = np.random.default_rng(8)
     universe = (rng.permutation(1 << 20)[:1400].astype(np.int64) + 1) * 7919
+    limit = cap - cap // 32
     held = {}
-    for step, chunk in enumerate(np.array_split(universe, 4)):
+    # up to the limit in two batches, then the rest: a batch that does not fit is refused whole
+    for step, chunk in enumerate([universe[:500], universe[500:limit], universe[limit:]]):
         rows = tab.mono_lookup_or_insert(torch.from_numpy(chunk).to(dev), step).cpu().numpy()
         held.update({k: r for k, r in zip(chunk.tolist(), rows.tolist()) if r >= 0})
     st = tab.mono_table_stats()
-    assert st["size"] == len(held) == cap - cap // 32 and st["n_full"] > 0 and st["n_lost"] == 0
+    assert st["size"] == len(held) == limit and st["n_full"] == 1400 - limit and st["n_lost"] == 0
     big = tab.rehashed(cap * 2, 1)
     tab.close()
     st = big.mono_table_stats()
@@ -249,14 +251,16 @@ def test_rehash_at_the_fill_limit_loses_nothing(dev, cap):
     seed, dim, max_ids = 97, 4, 1 << 18
     tab = Table(cap, dim, seed, freq_threshold=1, max_ids=max_ids, max_bags=1, device=dev)
     universe = (np.random.default_rng(9).permutation(4 * cap)[: cap + cap // 8].astype(np.int64) + 1) * 7919
+    limit = cap - cap // 32
     held = {}
-    for step, lo in enumerate(range(0, universe.shape[0], max_ids)):
-        chunk = universe[lo:lo + max_ids]
+    # exactly `limit` keys in batches that fit, then the rest of the universe in one batch that does not
+    bounds = list(range(0, limit, max_ids)) + [limit, universe.shape[0]]
+    for step, (lo, hi) in enumerate(zip(bounds[:-1], bounds[1:])):
+        chunk = universe[lo:hi]
         rows = tab.mono_lookup_or_insert(torch.from_numpy(chunk).to(dev), step).cpu().numpy()
         held.update({k: r for k, r in zip(chunk.tolist(), rows.tolist()) if r >= 0})
-    limit = cap - cap // 32
     st = tab.mono_table_stats()
-    assert st["size"] == len(held) == limit and st["n_lost"] == 0 and st["n_full"] > 0
+    assert st["size"] == len(held) == limit and st["n_lost"] == 0 and st["n_full"] == universe.shape[0] - limit
     keys_now = np.array(sorted(held), dtype=np.int64)
     rows_now = np.array([held[k] for k in keys_now.tolist()])
     for generation in (1, 2, 3):
@@ -350,3 +354,37 @@ def test_restore_without_counters_on_a_table_that_never_expires(dev, hashes):
         _full_step(tab_b, orc_b, b, dev, wl, 1e-5, seed=seed)
     tab_a.close()
     tab_b.close()
+
+
+@pytest.mark.parametrize("hashes", [1, 2])
+def test_counter_words_imported_over_a_populated_table_hide_no_key(dev, hashes):
+    """All-zero counter words (and then random ones over a window) written into a populated table that never
+    expires keys: a lookup there trusts a counter below the threshold as proof of absence, so the import
+    must leave every stored key counted.  Counter words = oracle's, every key still found on both sides."""
+    from paper_2209_07663_amd.binding import Table
+    wl, seed = synth.scaled(synth.CONFIGS["cfg2"], samples=1024, capacity=1 << 16), 151
+    tab = Table(wl.capacity, wl.dim, seed, wl.freq_threshold, 0, False, max_ids=1 << 18, max_bags=wl.n_bags,
+                device=dev, filter_hashes=hashes)
+    orc = Oracle(wl.capacity, wl.dim, seed, wl.freq_threshold, 0, False, kind="cuckoo", filter_hashes=hashes)
+    batches = [synth.make_batch(wl, seed, s, with_grad=True) for s in range(5)]
+    for b in batches[:3]:
+        _full_step(tab, orc, b, dev, wl, 1e-5, seed=seed)
+    stored = tab.mono_table_export(with_values=False)["keys"]
+    assert stored.shape[0] > 1000
+    zeros = np.zeros(tab.n_filter, dtype=np.uint32)
+    tab.mono_filter_import(torch.from_numpy(zeros.view(np.int32)).to(dev))
+    orc.write_filter_words(zeros)
+    got = tab.mono_filter_export()
+    assert (got == orc.filter_words()).all() and np.count_nonzero(got) >= stored.shape[0] // 2
+    k_d = torch.from_numpy(stored).to(dev)
+    assert bool((tab.mono_lookup_or_insert(k_d, 3) >= 0).all().item()) and orc.lookup_or_insert(stored, 3).all()
+    rng = np.random.default_rng(2)
+    first, count = tab.n_filter // 4, tab.n_filter // 2
+    words = ((rng.integers(0, 4, size=count) << 8) | rng.integers(0, 3, size=count)).astype(np.uint32)
+    tab.mono_filter_import(torch.from_numpy(words.view(np.int32)).to(dev), first)
+    orc.write_filter_words(words, first)
+    assert (tab.mono_filter_export() == orc.filter_words()).all()
+    assert bool((tab.mono_lookup_or_insert(k_d, 3) >= 0).all().item()) and orc.lookup_or_insert(stored, 3).all()
+    for b in batches[3:]:
+        _full_step(tab, orc, b, dev, wl, 1e-5, seed=seed)
+    tab.close()

@@ -117,6 +117,63 @@ def test_streaming_drift_with_expiry(dev):
     assert log[-1][2] > 0
 
 
+@pytest.mark.timeout(600)
+def test_streaming_config_with_its_own_parameters_through_the_fill_limit_and_expiry(dev):
+    """configs[3] with its parameters unchanged (threshold 5, expiry after 20 steps, 5 % of the hot ranks
+    permuted per step, sweep every step), scaled in batch and table only: filled to load 0.9 with the hottest
+    IDs, then 100 training steps.  The load climbs to the fill limit of 31/32 around step 10 (from there a
+    batch whose new keys do not all fit places none of them, on both sides), the first expiry at step 20
+    empties most of the table, and the stream settles.  Presence, refused counts and expired sets are
+    compared at every step, whole tables and counter words every tenth."""
+    wl = synth.scaled(synth.CONFIGS["cfg4"], samples=256, capacity=1 << 17, drift_ranks=1 << 18)
+    assert wl.freq_threshold == 5 and wl.expire_steps == 20 and wl.drift_frac == 0.05
+    seed = 4
+    tab = make_table(wl, seed, max_ids=1 << 17, dev=dev)
+    orc = make_oracle(wl, seed)
+    drift = synth.DriftMap(wl, seed)
+    hot = synth.hottest_ids(wl, int(0.9 * wl.capacity), drift)
+    hot_d = torch.from_numpy(hot).to(dev)
+    for _ in range(wl.freq_threshold):
+        rows = tab.mono_lookup_or_insert(hot_d, 0)
+        present = orc.lookup_or_insert(hot, 0)
+    assert present.all() and bool((rows >= 0).all().item())
+    n_exp = torch.zeros(1, dtype=torch.int64, device=dev)
+    out = torch.zeros(wl.capacity, dtype=torch.int64, device=dev)
+    refused_at, expired_total, top_load = None, 0, 0.0
+    for step in range(1, 101):
+        b = synth.make_batch(wl, seed, step, with_grad=True, drift=drift)
+        keys, offs = torch.from_numpy(b["keys"]).to(dev), torch.from_numpy(b["offsets"]).to(dev)
+        rows = tab.mono_lookup_or_insert(keys, step)
+        present = orc.lookup_or_insert(b["keys"], step)
+        assert ((rows.cpu().numpy() >= 0) == present).all(), "presence differs at step %d" % step
+        tc.rows_close(tab.mono_gather_pool(rows, offs).cpu().numpy(), orc.pool(b["keys"], b["offsets"]), RTOL_F32)
+        tab.mono_apply_grad_adagrad(rows, offs, torch.from_numpy(b["grad"]).to(dev), wl.lr, wl.eps)
+        orc.apply_grad_adagrad(b["keys"], b["offsets"], b["grad"], wl.lr, wl.eps)
+        st = tab.mono_table_stats()
+        top_load = max(top_load, st["size"] / wl.capacity)
+        assert st["n_full"] == orc.refused_full, "refused keys differ at step %d" % step
+        assert st["n_insert_failed"] == 0 and st["n_lost"] == 0 and orc.insert_failures == 0
+        if refused_at is None and st["n_full"]:
+            refused_at = step
+        tab.mono_expire_sweep(step, n_exp, out)
+        want = orc.expire_sweep(step)
+        n = int(n_exp.item())
+        got = np.sort(out[:n].cpu().numpy().view(np.uint64)).view(np.int64)
+        assert n == want.shape[0] and (got == want).all(), "expired sets differ at step %d" % step
+        expired_total += n
+        if step % 10 == 0:
+            d = tab.mono_table_export()
+            tc.check_placement(d, wl.capacity, 8, seed)
+            tc.assert_same_table(d, orc.dump(), exact_rows=False, rtol=RTOL_F32)
+            assert (tab.mono_filter_export() == orc.filter_words()).all(), "counter words differ at step %d" % step
+            print("step %d load %.3f refused %d expired so far %d" % (step, st["size"] / wl.capacity, st["n_full"],
+                                                                     expired_total), flush=True)
+    assert refused_at is not None and refused_at < 20        # the limit was reached before anything expired
+    assert top_load <= 31 / 32 and top_load > 0.95
+    assert expired_total > wl.capacity // 2                  # ... and the first expiry emptied most of the table
+    tab.close()
+
+
 def test_train_step_bf16_rows(dev):
     """configs[4] shapes: bf16 rows, dim 64, one ID per bag, Zipf 1.2 over 2^63, threshold 2, expiry."""
     wl = synth.scaled(synth.CONFIGS["cfg5"], samples=16384, capacity=1 << 18)

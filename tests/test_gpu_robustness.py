@@ -29,33 +29,43 @@ def _lookup(tab, keys_h, step, dev):
 
 
 def test_overfull_table_loses_nothing_and_recovers(dev):
+    """1500 keys offered to a table whose fill limit is 992: a batch whose new keys do not all fit places
+    none of them (on the device and in the oracle alike), a last batch sized to the room that is left fills
+    the table to the limit exactly, and from then on every new key is refused and counted."""
     from paper_2209_07663_amd.binding import Table
     seed, cap, dim = 21, 1 << 10, 8
+    limit = cap - cap // 32
     tab = Table(cap, dim, seed, freq_threshold=1, expire_steps=4, max_ids=4096, max_bags=4096, device=dev)
+    orc = Oracle(cap, dim, seed, 1, 4, False, kind="cuckoo")
     rng = np.random.default_rng(5)
     universe = (rng.permutation(1 << 20)[:1500].astype(np.int64) + 1) * 7919
+    chunks = np.array_split(universe, 5)                 # 300 each: the fourth would pass the limit
+    chunks.append(universe[900:900 + (limit - 900)])     # exactly the room that is left
     held = {}                                            # key -> row, as handed out
-    for step, chunk in enumerate(np.array_split(universe, 5)):
+    for step, chunk in enumerate(chunks):
         print("overfull: step", step, flush=True)
-        rows = _lookup(tab, chunk, step, dev)
+        rows = _lookup(tab, chunk, min(step, 4), dev)
+        present = orc.lookup_or_insert(chunk, min(step, 4))
+        assert ((rows >= 0) == present).all()
         assert (rows >= -1).all() and (rows < cap).all()
+        assert (rows >= 0).all() or (rows == -1).all()   # all of a batch's new keys or none
         for k, r in zip(chunk.tolist(), rows.tolist()):
             if r >= 0:
                 held[k] = r
         d = tab.mono_table_export()
         st = tab.mono_table_stats()
-        assert st["n_lost"] == 0
-        assert d["keys"].shape[0] == st["size"] <= cap
+        assert st["n_lost"] == 0 and st["n_full"] == orc.refused_full
+        assert d["keys"].shape[0] == st["size"] <= limit
         assert int((d["slot"] < 0).sum()) == st["stash_size"]
         tc.check_placement(d, cap, 8, seed)              # unique keys, slots and rows; h0 / h1 buckets
+        tc.assert_same_table(d, orc.dump(), exact_rows=True)
         # the table holds exactly the keys that were given a row, under that row
         assert sorted(held) == d["keys"].tolist()
         assert (d["row"] == np.array([held[k] for k in d["keys"].tolist()])).all()
         # their rows still carry the initial values: no eviction chain damaged a resident
         assert (d["rows"] == tc.init_rows(d["keys"], dim, seed).astype(np.float32)).all()
     st = tab.mono_table_stats()
-    limit = cap - cap // 32                                # the last 1/32 of the rows is never handed out
-    assert st["n_full"] > 0 and st["size"] == limit        # 1500 keys cannot fit; the rest was refused, and counted
+    assert st["n_full"] == 600 and st["size"] == limit     # two batches of 300 were refused whole, and counted
     assert st["n_insert_failed"] == 0 and st["stash_size"] == 0   # ... before any eviction chain could fail
     # every stored key is found again, at its row, wherever an eviction chain moved it (stash included)
     keys_now = np.array(sorted(held), dtype=np.int64)
@@ -64,7 +74,8 @@ def test_overfull_table_loses_nothing_and_recovers(dev):
     # keys turned away stay absent while no row is free, and are counted, not stored
     size_before = tab.mono_table_stats()["size"]
     away = np.array([k for k in universe.tolist() if k not in held][:100], dtype=np.int64)
-    assert (_lookup(tab, away, 5, dev) == -1).all()
+    assert (_lookup(tab, away, 5, dev) == -1).all() and not orc.lookup_or_insert(away, 5).any()
+    assert (_lookup(tab, away[:1], 5, dev) == -1).all()    # not even one more key
     assert tab.mono_table_stats()["size"] == limit
     # recovery: everything expires, rows and slots are free again
     n_exp = torch.zeros(1, dtype=torch.int64, device=dev)

@@ -33,8 +33,8 @@ MUTATIONS = [
      "if (j == 0) count = filter_[filter_index(k, j)] & 255u;", "tests/test_oracle_filter.py"),
     ("restore_ignores_last_seen", "    e.last_seen = last_seen[i];", "    e.last_seen = 0;",
      "tests/test_oracle_maintenance.py -k restored_table"),
-    ("admission_strictly_above_threshold", "if (count >= p_.freq_threshold) init_entry(p_, k, step, &table_[k]);",
-     "if (count > p_.freq_threshold) init_entry(p_, k, step, &table_[k]);", "tests/test_oracle_semantics.py -k threshold"),
+    ("admission_strictly_above_threshold", "if (count >= p_.freq_threshold) admissible.insert(k);",
+     "if (count > p_.freq_threshold) admissible.insert(k);", "tests/test_oracle_semantics.py -k threshold"),
     ("hits_are_counted_too", "      if (k == kEmptyKey || was_hit[i]) continue;\n      for (uint32_t j = 0; j < p_.filter_hashes; ++j) {  // one touch per counter of the key",
      "      if (k == kEmptyKey) continue;\n      for (uint32_t j = 0; j < p_.filter_hashes; ++j) {  // one touch per counter of the key",
      "tests/test_oracle_semantics.py tests/test_oracle_pins.py -k 'filter or counter or tiny'"),
@@ -60,6 +60,12 @@ MUTATIONS = [
      "uint64_t id_q = id % rows, id_r = id / rows;", "tests/test_oracle_quotient_remainder.py"),
     ("quotient_remainder_product_instead_of_sum", "(double)table_r[id_r * dim + j] + (double)table_q[id_q * dim + j];",
      "(double)table_r[id_r * dim + j] * (double)table_q[id_q * dim + j];", "tests/test_oracle_quotient_remainder.py"),
+    ("written_counters_may_hide_a_stored_key", "        if (i < first || i - first >= count) continue;\n        uint32_t w = filter_word(i);\n        if ((w & 255u) < least) set_filter_word(i, (w & ~255u) | least);",
+     "        if (i < first || i - first >= count) continue;", "tests/test_oracle_maintenance.py -k written_over"),
+    ("fill_limit_admits_what_fits", "    if (size_ + admissible.size() > fill_limit()) {", "    if (false) {",
+     "tests/test_oracle_semantics.py -k 'fill_limit and cuckoo'"),
+    ("fill_limit_is_the_whole_capacity", "uint64_t fill_limit() const { return p_.capacity - p_.capacity / 32; }",
+     "uint64_t fill_limit() const { return p_.capacity; }", "tests/test_oracle_semantics.py -k fill_limit"),
     ("evicted_goes_to_same_table", "      side = 1 - side;  // the evicted element goes to its other sub-table",
      "      side = side;", "tests/test_oracle_pins.py -k cuckoo"),
 ]

@@ -166,3 +166,46 @@ def test_oracle_runs_the_small_configuration():
     pos = np.searchsorted(d["keys"], b["keys"])
     assert (out == d["rows"][pos]).all()                          # one ID per bag: pooled = the row
     assert (d["rows"] == tc.init_rows(d["keys"], wl.dim, 1).astype(np.float32)).all()
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_fill_limit_admits_all_new_keys_of_a_batch_or_none(kind):
+    """A table of 64 slots stores at most 64 - 64/32 = 62 keys.  A batch whose new keys would pass that is
+    refused whole (hits are still served, counters still count), whatever the order of its keys; a batch
+    that fits exactly is admitted; expiry makes room again.  Expected values follow from the rule, kept
+    in a Python set."""
+    o = Oracle(64, 2, seed=6, freq_threshold=1, expire_steps=3, kind=kind, n_filter=1 << 16)   # no shared counters
+    stored = set()
+    a = np.arange(100, 160, dtype=np.int64)                           # 60 keys: fits
+    assert o.lookup_or_insert(a, 0).all()
+    stored |= set(a.tolist())
+    b = np.array([1, 100, 2, 3], dtype=np.int64)                      # three new keys: 63 > 62 -> none of them
+    assert o.lookup_or_insert(b, 0).tolist() == [False, True, False, False]
+    assert o.refused_full == 3 and o.dump()["keys"].tolist() == sorted(stored)
+    assert o.lookup_or_insert(b[::-1].copy(), 0).tolist() == [False, False, True, False]   # same in any order
+    assert o.refused_full == 6
+    # the refused keys were counted all the same (twice by now)
+    assert [int(o.filter_words(o.filter_index(k), 1)[0]) & 255 for k in (1, 2, 3)] == [2, 2, 2]
+    c = np.array([1, 2], dtype=np.int64)                              # two new keys: 62 <= 62 -> both
+    assert o.lookup_or_insert(c, 1).all()
+    stored |= {1, 2}
+    assert o.lookup_or_insert(np.array([3], dtype=np.int64), 1).tolist() == [False]     # full: not even one
+    assert o.refused_full == 7 and len(o.dump()["keys"]) == 62
+    # step 3: the 60 keys last seen at step 0 expire (3 - 0 >= 3); 1 and 2 (seen at 1) stay
+    gone = o.expire_sweep(3)
+    assert sorted(gone.tolist()) == sorted(k for k in a.tolist())
+    assert o.lookup_or_insert(np.array([3], dtype=np.int64), 3).tolist() == [True]
+    assert o.dump()["keys"].tolist() == [1, 2, 3]
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_fill_limit_applies_to_restored_records_too(kind):
+    o = Oracle(64, 2, seed=7, freq_threshold=1, kind=kind)
+    keys = np.arange(1, 61, dtype=np.int64)
+    z = lambda n: (np.zeros((n, 2), np.float32), np.zeros(n, np.float32), np.zeros(n, np.uint32))
+    assert o.import_entries(keys, *z(60)) == 0
+    # 60 stored; a call with three records of new keys (one of them twice) and one stored key: 63 > 62 -> all refused
+    more = np.array([70, 71, 71, 72, 5], dtype=np.int64)
+    assert o.import_entries(more, *z(5)) == 5 and o.refused_full == 3
+    assert o.import_entries(more[:3], *z(3)) == 1                     # two new keys fit; the second 71 is a duplicate
+    assert o.dump()["keys"].tolist() == list(range(1, 61)) + [70, 71]
