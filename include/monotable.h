@@ -42,7 +42,7 @@ extern "C" {
 
 typedef struct mono_table mono_table; /* opaque; one table = one embedding dimension */
 
-enum { MONO_OK = 0, MONO_EINVAL = -1, MONO_ENOMEM = -2, MONO_EHIP = -3 };
+enum { MONO_OK = 0, MONO_EINVAL = -1, MONO_ENOMEM = -2, MONO_EHIP = -3, MONO_ELIMIT = -4 };
 enum { MONO_ROWS_FP32 = 0, MONO_ROWS_BF16 = 1 }; /* `flags`: storage type of the embedding rows */
 
 typedef struct mono_stats {
@@ -143,6 +143,23 @@ int mono_qr_gather_pool(const void* d_table_r, const void* d_table_q, uint32_t l
  * Occurrences with row -1 are dropped.  d_rows / d_offsets as in mono_gather_pool. */
 int mono_apply_grad_adagrad(mono_table* t, const int32_t* d_rows, uint64_t n, const int64_t* d_offsets,
                             uint64_t n_bags, const float* d_grad, float lr, float eps, void* stream);
+
+/* mono_apply_grad_adagrad for callers that must not allocate device memory and cannot bring a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and
+ * same result as mono_apply_grad_adagrad, but the per-call workspace (bag indices, the two buffers of
+ * sorted (row, bag) pairs, radix histograms, partial sums) is a fixed array inside the library instead of
+ * the table's arena: about 13 MB of device memory per GPU the library runs on, held until the process
+ * ends.  The call allocates nothing (no hipMalloc / hipFree, no event creation) and never synchronises.
+ *   limit   n <= mono_noalloc_max_ids() (262144) IDs per call, any dim the table can have; a larger batch
+ *           is refused with MONO_ELIMIT and nothing is done (split the batch by whole bags, or use
+ *           mono_apply_grad_adagrad)
+ *   sharing every call on one GPU uses the same array, whatever the table: two such calls that overlap on
+ *           one GPU (different streams, different threads) race; issue them in order on one stream.
+ *           Nothing in the array needs clearing between calls.
+ * The table's device must be the current device. */
+int mono_apply_grad_adagrad_noalloc(mono_table* t, const int32_t* d_rows, uint64_t n, const int64_t* d_offsets,
+                                    uint64_t n_bags, const float* d_grad, float lr, float eps, void* stream);
+uint64_t mono_noalloc_max_ids(void);
 
 /* Expiry (section 2.1, second heuristic): removes every key with now - last_seen >= expire_steps
  * (nothing if expire_steps == 0) and frees its row.

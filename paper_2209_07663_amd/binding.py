@@ -11,7 +11,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmonotable.so")
 
-MONO_OK, MONO_EINVAL, MONO_ENOMEM, MONO_EHIP = 0, -1, -2, -3
+MONO_OK, MONO_EINVAL, MONO_ENOMEM, MONO_EHIP, MONO_ELIMIT = 0, -1, -2, -3, -4
 MONO_ROWS_FP32, MONO_ROWS_BF16 = 0, 1
 
 _u64, _u32, _vp, _f32 = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_float
@@ -35,6 +35,8 @@ SYMBOLS = {
     "mono_gather_pool": (ctypes.c_int, [_vp, _vp, _u64, _vp, _u64, _vp, _vp]),
     "mono_qr_gather_pool": (ctypes.c_int, [_vp, _vp, _u32, _u32, _u32, _vp, _u64, _vp, _u64, _vp, _vp]),
     "mono_apply_grad_adagrad": (ctypes.c_int, [_vp, _vp, _u64, _vp, _u64, _vp, _f32, _f32, _vp]),
+    "mono_apply_grad_adagrad_noalloc": (ctypes.c_int, [_vp, _vp, _u64, _vp, _u64, _vp, _f32, _f32, _vp]),
+    "mono_noalloc_max_ids": (_u64, []),
     "mono_expire_sweep": (ctypes.c_int, [_vp, _u32, _vp, _vp, _u64, _vp]),
     "mono_table_stats": (ctypes.c_int, [_vp, ctypes.POINTER(mono_stats), _vp]),
     "mono_table_export": (ctypes.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _u64, ctypes.POINTER(_u64), _vp]),
@@ -183,6 +185,19 @@ class Table:
             raise ValueError("grad must hold n_bags * dim elements")
         _check(self.lib.mono_apply_grad_adagrad(self.h, _p(rows), rows.shape[0], _p(offsets), n_bags, _p(grad), lr,
                                                 eps, self._s()), "mono_apply_grad_adagrad")
+
+    def mono_apply_grad_adagrad_noalloc(self, rows, offsets, grad, lr, eps):
+        """The update through the library's fixed workspace (at most mono_noalloc_max_ids() IDs per call)."""
+        _dev(rows, torch.int32)
+        _dev(offsets, torch.int64)
+        _dev(grad, torch.float32)
+        n_bags = offsets.shape[0] - 1
+        if grad.numel() != n_bags * self.dim:
+            raise ValueError("grad must hold n_bags * dim elements")
+        with torch.cuda.device(self.device):
+            _check(self.lib.mono_apply_grad_adagrad_noalloc(self.h, _p(rows), rows.shape[0], _p(offsets), n_bags,
+                                                            _p(grad), lr, eps, self._s()),
+                   "mono_apply_grad_adagrad_noalloc")
 
     def mono_expire_sweep(self, now, n_expired=None, expired_keys=None):
         max_expired = 0

@@ -26,6 +26,10 @@ constexpr uint32_t kSortItemsPerBlock = MONO_SORT_ITEMS;      // consecutive ele
 constexpr int kPairsPerLane = 16;                  // sorted pairs per lane of a lane group in seg_reduce
 constexpr uint32_t kReduceTile = 256 * kPairsPerLane;  // sorted pairs reduced by one block
 
+#ifndef MONO_NOALLOC_MAX_IDS
+#define MONO_NOALLOC_MAX_IDS (1ull << 18)
+#endif
+
 inline uint64_t sort_units(uint64_t n) { return (n + kSortItemsPerBlock - 1) / kSortItemsPerBlock; }
 inline uint64_t reduce_tiles(uint64_t n) { return (n + 255) / 256; }  // most tiles a batch can need (one pair per lane)
 

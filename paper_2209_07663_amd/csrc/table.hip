@@ -1,4 +1,5 @@
 // Host side of the C ABI declared in include/monotable.h: argument checks, arena layout, launches.
+#include <mutex>
 #include <new>
 
 #include "../../include/monotable.h"
@@ -19,6 +20,19 @@ struct mono_table {
   int device = 0;
   Profiler prof;
 };
+
+// Fixed workspace of mono_apply_grad_adagrad_noalloc: one copy per GPU the library runs on, held until
+// the process ends.  In host code this name is only a handle for hipGetSymbolAddress; the address the
+// kernels get is the per-device pointer that static_workspace() keeps.
+constexpr uint64_t kStaticMaxIds = MONO_NOALLOC_MAX_IDS;  // largest batch of the allocation-free entry point
+constexpr uint32_t kStaticMaxDim = 1024;
+constexpr size_t static_part(size_t bytes) { return (bytes + 255) & ~(size_t)255; }
+constexpr size_t kStaticScratchBytes =
+    static_part(kStaticMaxIds * 4) + 2 * static_part(kStaticMaxIds * sizeof(uint2)) +
+    static_part(((size_t)kSortMaxBins * ((kStaticMaxIds + kSortItemsPerBlock - 1) / kSortItemsPerBlock) + kSortMaxBins) * 4) +
+    static_part(2 * ((kStaticMaxIds + 255) / 256) * kStaticMaxDim * sizeof(float)) +
+    static_part(2 * ((kStaticMaxIds + 255) / 256) * sizeof(uint32_t));
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -123,6 +137,45 @@ size_t layout(mono_table* t, char* base, uint64_t capacity, uint32_t dim, uint32
   return off;
 }
 
+// The per-device address of `scratch`, resolved once per device with that device current.
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+std::mutex g_scratch_mutex;
+
+hipError_t static_workspace(int device, uint32_t dim, UpdateWorkspace* ws) {
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  void* base = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+      int current = -1;
+      hipError_t e = hipGetDevice(&current);
+      if (e != hipSuccess) return e;
+      if (current != device) return hipErrorInvalidDevice;  // the table's device must be the current one
+      void* p = nullptr;
+      e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess) return e;
+      if (!p) return hipErrorInvalidSymbol;
+      g_scratch_ptr[device] = p;
+    }
+    base = g_scratch_ptr[device];
+  }
+  char* at = (char*)base;
+  auto take = [&](size_t bytes) {
+    char* p = at;
+    at += static_part(bytes);
+    return p;
+  };
+  const uint64_t tiles = reduce_tiles(kStaticMaxIds);
+  ws->bag_of = (uint32_t*)take(kStaticMaxIds * 4);
+  ws->pair_a = (uint2*)take(kStaticMaxIds * sizeof(uint2));
+  ws->pair_b = (uint2*)take(kStaticMaxIds * sizeof(uint2));
+  ws->hist = (uint32_t*)take(((size_t)kSortMaxBins * sort_units(kStaticMaxIds) + kSortMaxBins) * 4);
+  ws->part = (float*)take(2 * tiles * dim * sizeof(float));
+  ws->part_row = (uint32_t*)((char*)base + kStaticScratchBytes - static_part(2 * tiles * sizeof(uint32_t)));
+  return hipSuccess;
+}
+
 }  // namespace
 
 extern "C" {
@@ -133,6 +186,7 @@ const char* mono_strerror(int err) {
     case MONO_EINVAL: return "invalid argument";
     case MONO_ENOMEM: return "out of device memory";
     case MONO_EHIP: return "HIP runtime error";
+    case MONO_ELIMIT: return "batch exceeds the fixed workspace of the allocation-free entry point";
     default: return "unknown error";
   }
 }
@@ -274,6 +328,23 @@ int mono_apply_grad_adagrad(mono_table* t, const int32_t* d_rows, uint64_t n, co
   if (!d_rows || !d_offsets || !d_grad) return MONO_EINVAL;
   return launch_apply_grad_adagrad(t->view, t->ws, d_rows, n, d_offsets, n_bags, d_grad, lr, eps,
                                    (hipStream_t)stream, &t->prof) == hipSuccess
+             ? MONO_OK
+             : MONO_EHIP;
+}
+
+uint64_t mono_noalloc_max_ids(void) { return kStaticMaxIds; }
+
+int mono_apply_grad_adagrad_noalloc(mono_table* t, const int32_t* d_rows, uint64_t n, const int64_t* d_offsets,
+                                    uint64_t n_bags, const float* d_grad, float lr, float eps, void* stream) {
+  if (!t) return MONO_EINVAL;
+  if (n > kStaticMaxIds || n_bags > kStaticMaxIds + 1 || t->view.dim > kStaticMaxDim) return MONO_ELIMIT;
+  if (n == 0 || n_bags == 0) return MONO_OK;
+  if (!d_rows || !d_offsets || !d_grad) return MONO_EINVAL;
+  UpdateWorkspace ws;
+  if (static_workspace(t->device, t->view.dim, &ws) != hipSuccess) return MONO_EHIP;
+  // (no per-kernel events here: creating one may allocate)
+  return launch_apply_grad_adagrad(t->view, ws, d_rows, n, d_offsets, n_bags, d_grad, lr, eps, (hipStream_t)stream,
+                                   nullptr) == hipSuccess
              ? MONO_OK
              : MONO_EHIP;
 }
