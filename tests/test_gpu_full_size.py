@@ -1,9 +1,8 @@
 """Full-size configurations on the device, in the launch configuration bench.py times.
 
-configs[1] runs whole against the oracle (it finishes a step in a few seconds).  configs[2],
-configs[3] (filled to load 0.9 first) and configs[4] are too large for that, so they are checked on
-sampled outputs recomputed one by one in numpy from the device's own table dumps, plus the invariants
-that hold at any size.
+Every configuration runs whole against the oracle on the same seeded batches: presence of every
+occurrence, every pooled row, refused counts, expired sets, and at the end the whole table (keys,
+last-seen steps, rows, accumulators, placement) and every counter word.
 """
 import numpy as np
 import pytest
@@ -50,148 +49,121 @@ def test_config2_full_size_against_oracle():
     tab.close()
 
 
+def _full_step_against_oracle(tab, orc, b, dev, wl, rtol, sweep, out_buf):
+    """One whole step on both sides at full size: presence of every occurrence, every pooled row, the update,
+    and (if asked) the sweep with its set of expired keys."""
+    step = b["step"]
+    keys, offs = torch.from_numpy(b["keys"]).to(dev), torch.from_numpy(b["offsets"]).to(dev)
+    rows = tab.mono_lookup_or_insert(keys, step)
+    present = orc.lookup_or_insert(b["keys"], step)
+    assert ((rows.cpu().numpy() >= 0) == present).all(), "presence differs at step %d" % step
+    pooled = tab.mono_gather_pool(rows, offs).cpu().numpy()
+    tc.rows_close(pooled, orc.pool(b["keys"], b["offsets"]), rtol)
+    del pooled
+    tab.mono_apply_grad_adagrad(rows, offs, torch.from_numpy(b["grad"]).to(dev), wl.lr, wl.eps)
+    orc.apply_grad_adagrad(b["keys"], b["offsets"], b["grad"], wl.lr, wl.eps)
+    n = 0
+    if sweep:
+        n_exp = torch.zeros(1, dtype=torch.int64, device=dev)
+        tab.mono_expire_sweep(step, n_exp, out_buf)
+        want = orc.expire_sweep(step)
+        n = int(n_exp.item())
+        assert n == want.shape[0], "expired counts differ at step %d: %d vs %d" % (step, n, want.shape[0])
+        if n:
+            got = np.sort(out_buf[:n].cpu().numpy().view(np.uint64)).view(np.int64)
+            assert (got == want).all(), "expired sets differ at step %d" % step
+    st = tab.mono_table_stats()
+    assert st["n_insert_failed"] == 0 and st["n_lost"] == 0 and orc.insert_failures == 0
+    assert st["n_full"] == orc.refused_full
+    return n, st
+
+
+def _whole_tables_equal(tab, orc, wl, seed, rtol):
+    d = tab.mono_table_export()
+    tc.check_placement(d, wl.capacity, 8, seed)
+    tc.assert_same_table(d, orc.dump(), exact_rows=False, rtol=rtol)
+    del d
+    assert (tab.mono_filter_export() == orc.filter_words()).all(), "counter words differ"
+
+
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("name,samples", [("cfg3", None), ("cfg5", None)])
-def test_large_configs_sampled(name, samples):
+def test_config3_full_size_against_oracle():
+    """configs[2] whole against the oracle: 131072 samples x 40 slots (26 M IDs per step), dim 64, Adagrad,
+    two steps from the empty table (about 4 M keys admitted per step); whole table, every pooled row and
+    every counter word compared."""
     dev = torch.device("cuda:0")
-    wl, seed = synth.CONFIGS[name], 3
-    rtol = 1e-2 if wl.bf16 else 1e-5
-    rng = np.random.default_rng(0)
-    tab = None
-    seen_before = set()
+    wl, seed = synth.CONFIGS["cfg3"], 3
+    tab, orc = None, Oracle(wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, kind="cuckoo")
     for step in range(2):
-        print(name, "full size, step", step, flush=True)
+        print("config3 full size, step", step, flush=True)
         b = synth.make_batch(wl, seed, step, with_grad=True)
-        keys_h, offs_h, grad_h = b["keys"], b["offsets"], b["grad"]
         if tab is None:
-            tab = _table(wl, seed, int(keys_h.shape[0] * 1.05) + 1024, dev)
-        keys, offs = torch.from_numpy(keys_h).to(dev), torch.from_numpy(offs_h).to(dev)
-        rows = tab.mono_lookup_or_insert(keys, step)
-        rows_h = rows.cpu().numpy()
-        before = tab.mono_table_export()
-        tc.check_placement(before, wl.capacity, 8, seed)
-        # the key -> row map handed out is the one stored, and absent keys are exactly the non-admitted ones
-        present = rows_h >= 0
-        pos = np.searchsorted(before["keys"].view(np.uint64), keys_h[present].view(np.uint64))
-        assert (before["keys"][pos] == keys_h[present]).all() and (before["row"][pos] == rows_h[present]).all()
-        assert not np.isin(keys_h[~present], before["keys"]).any()
-        # admission rule on a sample of distinct keys: present <=> counter word reached the threshold
-        uniq = np.unique(keys_h)
-        some = rng.choice(uniq, size=min(20000, uniq.shape[0]), replace=False)
-        widx = tc.filter_index(some, 4 * wl.capacity, seed).astype(np.int64)
-        words = np.array([tab.mono_filter_export(int(i), 1)[0] for i in widx[:300]])
-        is_in = np.isin(some[:300], before["keys"])
-        was_in = np.array([k in seen_before for k in some[:300].tolist()])
-        assert ((words & 255) >= max(wl.freq_threshold, 1))[is_in & ~was_in].all()
-        assert (is_in | ((words & 255) < max(wl.freq_threshold, 1)))[~was_in].all()
-        # freshly admitted rows carry the initial values
-        new = ~np.isin(before["keys"], np.fromiter(seen_before, dtype=np.int64, count=len(seen_before)))
-        pick = np.flatnonzero(new)[:2000]
-        want = tc.init_rows(before["keys"][pick], wl.dim, seed).astype(np.float32)
-        if wl.bf16:
-            want = torch.from_numpy(want).to(torch.bfloat16).to(torch.float32).numpy()
-        assert (before["rows"][pick] == want).all() and (before["acc"][pick] == 0).all()
-        assert (before["last_seen"][np.isin(before["keys"], uniq)] == step).all()
-        # pooled sums of sampled bags from the dumped rows
-        pooled = tab.mono_gather_pool(rows, offs)
-        bags = rng.choice(wl.n_bags, size=3000, replace=False)
-        rowmap = np.full(int(before["row"].max()) + 1, -1, dtype=np.int64)
-        rowmap[before["row"]] = np.arange(before["row"].shape[0])
-        ref = np.zeros((bags.shape[0], wl.dim), dtype=np.float64)
-        for j, bg in enumerate(bags.tolist()):
-            r = rows_h[offs_h[bg]:offs_h[bg + 1]]
-            ref[j] = before["rows"][rowmap[r[r >= 0]]].astype(np.float64).sum(axis=0)
-        tc.rows_close(pooled[torch.from_numpy(bags).to(dev)].cpu().numpy(), ref, 1e-5 if not wl.bf16 else 1e-5)
-        # update: the hottest keys and a random sample, recomputed from their occurrences
-        tab.mono_apply_grad_adagrad(rows, offs, torch.from_numpy(grad_h).to(dev), wl.lr, wl.eps)
-        after = tab.mono_table_export()
-        assert (after["keys"] == before["keys"]).all() and (after["last_seen"] == before["last_seen"]).all()
-        vals, counts = np.unique(keys_h[present], return_counts=True)
-        hot = vals[np.argsort(counts)[-8:]]
-        chosen = np.unique(np.concatenate([hot, rng.choice(vals, size=400, replace=False)]))
-        bag_of = np.repeat(np.arange(wl.n_bags), np.diff(offs_h))
-        sel = np.isin(keys_h, chosen)
-        k_sel, b_sel = keys_h[sel], bag_of[sel]
-        order = np.argsort(k_sel, kind="stable")
-        k_sel, b_sel = k_sel[order], b_sel[order]
-        starts = np.flatnonzero(np.r_[True, k_sel[1:] != k_sel[:-1]])
-        gsum = np.add.reduceat(grad_h[b_sel].astype(np.float64), starts, axis=0)
-        kk = k_sel[starts]
-        p = np.searchsorted(before["keys"].view(np.uint64), kk.view(np.uint64))
-        acc = before["acc"][p].astype(np.float64) + (gsum ** 2).sum(axis=1) / wl.dim
-        w = before["rows"][p].astype(np.float64) - wl.lr * gsum / (np.sqrt(acc)[:, None] + wl.eps)
-        tc.rows_close(after["rows"][p], w, rtol)
-        assert (np.abs(after["acc"][p] - acc) <= 1e-5 * acc).all()
-        # rows of keys outside the batch are untouched
-        idle = ~np.isin(before["keys"], uniq)
-        assert (after["rows"][idle] == before["rows"][idle]).all() and (after["acc"][idle] == before["acc"][idle]).all()
-        tab.mono_expire_sweep(step)
-        seen_before = set(tab.mono_table_export(with_values=False)["keys"].tolist())
-        st = tab.mono_table_stats()
-        assert st["n_insert_failed"] == 0 and st["n_lost"] == 0 and st["n_full"] == 0
+            tab = _table(wl, seed, int(b["keys"].shape[0] * 1.05) + 1024, dev)
+        _full_step_against_oracle(tab, orc, b, dev, wl, 1e-5, sweep=False, out_buf=None)
+    print("config3 full size, comparing the tables", flush=True)
+    _whole_tables_equal(tab, orc, wl, seed, 1e-5)
+    assert tab.mono_table_stats()["size"] > 5_000_000
     tab.close()
 
 
 @pytest.mark.timeout(900)
-def test_config4_filled_to_load_09_then_streaming_steps():
-    """configs[3] at full size: the 0.9 * capacity hottest IDs are admitted first (threshold 5: each
-    is looked up five times), then drifting batches with a sweep every step.  30 M keys are too many
-    for the oracle, so: placement, uniqueness and conservation on the whole dump, the admission rule
-    and initial rows on samples, no failed eviction chain, and the same sampled checks per step."""
+def test_config5_full_size_against_oracle():
+    """configs[4] whole against the oracle: capacity 2^28, bf16 rows of dim 64, threshold 2, one ID per bag,
+    1 M IDs per step; three steps with a sweep each (nothing is 50 steps old yet: the scaled run in
+    test_gpu_parity.py crosses the expiry), whole table (rows within the bf16 tolerance), all 2^30 counter
+    words and every pooled row compared."""
     dev = torch.device("cuda:0")
-    wl, seed = synth.CONFIGS["cfg4"], 4
+    wl, seed = synth.CONFIGS["cfg5"], 5
+    orc = Oracle(wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, kind="cuckoo")
+    tab = _table(wl, seed, wl.n_bags, dev)
+    out = torch.zeros(1 << 20, dtype=torch.int64, device=dev)
+    for step in range(3):
+        print("config5 full size, step", step, flush=True)
+        b = synth.make_batch(wl, seed, step, with_grad=True)
+        n, st = _full_step_against_oracle(tab, orc, b, dev, wl, 1e-2, sweep=True, out_buf=out)
+        assert n == 0
+    print("config5 full size, comparing the tables", flush=True)
+    _whole_tables_equal(tab, orc, wl, seed, 1e-2)
+    assert tab.mono_table_stats()["size"] > 50_000
+    tab.close()
+
+
+@pytest.mark.timeout(1100)
+def test_config4_full_size_from_load_075_through_an_expiry_against_oracle():
+    """configs[3] at full size against the oracle: the 0.75 * capacity hottest IDs are admitted first
+    (threshold 5: each is looked up five times, on both sides), then drifting batches with a sweep every
+    step.  The expiry time is shortened from 20 steps to 3 so that the run reaches a sweep that removes keys
+    (most of the fill, about 20 M keys, at step 3) within a few steps; everything else is the configuration's
+    own.  Presence, pooled rows, refused counts and expired sets at every step, whole table and counter words
+    at the end."""
+    from dataclasses import replace
+    dev = torch.device("cuda:0")
+    wl, seed = replace(synth.CONFIGS["cfg4"], expire_steps=3), 4
     drift = synth.DriftMap(wl, seed)
-    hot = synth.hottest_ids(wl, int(0.9 * wl.capacity), drift)
-    assert np.unique(hot).shape[0] == hot.shape[0]
-    batches = [synth.make_batch(wl, seed, s, with_grad=True, drift=drift) for s in range(1, 4)]
-    max_ids = max(1 << 23, max(b["keys"].shape[0] for b in batches))
+    hot = synth.hottest_ids(wl, int(0.75 * wl.capacity), drift)
+    max_ids = 1 << 23
     tab = _table(wl, seed, max_ids, dev)
+    orc = Oracle(wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, kind="cuckoo")
     rows = torch.empty(max_ids, dtype=torch.int32, device=dev)
     for lo in range(0, hot.shape[0], max_ids):
-        chunk = torch.from_numpy(hot[lo:lo + max_ids]).to(dev)
+        chunk = hot[lo:lo + max_ids]
+        dchunk = torch.from_numpy(chunk).to(dev)
         for rep in range(wl.freq_threshold):
-            tab.mono_lookup_or_insert(chunk, 0, rows[: chunk.shape[0]])
-        # on the fifth sighting at the latest (keys that share a counter with others get there earlier)
-        assert int((rows[: chunk.shape[0]] >= 0).sum().item()) == chunk.shape[0]
-    print("config4: filled", flush=True)
-    st = tab.mono_table_stats()
-    assert st["size"] == hot.shape[0] and st["n_insert_failed"] == 0 and st["n_lost"] == 0 and st["n_full"] == 0
-    d = tab.mono_table_export(with_values=False)
-    assert (d["keys"].view(np.uint64) == np.sort(hot.view(np.uint64))).all()
-    tc.check_placement(d, wl.capacity, 8, seed)
-    rng = np.random.default_rng(0)
-    stored = d["keys"]
-    for b in batches:
-        step = b["step"]
+            tab.mono_lookup_or_insert(dchunk, 0, rows[: chunk.shape[0]])
+            present = orc.lookup_or_insert(chunk, 0)
+        assert ((rows[: chunk.shape[0]].cpu().numpy() >= 0) == present).all() and present.all()
+        print("config4 full size: filled chunk at", lo, flush=True)
+    assert tab.mono_table_stats()["size"] == hot.shape[0]
+    out = torch.zeros(wl.capacity, dtype=torch.int64, device=dev)
+    expired = []
+    for step in range(1, 6):
         print("config4 full size, step", step, flush=True)
-        keys_h, offs_h = b["keys"], b["offsets"]
-        keys, offs = torch.from_numpy(keys_h).to(dev), torch.from_numpy(offs_h).to(dev)
-        r = tab.mono_lookup_or_insert(keys, step)
-        r_h = r.cpu().numpy()
-        present = r_h >= 0
-        was_stored = np.isin(keys_h, stored)
-        assert present[was_stored].all()                      # a stored key is always found
-        # the others: present exactly if their counter word reached the threshold (sampled)
-        cand = np.unique(keys_h[~was_stored])
-        some = rng.choice(cand, size=min(300, cand.shape[0]), replace=False)
-        widx = tc.filter_index(some, 4 * wl.capacity, seed).astype(np.int64)
-        words = np.array([tab.mono_filter_export(int(i), 1)[0] for i in widx])
-        got_in = np.isin(some, keys_h[present])
-        assert (got_in == ((words & 255) >= wl.freq_threshold)).all()
-        pooled = tab.mono_gather_pool(r, offs)
-        tab.mono_apply_grad_adagrad(r, offs, torch.from_numpy(b["grad"]).to(dev), wl.lr, wl.eps)
-        assert bool(torch.isfinite(pooled).all().item())
-        n_exp = torch.zeros(1, dtype=torch.int64, device=dev)
-        tab.mono_expire_sweep(step, n_exp, None)
-        assert int(n_exp.item()) == 0                          # nothing is 20 steps old yet
-        d = tab.mono_table_export(with_values=False)
-        tc.check_placement(d, wl.capacity, 8, seed)
-        assert np.isin(stored, d["keys"]).all()
-        assert (d["last_seen"][np.isin(d["keys"], np.unique(keys_h[present]))] == step).all()
-        stored = d["keys"]
-        st = tab.mono_table_stats()
-        assert st["size"] == stored.shape[0] and st["n_insert_failed"] == 0 and st["n_lost"] == 0 and st["n_full"] == 0
-    assert stored.shape[0] > hot.shape[0]                      # keys keep being admitted at load 0.9
+        b = synth.make_batch(wl, seed, step, with_grad=True, drift=drift)
+        n, st = _full_step_against_oracle(tab, orc, b, dev, wl, 1e-5, sweep=True, out_buf=out)
+        expired.append(n)
+    assert expired[:2] == [0, 0] and expired[2] > 10_000_000 and expired[3] > 0    # a non-empty expiry fired
+    print("config4 full size, comparing the tables", flush=True)
+    _whole_tables_equal(tab, orc, wl, seed, 1e-5)
     tab.close()
 
 

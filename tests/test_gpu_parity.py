@@ -59,6 +59,7 @@ def compare_step(tab, orc, batch, dev, rtol, exact_rows, train, lr=0.05, eps=1e-
         tab.mono_apply_grad_adagrad(rows, offs, torch.from_numpy(grad_h).to(dev), lr, eps)
         orc.apply_grad_adagrad(keys_h, offs_h, grad_h, lr, eps)
         tc.assert_same_table(tab.mono_table_export(), orc.dump(), exact_rows=False, rtol=rtol)
+    n = None
     if sweep_at is not None:
         n_exp = torch.zeros(1, dtype=torch.int64, device=dev)
         out = torch.full((tab.capacity,), -7, dtype=torch.int64, device=dev)
@@ -69,7 +70,7 @@ def compare_step(tab, orc, batch, dev, rtol, exact_rows, train, lr=0.05, eps=1e-
         assert n == want.shape[0] and (got == want).all(), "expired sets differ at step %d" % step
         tc.assert_same_table(tab.mono_table_export(), orc.dump(), exact_rows=exact_rows and not train, rtol=rtol)
     if log is not None:
-        log.append((step, int(present.sum()), d["keys"].shape[0], worst))
+        log.append((step, int(present.sum()), d["keys"].shape[0], worst, n))
 
 
 def run_stream(wl, seed, steps, dev, train=False, sweep=False, check_filter=True):
@@ -178,6 +179,19 @@ def test_train_step_bf16_rows(dev):
     """configs[4] shapes: bf16 rows, dim 64, one ID per bag, Zipf 1.2 over 2^63, threshold 2, expiry."""
     wl = synth.scaled(synth.CONFIGS["cfg5"], samples=16384, capacity=1 << 18)
     run_stream(wl, seed=5, steps=4, dev=dev, train=True, sweep=True)
+
+
+@pytest.mark.timeout(600)
+def test_large_table_config_with_its_own_parameters_across_its_expiry(dev):
+    """configs[4] with its parameters unchanged (bf16 rows of dim 64, threshold 2, expiry after 50 steps, one
+    ID per bag, Zipf(1.2) over 2^63), scaled in batch and table only, for 64 training steps with a sweep each:
+    from step 50 on keys that were admitted early and never seen again leave, and the bf16 update is compared
+    with the oracle's rounding all the way."""
+    wl = synth.scaled(synth.CONFIGS["cfg5"], samples=2048, capacity=1 << 16)
+    assert wl.bf16 and wl.freq_threshold == 2 and wl.expire_steps == 50 and wl.dim == 64
+    log = run_stream(wl, seed=15, steps=64, dev=dev, train=True, sweep=True, check_filter=False)
+    expired = [entry[4] for entry in log]
+    assert sum(expired[:50]) == 0 and min(expired[51:]) > 0 and sum(expired) > 500    # keys leave once they turn 50
 
 
 @pytest.mark.parametrize("dim,bf16", [(4, False), (24, False), (128, False), (256, False), (512, False), (768, True),
