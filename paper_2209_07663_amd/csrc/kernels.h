@@ -8,10 +8,11 @@ namespace mono {
 
 // Per-call scratch for the update path, carved out of the table's arena.
 struct UpdateWorkspace {
-  uint32_t* bag_of;     // [max_ids] bag of each occurrence
+  uint32_t* bag_of;     // [max_ids]: first [sort_units] words: the bag that holds each sort unit's first occurrence
+                        // (a restore call borrows the whole array for its per-record results)
   uint2* pair_a;        // [max_ids] (row, bag) pairs, ping
   uint2* pair_b;        // [max_ids] pong
-  uint32_t* hist;       // [kSortMaxBins * sort_units(max_ids) + kSortMaxBins]
+  uint32_t* hist;       // [sort_hist_words(max_ids)]: per-unit digit histograms (bin-major), then the bin totals
   float* part;          // [2 * tiles * dim] partial gradient sums of runs that cross tile borders
   uint32_t* part_row;   // [2 * tiles] row (+ head flag) of each partial, kNoRow if unused
 };
@@ -31,6 +32,8 @@ constexpr uint32_t kReduceTile = 256 * kPairsPerLane;  // sorted pairs reduced b
 #endif
 
 inline uint64_t sort_units(uint64_t n) { return (n + kSortItemsPerBlock - 1) / kSortItemsPerBlock; }
+// words of the histogram workspace for batches of at most n elements: one histogram per unit, then the bin totals
+inline uint64_t sort_hist_words(uint64_t n) { return (uint64_t)kSortMaxBins * (sort_units(n) + 1); }
 inline uint64_t reduce_tiles(uint64_t n) { return (n + 255) / 256; }  // most tiles a batch can need (one pair per lane)
 
 // How many bits of the row index are sorted, in how many passes (computed alike on host and device).
@@ -80,7 +83,7 @@ hipError_t launch_apply_grad_adagrad(const TableView& t, const UpdateWorkspace& 
 // Stable LSD radix sort of the (row, bag) pairs of a batch; the result is in pair_b if the plan for
 // the device's high-water mark has an odd number of passes, else in pair_a.
 hipError_t launch_sort_pairs(const TableView& t, const UpdateWorkspace& ws, const int32_t* d_rows, uint64_t n,
-                             uint64_t n_bags, hipStream_t stream, Profiler* prof);
+                             const int64_t* d_offsets, uint64_t n_bags, hipStream_t stream, Profiler* prof);
 
 hipError_t launch_expire_sweep(const TableView& t, uint32_t now, uint64_t* d_n_expired, int64_t* d_expired_keys,
                                uint64_t max_expired, hipStream_t stream, Profiler* prof);

@@ -13,7 +13,6 @@ enum KernelId {
   K_INSERT,
   K_RESOLVE,
   K_GATHER_POOL,
-  K_EXPAND_BAGS,
   K_SORT_HIST,
   K_SORT_SCAN,
   K_SORT_SCATTER,
@@ -27,7 +26,7 @@ enum KernelId {
 };
 
 inline const char* kernel_name(int id) {
-  static const char* names[K_COUNT] = {"probe_count", "admit_elect", "insert", "resolve", "gather_pool", "expand_bags",
+  static const char* names[K_COUNT] = {"probe_count", "admit_elect", "insert", "resolve", "gather_pool",
                                        "sort_hist",   "sort_scan",    "sort_scatter", "seg_reduce",  "combine",
                                        "sweep_begin", "sweep_find", "sweep_remove", "sweep_end"};
   return id >= 0 && id < K_COUNT ? names[id] : "?";

@@ -6,8 +6,10 @@
 // bits are sorted in the fewest passes of at most kSortMaxBits bits, of equal width (eight bits or fewer
 // up to 16 M rows: a block's share of a bin is then long enough to leave as whole lines); the host launches the worst-case number of passes
 // and the superfluous ones return at once.  Pass p reads buffer (p even ? a : b)
-// and writes the other one.  Dropped occurrences (row -1) are left out by pass 0, which also
-// publishes the number of pairs that remain (kValidPairs slot of the control block's scratch).
+// and writes the other one.  Pass 0 reads the row indices as the caller holds them and finds the bag
+// of every occurrence from the offsets (no array of bag numbers is ever written to memory); dropped
+// occurrences (row -1) are left out by it, and it publishes the number of pairs that remain
+// (kValidPairs slot of the control block's scratch).
 //
 // Unit of work: one block of four waves owns kSortItemsPerBlock consecutive elements, a quarter
 // per wave.  Per pass:
@@ -53,10 +55,38 @@ __device__ inline uint32_t first_key(const int32_t* rows, uint64_t i, uint32_t h
   return r < hwm ? r : hwm;
 }
 
+// An offset of the caller's, bounded to the n occurrences of the batch.
+__device__ inline uint64_t bounded_offset(const int64_t* offsets, uint64_t b, uint64_t n) {
+  const int64_t o = offsets[b];
+  return o < 0 ? 0ull : ((uint64_t)o > n ? n : (uint64_t)o);
+}
+
+// The bag that holds occurrence `pos`: the last bag b with offsets[b] <= pos (offsets are non-decreasing
+// and start at 0).  Run by a whole wave: 64 probes per step, four dependent steps for two million bags.
+// Whatever the offsets hold, the answer is a bag index below n_bags and the loop ends.
+__device__ inline uint32_t bag_holding(const int64_t* offsets, uint64_t n_bags, uint64_t n, uint64_t pos) {
+  uint64_t lo = 0, hi = n_bags;
+  while (hi - lo > 1) {
+    const uint64_t step = (hi - lo + 63) / 64;
+    const uint64_t p = lo + (uint64_t)(lane_id() + 1) * step;
+    const bool ok = p < hi && bounded_offset(offsets, p, n) <= pos;
+    const uint64_t m = __ballot(ok);
+    const uint64_t k = m == ~0ull ? 64 : (uint64_t)(__ffsll((unsigned long long)~m) - 1);  // leading yes answers
+    const uint64_t nlo = lo + k * step, nhi = lo + (k + 1) * step;
+    lo = nlo;
+    hi = nhi < hi ? nhi : hi;
+  }
+  return (uint32_t)lo;
+}
+
+// Pass 0 also notes, for the scatter kernel of the same pass, the bag that holds the unit's first
+// occurrence (the last wave of the block searches while the others count).
 __global__ __launch_bounds__(kSortBlock) void sort_hist_kernel(const Control* __restrict__ ctl, uint32_t pass,
                                                                const int32_t* __restrict__ rows,
                                                                const uint2* __restrict__ src, uint64_t n,
-                                                               uint64_t units, uint32_t* __restrict__ hist) {
+                                                               uint64_t units, uint32_t* __restrict__ hist,
+                                                               const int64_t* __restrict__ offsets, uint64_t n_bags,
+                                                               uint32_t* __restrict__ unit_bag) {
   const SortPlan plan = make_sort_plan(ctl->hwm);
   if (pass >= plan.passes) return;
   __shared__ uint32_t cnt[kSortMaxBins];
@@ -66,16 +96,25 @@ __global__ __launch_bounds__(kSortBlock) void sort_hist_kernel(const Control* __
   __syncthreads();
   const uint64_t base = unit * kSortItemsPerBlock;
   if (pass > 0) n = ctl->scratch[kValidPairs];
-#pragma unroll 8
-  for (uint32_t r = 0; r < kSortItemsPerBlock / kSortBlock; ++r) {
+  // every key of the thread is requested before the first one is counted (left to itself the compiler
+  // keeps each load behind the LDS atomic before it: eight memory round trips in a row)
+  constexpr uint32_t kPerThread = kSortItemsPerBlock / kSortBlock;
+  uint32_t key[kPerThread];
+#pragma unroll
+  for (uint32_t r = 0; r < kPerThread; ++r) {
     const uint64_t i = base + (uint64_t)r * kSortBlock + threadIdx.x;
-    if (i < n) {
-      const uint32_t k = pass == 0 ? first_key(rows, i, plan.hwm) : src[i].x;
-      if (k < plan.hwm) atomicAdd(&cnt[(k >> shift) & mask], 1u);
-    }
+    key[r] = plan.hwm;
+    if (i < n) key[r] = pass == 0 ? first_key(rows, i, plan.hwm) : src[i].x;
   }
+#pragma unroll
+  for (uint32_t r = 0; r < kPerThread; ++r)
+    if (key[r] < plan.hwm) atomicAdd(&cnt[(key[r] >> shift) & mask], 1u);
   __syncthreads();
   for (uint32_t b = threadIdx.x; b < nbins; b += kSortBlock) hist[(uint64_t)b * units + unit] = cnt[b];
+  if (pass == 0 && (threadIdx.x >> 6) == kSortWaves - 1) {  // wave-uniform; after the last barrier: nobody waits for it
+    const uint32_t b0 = bag_holding(offsets, n_bags, n, unit * kSortItemsPerBlock);
+    if (lane_id() == 0) unit_bag[unit] = b0;
+  }
 }
 
 // exclusive scan of hist[bin * units + 0 .. units) in place; total of the bin to totals[bin].
@@ -126,8 +165,10 @@ __global__ __launch_bounds__(256) void sort_scan_kernel(const Control* __restric
 
 __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __restrict__ ctl, uint32_t pass,
                                                                   const int32_t* __restrict__ rows,
-                                                                  const uint32_t* __restrict__ bag_of,
-                                                                  uint32_t last_bag, const uint2* __restrict__ src,
+                                                                  const int64_t* __restrict__ offsets,
+                                                                  uint64_t n_bags,
+                                                                  const uint32_t* __restrict__ unit_bag,
+                                                                  const uint2* __restrict__ src,
                                                                   uint64_t n, uint64_t units,
                                                                   const uint32_t* __restrict__ hist,
                                                                   const uint32_t* __restrict__ totals,
@@ -142,22 +183,57 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
   const uint64_t unit = blockIdx.x;
   const uint32_t shift = plan.shift(pass), bits = plan.width(pass), nbins = 1u << bits, mask = nbins - 1;
 
+  // 0. what step 3 needs from memory is asked for first: it arrives while the elements are loaded
+  const bool bin_thread = threadIdx.x < kSortMaxBins;
+  const uint32_t bin = threadIdx.x;
+  uint32_t tot = 0, before_me = 0;  // the bin in the whole batch / in the units before this one
+  if (bin_thread && bin < nbins) {
+    tot = totals[bin];
+    before_me = hist[(uint64_t)bin * units + unit];
+  }
   // 1. this wave's elements -> registers (independent, coalesced loads)
   if (pass > 0) n = ctl->scratch[kValidPairs];
-  const uint64_t base = unit * kSortItemsPerBlock + (uint64_t)wave * kSortPerWave;
+  const uint64_t ubase = unit * kSortItemsPerBlock;
+  const uint64_t base = ubase + (uint64_t)wave * kSortPerWave;
   uint2 kv[kSortRounds];
 #pragma unroll
   for (uint32_t r = 0; r < kSortRounds; ++r) {
     const uint64_t i = base + (uint64_t)r * 64 + lane;
     kv[r] = make_uint2(0xFFFFFFFFu, 0u);
-    // (an occurrence that the caller's offsets left outside every bag carries a stale bag number:
-    // bounded here, so that a malformed offsets array cannot send a gradient read out of range)
-    if (i < n) kv[r] = pass == 0 ? make_uint2(first_key(rows, i, plan.hwm), min(bag_of[i], last_bag)) : src[i];
+    if (i < n) kv[r] = pass == 0 ? make_uint2(first_key(rows, i, plan.hwm), 0u) : src[i];
     if (kv[r].x >= plan.hwm) kv[r].x = 0xFFFFFFFFu;  // dropped occurrence (or past the end): left out
   }
   for (uint32_t b = threadIdx.x; b < kSortMaxBins; b += kSortBlock) {
 #pragma unroll
     for (int w = 0; w < kSortWaves; ++w) lds[w][b] = 0;
+  }
+  if (pass == 0) {
+    // The bag of every occurrence of the unit (the pooled gradient of bag b is the gradient of each of its
+    // occurrences): the unit's bags are walked from the one that holds its first occurrence, and each
+    // writes its number over its occurrences in an LDS array (the memory of `stage`, which is not needed
+    // yet).  Whatever the offsets hold, every write stays inside the unit and every bag number that is
+    // read is bounded to the bags of the batch.
+    uint32_t* bag_here = reinterpret_cast<uint32_t*>(stage);
+    const uint64_t uend = ubase + kSortItemsPerBlock < n ? ubase + kSortItemsPerBlock : n;
+    constexpr uint32_t kBagsPerThread = 4;  // consecutive bags per thread and round (a unit holds ~500 bags of four IDs)
+    // a thread stops at the first of its bags that starts at or after the end of the unit: offsets are
+    // non-decreasing, so no later bag of its can reach into the unit (no barrier inside the loop)
+    for (uint64_t b = (uint64_t)unit_bag[unit] + (uint64_t)threadIdx.x * kBagsPerThread; b < n_bags;
+         b += (uint64_t)kSortBlock * kBagsPerThread) {
+      uint64_t o[kBagsPerThread + 1];
+#pragma unroll
+      for (uint32_t q = 0; q <= kBagsPerThread; ++q) o[q] = b + q <= n_bags ? bounded_offset(offsets, b + q, n) : uend;
+      if (o[0] >= uend) break;
+#pragma unroll
+      for (uint32_t q = 0; q < kBagsPerThread; ++q) {
+        const uint64_t from = o[q] > ubase ? o[q] : ubase, to = o[q + 1] < uend ? o[q + 1] : uend;
+        for (uint64_t i = from; i < to; ++i) bag_here[i - ubase] = (uint32_t)(b + q);
+      }
+    }
+    __syncthreads();
+    const uint32_t last_bag = (uint32_t)(n_bags - 1);  // (an occurrence outside every bag reads whatever the LDS held)
+#pragma unroll
+    for (uint32_t r = 0; r < kSortRounds; ++r) kv[r].y = min(bag_here[wave * kSortPerWave + r * 64 + lane], last_bag);
   }
   __syncthreads();
   // 2. per-wave digit counts
@@ -170,13 +246,10 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
   //    (positions in `stage`) and once over all bins of the pass (start of the bin in dst)
   __shared__ uint32_t scan_sum[kScanWaves], scan_tot[kScanWaves];
   {
-    const bool bin_thread = threadIdx.x < kSortMaxBins;
-    const uint32_t bin = threadIdx.x;
-    uint32_t mine = 0, tot = 0;
+    uint32_t mine = 0;
     if (bin_thread && bin < nbins) {
 #pragma unroll
       for (int w = 0; w < kSortWaves; ++w) mine += lds[w][bin];
-      tot = totals[bin];
     }
     uint32_t x = mine, y = tot;  // inclusive wave scans
 #pragma unroll
@@ -200,7 +273,7 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
       }
       if (bin < nbins) {
         local_start[bin] = run;
-        global_start[bin] = run_tot + hist[(uint64_t)bin * units + unit];
+        global_start[bin] = run_tot + before_me;
         uint32_t at = run;
 #pragma unroll
         for (int w = 0; w < kSortWaves; ++w) {
@@ -239,7 +312,7 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
 }
 
 hipError_t launch_sort_pairs(const TableView& t, const UpdateWorkspace& ws, const int32_t* d_rows, uint64_t n,
-                             uint64_t n_bags, hipStream_t stream, Profiler* prof) {
+                             const int64_t* d_offsets, uint64_t n_bags, hipStream_t stream, Profiler* prof) {
   if (n == 0) return hipSuccess;
   const uint64_t units = sort_units(n);
   uint32_t* totals = ws.hist + (uint64_t)kSortMaxBins * units;
@@ -248,11 +321,12 @@ hipError_t launch_sort_pairs(const TableView& t, const UpdateWorkspace& ws, cons
   for (uint32_t p = 0; p < worst.passes; ++p) {
     const uint2* src = p % 2 == 0 ? ws.pair_a : ws.pair_b;
     uint2* dst = p % 2 == 0 ? ws.pair_b : ws.pair_a;
-    MONO_LAUNCH(prof, K_SORT_HIST, stream, sort_hist_kernel, grid, block, t.ctl, p, d_rows, src, n, units, ws.hist);
+    MONO_LAUNCH(prof, K_SORT_HIST, stream, sort_hist_kernel, grid, block, t.ctl, p, d_rows, src, n, units, ws.hist,
+                d_offsets, n_bags, ws.bag_of);
     MONO_LAUNCH(prof, K_SORT_SCAN, stream, sort_scan_kernel, dim3(kSortMaxBins), dim3(256), t.ctl, p, ws.hist, units,
                 totals);
-    MONO_LAUNCH(prof, K_SORT_SCATTER, stream, sort_scatter_kernel, grid, block, t.ctl, p, d_rows, ws.bag_of,
-                (uint32_t)(n_bags - 1), src, n, units, ws.hist, totals, dst);
+    MONO_LAUNCH(prof, K_SORT_SCATTER, stream, sort_scatter_kernel, grid, block, t.ctl, p, d_rows, d_offsets, n_bags,
+                ws.bag_of, src, n, units, ws.hist, totals, dst);
   }
   return hipGetLastError();
 }

@@ -29,7 +29,7 @@ constexpr uint32_t kStaticMaxDim = 1024;
 constexpr size_t static_part(size_t bytes) { return (bytes + 255) & ~(size_t)255; }
 constexpr size_t kStaticScratchBytes =
     static_part(kStaticMaxIds * 4) + 2 * static_part(kStaticMaxIds * sizeof(uint2)) +
-    static_part(((size_t)kSortMaxBins * ((kStaticMaxIds + kSortItemsPerBlock - 1) / kSortItemsPerBlock) + kSortMaxBins) * 4) +
+    static_part((size_t)kSortMaxBins * ((kStaticMaxIds + kSortItemsPerBlock - 1) / kSortItemsPerBlock + 1) * 4) +
     static_part(2 * ((kStaticMaxIds + 255) / 256) * kStaticMaxDim * sizeof(float)) +
     static_part(2 * ((kStaticMaxIds + 255) / 256) * sizeof(uint32_t));
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
@@ -106,7 +106,7 @@ size_t layout(mono_table* t, char* base, uint64_t capacity, uint32_t dim, uint32
   char* bag_of = take(max_ids * 4);
   char* pair_a = take(max_ids * sizeof(uint2));
   char* pair_b = take(max_ids * sizeof(uint2));
-  char* hist = take(((size_t)kSortMaxBins * sort_units(max_ids) + kSortMaxBins) * 4);
+  char* hist = take(sort_hist_words(max_ids) * 4);
   char* part = take(2 * tiles * dim * sizeof(float));
   char* part_row = take(2 * tiles * sizeof(uint32_t));
   (void)max_bags;
@@ -170,7 +170,7 @@ hipError_t static_workspace(int device, uint32_t dim, UpdateWorkspace* ws) {
   ws->bag_of = (uint32_t*)take(kStaticMaxIds * 4);
   ws->pair_a = (uint2*)take(kStaticMaxIds * sizeof(uint2));
   ws->pair_b = (uint2*)take(kStaticMaxIds * sizeof(uint2));
-  ws->hist = (uint32_t*)take(((size_t)kSortMaxBins * sort_units(kStaticMaxIds) + kSortMaxBins) * 4);
+  ws->hist = (uint32_t*)take(sort_hist_words(kStaticMaxIds) * 4);
   ws->part = (float*)take(2 * tiles * dim * sizeof(float));
   ws->part_row = (uint32_t*)((char*)base + kStaticScratchBytes - static_part(2 * tiles * sizeof(uint32_t)));
   return hipSuccess;

@@ -1,9 +1,9 @@
 // apply_grad_adagrad: duplicate-ID gradient scatter-reduce + row-wise Adagrad.
 //
-//   expand       bag index of every occurrence (the pooled gradient of bag b is the gradient of each
-//                of its occurrences)
-//   sort         stable radix sort of (row, bag) by row: the occurrences of a row become one run;
-//                dropped occurrences (row -1) are left out
+//   sort         stable radix sort of (row, bag) by row: the occurrences of a row become one run (the
+//                pooled gradient of bag b is the gradient of each of its occurrences; the first pass
+//                finds the bag of every occurrence from the offsets); dropped occurrences (row -1) are
+//                left out
 //   seg_reduce   the sorted sequence is cut into chunks of 16 pairs per lane of a lane group (dim/4
 //                lanes, four elements each); the group loads its chunk's pairs at once, then walks
 //                them with eight gradient rows in flight, summing grad[bag] along each run.  A run that lies
@@ -27,16 +27,6 @@
 namespace mono {
 
 constexpr uint32_t kHeadFlag = 0x80000000u;
-
-__global__ __launch_bounds__(256) void expand_bags_kernel(const int64_t* __restrict__ offsets, uint64_t n_bags,
-                                                          uint64_t n, uint32_t* __restrict__ bag_of) {
-  const uint64_t b = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= n_bags) return;
-  int64_t s = offsets[b], e = offsets[b + 1];
-  s = s < 0 ? 0 : s;  // offsets are the caller's: never write outside the n occurrences
-  e = e > (int64_t)n ? (int64_t)n : e;
-  for (int64_t i = s; i < e; ++i) bag_of[i] = (uint32_t)b;
-}
 
 template <typename E>
 __device__ inline float4 load_row4(const E* rows, uint32_t row, uint32_t dim, uint32_t l);
@@ -366,9 +356,7 @@ hipError_t launch_apply_grad_adagrad(const TableView& t, const UpdateWorkspace& 
                                      const int64_t* d_offsets, uint64_t n_bags, const float* d_grad, float lr, float eps,
                                      hipStream_t stream, Profiler* prof) {
   if (n == 0 || n_bags == 0) return hipSuccess;
-  MONO_LAUNCH(prof, K_EXPAND_BAGS, stream, expand_bags_kernel, dim3((unsigned)((n_bags + 255) / 256)), dim3(256),
-              d_offsets, n_bags, n, ws.bag_of);
-  hipError_t e = launch_sort_pairs(t, ws, d_rows, n, n_bags, stream, prof);
+  hipError_t e = launch_sort_pairs(t, ws, d_rows, n, d_offsets, n_bags, stream, prof);
   if (e != hipSuccess) return e;
   uint32_t group_log2 = 0;
   while (group_log2 < 6 && (4u << group_log2) < t.dim) ++group_log2;
