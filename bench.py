@@ -37,10 +37,10 @@ BUCKET_LINE = 128       # bytes of a bucket as this library stores it (keys + ro
 # them.  The figure is attached to a bench line only when workload and fill load are those of the
 # profiled command, together with the name of the summary it comes from; otherwise `traffic` is null.
 TRAFFIC_FROM_PROFILE = {
-    "cfg2": {"profile": "profiles/bench_cfg2_full_step.md", "fill_load": 0.0,
-             "step": 3.47e9,
-             "kernels": {"probe_count": 882.9e6, "seg_reduce": 985.7e6, "gather_pool": 503.1e6,
-                         "admit_elect": 361.5e6, "sort_scatter": 121.3e6, "sort_hist": 58.2e6, "insert": 103.8e6}},
+    "cfg2": {"profile": "profiles/bench_cfg2_full_step.md", "fill_load": 0.5,
+             "step": 3705.2e6,
+             "kernels": {"probe_count": 976.4e6, "seg_reduce": 1130.2e6, "gather_pool": 548.2e6,
+                         "admit_elect": 280.6e6, "sort_scatter": 140.4e6, "sort_hist": 73.3e6, "insert": 79.2e6}},
 }
 
 
