@@ -84,6 +84,9 @@ struct TableView {
   Winner* win_list;          // [kWinLists * win_cap] elected occurrences
   uint32_t* win_cnt;         // [kWinLists * kWinStride] fill of each sub-list (zero between calls)
   uint64_t win_cap;
+  unsigned long long* occupied;  // [capacity / 512, at least 1] one bit per bucket: set when a slot of the bucket is
+                                 // taken; a clear bit proves the bucket empty (the sweep skips it), a set bit
+                                 // proves nothing (the sweep clears it when it finds the bucket empty)
   uint32_t* sweep_list;      // [kWinLists * sweep_cap] slots found expired by the running sweep
   uint32_t* sweep_cnt;       // [kWinLists * kWinStride]
   uint64_t sweep_cap;
@@ -122,6 +125,10 @@ __host__ __device__ inline int64_t rows_on_offer(uint64_t capacity, int32_t free
   const int64_t offer = (int64_t)free_n - (int64_t)(capacity >> kReserveShift);
   return offer > 0 ? offer : 0;
 }
+
+constexpr int kSweepSlotsPerThread = 8;     // a wave of the sweep owns 64 buckets = one word of the occupancy bitmap
+constexpr uint64_t kSweepSlotsPerBlock = 256ull * kSweepSlotsPerThread;
+__host__ __device__ inline uint64_t occupancy_words(uint64_t capacity) { return (capacity + 511) / 512; }
 
 __device__ inline uint64_t shr_or_zero(uint64_t h, uint32_t shift) { return shift >= 64 ? 0 : h >> shift; }
 

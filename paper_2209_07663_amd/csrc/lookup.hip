@@ -296,7 +296,18 @@ __device__ inline void wait_all_memory_ops() {
   __asm__ volatile("" ::: "memory");
 }
 
-__device__ inline bool try_claim(Bucket* b, uint64_t k, unsigned long long meta) {
+// The bucket's bit in the occupancy bitmap.  Read first, with an ordinary load: most buckets that take a
+// key hold one already, and a stale copy can only show a bit as clear that another compute unit has set
+// in this very kernel (bits are cleared by the sweep alone, in a kernel of its own), which costs one
+// redundant atomic.
+__device__ inline void mark_occupied(const TableView& t, const Bucket* b) {
+  const uint64_t idx = (uint64_t)(b - t.buckets);
+  unsigned long long* w = &t.occupied[idx >> 6];
+  const unsigned long long bit = 1ull << (idx & 63);
+  if (!(*w & bit)) atomicOr(w, bit);
+}
+
+__device__ inline bool try_claim(const TableView& t, Bucket* b, uint64_t k, unsigned long long meta) {
   // snapshot of the eight keys (may be stale: a slot seen free may be taken by now; the CAS decides)
   const ulonglong2* kp = reinterpret_cast<const ulonglong2*>(b->key);
   const ulonglong2 a0 = kp[0], a1 = kp[1], a2 = kp[2], a3 = kp[3];
@@ -307,6 +318,7 @@ __device__ inline bool try_claim(Bucket* b, uint64_t k, unsigned long long meta)
     if (atomicCAS((unsigned long long*)&b->key[l], (unsigned long long)kEmptyKey, (unsigned long long)k) ==
         (unsigned long long)kEmptyKey) {
       st_agent(&b->meta[l], meta);  // issued after the CAS has returned: publishes the slot
+      mark_occupied(t, b);
       return true;
     }
   }
@@ -348,8 +360,8 @@ __device__ void cuckoo_insert(const TableView& t, uint64_t k, unsigned long long
 #pragma unroll 1
   for (int kick = 0; kick < kMaxKicks; ++kick) {
     Bucket* b = &t.buckets[bucket_index(t, side, k)];
-    if (try_claim(b, k, meta)) goto done;
-    if (kick == 0 && try_claim(&t.buckets[bucket_index(t, 1, k)], k, meta)) goto done;
+    if (try_claim(t, b, k, meta)) goto done;
+    if (kick == 0 && try_claim(t, &t.buckets[bucket_index(t, 1, k)], k, meta)) goto done;
     // evict: take the lock of a published slot
     const uint32_t v0 = pick_victim(t, b, side, (uint32_t)(mix64(k + (uint64_t)kick) >> 61));
 #pragma unroll 1

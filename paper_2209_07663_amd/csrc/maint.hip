@@ -12,8 +12,9 @@ __device__ inline bool is_expired(const TableView& t, uint32_t now, uint32_t see
 
 // Sweep in four kernels:
 //   sweep_begin  one thread: walks the (normally empty) stash; scratch[kSweepRemoved] = keys removed so far
-//   sweep_find   one thread per slot, read-only: slots whose stamp is too old are appended to one of
-//                kWinLists lists (one atomic per block, spread over the lists)
+//   sweep_find   eight slots per thread, only in buckets that the occupancy bitmap does not prove empty:
+//                slots whose stamp is too old are appended to one of kWinLists lists (one atomic per
+//                block, spread over the lists)
 //   sweep_remove dense over the found slots: pushes the row on the free stack by rank, reports the
 //                key, clears the slot
 //   sweep_end    one thread settles the counters
@@ -38,18 +39,49 @@ __global__ void sweep_begin_kernel(TableView t, uint32_t now, int64_t* expired_k
   c->scratch[kSweepRemoved] = removed;
 }
 
+// A wave owns 512 consecutive slots = 64 buckets = one word of the occupancy bitmap; a lane looks at one
+// slot of eight of those buckets (eight independent 8-byte loads, the eight lanes of a group covering a
+// bucket's meta words as one 64-byte access), and only at buckets whose bit is set: a sweep over a
+// sparsely filled table reads the bitmap and little else.  A bucket found empty gets its bit cleared.
 __global__ __launch_bounds__(256) void sweep_find_kernel(TableView t, uint32_t now) {
   __shared__ uint32_t wave_cnt[4];
   __shared__ uint32_t block_base;
-  const uint64_t g = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  bool expired = false;
-  if (g < t.capacity) {
-    const unsigned long long m = t.buckets[g >> 3].meta[g & 7];
-    expired = meta_row(m) != kNoRow && is_expired(t, now, meta_seen(m));
+  const uint64_t wave_global = ((uint64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const uint32_t lane = lane_id(), grp = lane >> 3, l8 = lane & 7;
+  const uint64_t slot0 = wave_global * 512;
+  // a table that is at least a quarter full has hardly an empty bucket: its sweep does not wait for the
+  // bitmap word before it asks for the buckets (and leaves the bitmap alone)
+  const int32_t free_n = t.ctl->free_n;
+  const bool dense = ((uint64_t)t.capacity - (uint64_t)(free_n < 0 ? 0 : free_n)) * 4 > t.capacity;
+  unsigned long long bits = 0;
+  if (slot0 < t.capacity) bits = dense ? ~0ull : t.occupied[wave_global];
+  unsigned long long m[kSweepSlotsPerThread];
+#pragma unroll
+  for (int s = 0; s < kSweepSlotsPerThread; ++s) {
+    const uint32_t bucket_here = 8u * (uint32_t)s + grp;
+    const uint64_t slot = slot0 + (uint64_t)bucket_here * 8 + l8;
+    m[s] = kNoMeta;
+    if (((bits >> bucket_here) & 1ull) && slot < t.capacity) m[s] = t.buckets[slot >> 3].meta[l8];
   }
+  uint64_t found[kSweepSlotsPerThread];
+  unsigned long long now_empty = 0;  // buckets of this wave that are flagged but hold nothing
+  uint32_t wave_total = 0;
+#pragma unroll
+  for (int s = 0; s < kSweepSlotsPerThread; ++s) {
+    const bool live = meta_row(m[s]) != kNoRow;
+    const uint64_t live_mask = __ballot(live);
+    const uint32_t bucket_here = 8u * (uint32_t)s + grp;
+    if (!dense && ((bits >> bucket_here) & 1ull) && ((live_mask >> (8 * grp)) & 0xFFull) == 0)
+      now_empty |= 1ull << bucket_here;
+    found[s] = __ballot(live && is_expired(t, now, meta_seen(m[s])));
+    wave_total += (uint32_t)__popcll(found[s]);
+  }
+  // every lane of a group computed the same verdict for its eight buckets: one lane per group clears
+#pragma unroll
+  for (int d = 8; d < 64; d <<= 1) now_empty |= __shfl_xor(now_empty, d);
+  if (lane == 0 && now_empty) atomicAnd(&t.occupied[wave_global], ~now_empty);
   const uint32_t wave = threadIdx.x >> 6;
-  const uint64_t mask = __ballot(expired);
-  if (lane_id() == 0) wave_cnt[wave] = (uint32_t)__popcll(mask);
+  if (lane == 0) wave_cnt[wave] = wave_total;
   __syncthreads();
   const uint32_t list = blockIdx.x & (kWinLists - 1);
   if (threadIdx.x == 0) {
@@ -57,10 +89,16 @@ __global__ __launch_bounds__(256) void sweep_find_kernel(TableView t, uint32_t n
     block_base = total ? atomicAdd(&t.sweep_cnt[list * kWinStride], total) : 0u;
   }
   __syncthreads();
-  if (expired) {
-    uint32_t p = block_base + (uint32_t)__popcll(mask & lanes_below());
-    for (uint32_t w = 0; w < wave; ++w) p += wave_cnt[w];
-    t.sweep_list[(uint64_t)list * t.sweep_cap + p] = (uint32_t)g;
+  if (wave_total == 0) return;  // wave-uniform
+  uint32_t p = block_base;
+  for (uint32_t w = 0; w < wave; ++w) p += wave_cnt[w];
+#pragma unroll
+  for (int s = 0; s < kSweepSlotsPerThread; ++s) {
+    if ((found[s] >> lane) & 1ull) {
+      const uint64_t slot = slot0 + (uint64_t)(8u * (uint32_t)s + grp) * 8 + l8;
+      t.sweep_list[(uint64_t)list * t.sweep_cap + p + (uint32_t)__popcll(found[s] & lanes_below())] = (uint32_t)slot;
+    }
+    p += (uint32_t)__popcll(found[s]);
   }
 }
 
@@ -126,7 +164,7 @@ hipError_t launch_expire_sweep(const TableView& t, uint32_t now, uint64_t* d_n_e
     return hipGetLastError();
   }
   MONO_LAUNCH(prof, K_SWEEP_BEGIN, stream, sweep_begin_kernel, dim3(1), dim3(64), t, now, d_expired_keys, max_expired);
-  const dim3 block(256), grid((unsigned)((t.capacity + 255) / 256));
+  const dim3 block(256), grid((unsigned)((t.capacity + kSweepSlotsPerBlock - 1) / kSweepSlotsPerBlock));
   MONO_LAUNCH(prof, K_SWEEP, stream, sweep_find_kernel, grid, block, t, now);
   MONO_LAUNCH(prof, K_SWEEP_REMOVE, stream, sweep_remove_kernel, dim3(grid.x < 2048u ? grid.x : 2048u), block, t,
               d_expired_keys, max_expired);
@@ -322,6 +360,8 @@ hipError_t launch_table_init(const TableView& t, uint64_t dset_size, hipStream_t
   if ((e = hipMemsetAsync(t.ctl, 0, sizeof(Control), stream)) != hipSuccess) return e;
   if ((e = hipMemsetAsync(t.win_cnt, 0, kWinLists * kWinStride * sizeof(uint32_t), stream)) != hipSuccess) return e;
   if ((e = hipMemsetAsync(t.sweep_cnt, 0, kWinLists * kWinStride * sizeof(uint32_t), stream)) != hipSuccess) return e;
+  if ((e = hipMemsetAsync(t.occupied, 0, occupancy_words(t.capacity) * sizeof(unsigned long long), stream)) != hipSuccess)
+    return e;
   if ((e = hipMemsetAsync(t.dset, 0, dset_size * sizeof(unsigned long long), stream)) != hipSuccess) return e;
   hipLaunchKernelGGL(init_free_rows_kernel, dim3((unsigned)((t.capacity + 255) / 256)), dim3(256), 0, stream, t);
   return hipGetLastError();

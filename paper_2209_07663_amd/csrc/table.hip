@@ -97,9 +97,11 @@ size_t layout(mono_table* t, char* base, uint64_t capacity, uint32_t dim, uint32
   char* dset_p = take(dset * sizeof(unsigned long long));
   char* dset_row = take(dset * sizeof(int32_t));
   const uint64_t win_cap = ((max_ids + 255) / 256 + kWinLists - 1) / kWinLists * 256;
-  const uint64_t sweep_cap = ((capacity + 255) / 256 + kWinLists - 1) / kWinLists * 256;
+  const uint64_t sweep_blocks = (capacity + kSweepSlotsPerBlock - 1) / kSweepSlotsPerBlock;
+  const uint64_t sweep_cap = (sweep_blocks + kWinLists - 1) / kWinLists * kSweepSlotsPerBlock;
   char* win_list = take(kWinLists * win_cap * sizeof(Winner));
   char* win_cnt = take(kWinLists * kWinStride * sizeof(uint32_t));
+  char* occupied = take(occupancy_words(capacity) * sizeof(unsigned long long));
   char* sweep_list = take(kWinLists * sweep_cap * sizeof(uint32_t));
   char* sweep_cnt = take(kWinLists * kWinStride * sizeof(uint32_t));
   const uint64_t tiles = reduce_tiles(max_ids);
@@ -124,6 +126,7 @@ size_t layout(mono_table* t, char* base, uint64_t capacity, uint32_t dim, uint32
     v.win_list = (Winner*)win_list;
     v.win_cnt = (uint32_t*)win_cnt;
     v.win_cap = win_cap;
+    v.occupied = (unsigned long long*)occupied;
     v.sweep_list = (uint32_t*)sweep_list;
     v.sweep_cnt = (uint32_t*)sweep_cnt;
     v.sweep_cap = sweep_cap;

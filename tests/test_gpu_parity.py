@@ -262,6 +262,31 @@ def test_edge_cases(dev):
     tab.close()
 
 
+def test_sweeps_of_a_sparse_table_find_keys_that_come_back_to_emptied_buckets(dev):
+    """A sweep only looks at buckets that a bitmap does not prove empty.  Keys are admitted into a large,
+    almost empty table, expire (their buckets empty out), a later sweep notes those buckets as empty, the
+    same keys come back into the same buckets, and expire again: every sweep must report exactly what
+    the oracle reports, and a capacity below one bitmap word (16 slots) works like any other."""
+    from paper_2209_07663_amd.binding import Table
+    for cap, n_keys in [(1 << 20, 3000), (1 << 9, 100), (16, 5)]:
+        seed = 43
+        tab = Table(cap, 4, seed, freq_threshold=1, expire_steps=2, max_ids=1 << 12, max_bags=1 << 12, device=dev)
+        orc = Oracle(cap, 4, seed, 1, 2, False, kind="cuckoo")
+        rng = np.random.default_rng(cap)
+        keys_a = (rng.permutation(1 << 20)[:n_keys].astype(np.int64) + 1) * 7919
+        keys_b = (rng.permutation(1 << 20)[:n_keys // 2].astype(np.int64) + 1) * 104729
+        plan = [(0, keys_a), (1, keys_b), (2, keys_b), (3, keys_b), (4, keys_b[:1]), (5, keys_a), (6, keys_a[:n_keys // 3]),
+                (7, keys_b[:1]), (8, keys_b[:1]), (9, keys_a)]
+        removed = 0
+        for step, keys_h in plan:
+            offs = np.arange(keys_h.shape[0] + 1, dtype=np.int64)
+            compare_step(tab, orc, {"keys": keys_h, "offsets": offs, "step": step}, dev, RTOL_F32, exact_rows=True,
+                         train=False, sweep_at=step)
+            removed = tab.mono_table_stats()["n_expired"]
+        assert removed >= n_keys                      # keys_a left once and came back
+        tab.close()
+
+
 @pytest.mark.parametrize("dim,bf16", [(4, False), (8, False), (32, False), (64, True), (100, False), (256, False)])
 def test_short_bags_of_zero_one_or_two_ids(dev, dim, bf16):
     """Bags of at most two IDs take a path of their own in the pooling kernel (several rounds of row
