@@ -99,7 +99,8 @@ int mono_table_create_ex(mono_table** out, uint64_t capacity, uint32_t dim, uint
                          uint32_t expire_steps, uint32_t flags, uint64_t max_ids, uint64_t max_bags,
                          uint32_t filter_hashes, uint32_t filter_log2, void* d_arena, size_t arena_bytes, void* stream);
 
-/* Frees the table (synchronises the device first).  The caller's arena, if any, is not freed. */
+/* Frees the table after waiting for the stream of the latest call that queued work for it (the calls of a
+ * table go to one stream in order).  The caller's arena, if any, is not freed. */
 int mono_table_destroy(mono_table* t);
 
 /* Batched lookup-or-insert (section 2.1: lookup in T0[h0(x)] / T1[h1(x)]; insertion with eviction

@@ -18,6 +18,8 @@ struct mono_table {
   uint64_t seed = 0;
   uint32_t generation = 0;  // rehash generation of the placement hashes h0 / h1
   int device = 0;
+  hipStream_t last_stream = nullptr;  // stream of the latest call that queued work for this table
+  bool used_stream = false;
   Profiler prof;
 };
 
@@ -179,6 +181,11 @@ hipError_t static_workspace(int device, uint32_t dim, UpdateWorkspace* ws) {
   return hipSuccess;
 }
 
+void note_stream(mono_table* t, void* stream) {
+  t->last_stream = (hipStream_t)stream;
+  t->used_stream = true;
+}
+
 }  // namespace
 
 extern "C" {
@@ -263,6 +270,7 @@ int mono_table_create_ex(mono_table** out, uint64_t capacity, uint32_t dim, uint
   v.sync_epoch = 1;
   t->max_ids = max_ids;
   t->max_bags = max_bags;
+  note_stream(t, stream);
   if (launch_table_init(v, t->dset_size, (hipStream_t)stream) != hipSuccess) {
     if (t->owned_arena) (void)hipFree(t->owned_arena);
     delete t;
@@ -275,7 +283,8 @@ int mono_table_create_ex(mono_table** out, uint64_t capacity, uint32_t dim, uint
 int mono_table_destroy(mono_table* t) {
   if (!t) return MONO_EINVAL;
   int rc = MONO_OK;
-  if (hipDeviceSynchronize() != hipSuccess) rc = MONO_EHIP;
+  // the calls of a table go to one stream in order: waiting for the latest one is waiting for all of them
+  if ((t->used_stream ? hipStreamSynchronize(t->last_stream) : hipDeviceSynchronize()) != hipSuccess) rc = MONO_EHIP;
   if (t->owned_arena && hipFree(t->owned_arena) != hipSuccess) rc = MONO_EHIP;
   for (auto& r : t->prof.recs) {  // timings nobody read
     (void)hipEventDestroy(r.start);
@@ -290,22 +299,25 @@ int mono_lookup_or_insert(mono_table* t, const int64_t* d_keys, uint64_t n, uint
   if (!t || n > t->max_ids || step >= (1u << 24) || step < t->last_step) return MONO_EINVAL;
   if (n == 0) return MONO_OK;
   if (!d_keys || !d_rows_out) return MONO_EINVAL;
-  t->last_step = step;
-  if (++t->epoch == 0) {  // the 32-bit call tag wrapped: forget every old tag
+  note_stream(t, stream);
+  uint32_t epoch = t->epoch + 1;
+  if (epoch == 0) {  // the 32-bit call tag wrapped: forget every old tag
     if (hipMemsetAsync(t->view.dset, 0, t->dset_size * sizeof(unsigned long long), (hipStream_t)stream) != hipSuccess)
       return MONO_EHIP;
-    t->epoch = 1;
+    epoch = 1;
   }
   const RestoreSource none = {nullptr, nullptr, nullptr};
-  return launch_lookup_or_insert(t->view, d_keys, n, step, t->epoch, d_rows_out, none, (hipStream_t)stream, &t->prof) ==
-                 hipSuccess
-             ? MONO_OK
-             : MONO_EHIP;
+  if (launch_lookup_or_insert(t->view, d_keys, n, step, epoch, d_rows_out, none, (hipStream_t)stream, &t->prof) != hipSuccess)
+    return MONO_EHIP;  // (the table's step and call tag move on only when the call was queued)
+  t->epoch = epoch;
+  t->last_step = step;
+  return MONO_OK;
 }
 
 int mono_gather_pool(mono_table* t, const int32_t* d_rows, uint64_t n, const int64_t* d_offsets, uint64_t n_bags,
                      float* d_out, void* stream) {
   if (!t || n > t->max_ids || n_bags > t->max_bags) return MONO_EINVAL;
+  note_stream(t, stream);
   if (n_bags == 0) return MONO_OK;
   if (!d_offsets || !d_out || (n && !d_rows)) return MONO_EINVAL;
   return launch_gather_pool(t->view, d_rows, n, d_offsets, n_bags, d_out, (hipStream_t)stream, &t->prof) == hipSuccess ? MONO_OK
@@ -327,6 +339,7 @@ int mono_qr_gather_pool(const void* d_table_r, const void* d_table_q, uint32_t l
 int mono_apply_grad_adagrad(mono_table* t, const int32_t* d_rows, uint64_t n, const int64_t* d_offsets,
                             uint64_t n_bags, const float* d_grad, float lr, float eps, void* stream) {
   if (!t || n > t->max_ids || n_bags > t->max_bags) return MONO_EINVAL;
+  note_stream(t, stream);
   if (n == 0 || n_bags == 0) return MONO_OK;
   if (!d_rows || !d_offsets || !d_grad) return MONO_EINVAL;
   return launch_apply_grad_adagrad(t->view, t->ws, d_rows, n, d_offsets, n_bags, d_grad, lr, eps,
@@ -340,6 +353,7 @@ uint64_t mono_noalloc_max_ids(void) { return kStaticMaxIds; }
 int mono_apply_grad_adagrad_noalloc(mono_table* t, const int32_t* d_rows, uint64_t n, const int64_t* d_offsets,
                                     uint64_t n_bags, const float* d_grad, float lr, float eps, void* stream) {
   if (!t) return MONO_EINVAL;
+  note_stream(t, stream);
   if (n > kStaticMaxIds || n_bags > kStaticMaxIds + 1 || t->view.dim > kStaticMaxDim) return MONO_ELIMIT;
   if (n == 0 || n_bags == 0) return MONO_OK;
   if (!d_rows || !d_offsets || !d_grad) return MONO_EINVAL;
@@ -355,6 +369,7 @@ int mono_apply_grad_adagrad_noalloc(mono_table* t, const int32_t* d_rows, uint64
 int mono_expire_sweep(mono_table* t, uint32_t now, uint64_t* d_n_expired, int64_t* d_expired_keys,
                       uint64_t max_expired, void* stream) {
   if (!t || now >= (1u << 24)) return MONO_EINVAL;
+  note_stream(t, stream);
   return launch_expire_sweep(t->view, now, d_n_expired, d_expired_keys, d_expired_keys ? max_expired : 0,
                              (hipStream_t)stream, &t->prof) == hipSuccess
              ? MONO_OK
@@ -421,6 +436,7 @@ int mono_export_touched(mono_table* t, int64_t* d_keys, int32_t* d_row, float* d
 int mono_table_import(mono_table* t, const int64_t* d_keys, const float* d_values, const float* d_acc,
                       const uint32_t* d_last_seen, uint64_t n, uint64_t* h_refused, void* stream) {
   if (!t || n > t->max_ids) return MONO_EINVAL;
+  note_stream(t, stream);
   if (h_refused) *h_refused = 0;
   if (n == 0) return MONO_OK;
   if (!d_keys || !d_values || !d_acc || !d_last_seen) return MONO_EINVAL;
@@ -447,6 +463,7 @@ int mono_table_import(mono_table* t, const int64_t* d_keys, const float* d_value
 
 int mono_filter_import(mono_table* t, const uint32_t* d_words, uint64_t first, uint64_t count, void* stream) {
   if (!t || first + count > t->view.n_filter || (count && !d_words)) return MONO_EINVAL;
+  note_stream(t, stream);
   return launch_filter_import(t->view, d_words, first, count, (hipStream_t)stream) == hipSuccess ? MONO_OK : MONO_EHIP;
 }
 
@@ -461,6 +478,7 @@ int mono_table_migrate(mono_table* dst, mono_table* src, uint32_t generation, vo
       b.n_filter / a.n_filter != b.capacity / a.capacity)  // the counter array grows with the table (powers of two)
     return MONO_EINVAL;  // dst must be a fresh table with the same parameters
   hipStream_t s = (hipStream_t)stream;
+  note_stream(dst, stream);
   Control c;
   if (hipMemcpyAsync(&c, a.ctl, sizeof(Control), hipMemcpyDeviceToHost, s) != hipSuccess ||
       hipStreamSynchronize(s) != hipSuccess)
