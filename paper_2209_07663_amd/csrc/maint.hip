@@ -39,66 +39,69 @@ __global__ void sweep_begin_kernel(TableView t, uint32_t now, int64_t* expired_k
   c->scratch[kSweepRemoved] = removed;
 }
 
-// A wave owns 512 consecutive slots = 64 buckets = one word of the occupancy bitmap; a lane looks at one
-// slot of eight of those buckets (eight independent 8-byte loads, the eight lanes of a group covering a
-// bucket's meta words as one 64-byte access), and only at buckets whose bit is set: a sweep over a
-// sparsely filled table reads the bitmap and little else.  A bucket found empty gets its bit cleared.
-__global__ __launch_bounds__(256) void sweep_find_kernel(TableView t, uint32_t now) {
-  __shared__ uint32_t wave_cnt[4];
-  __shared__ uint32_t block_base;
-  const uint64_t wave_global = ((uint64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+// A wave looks at 512 consecutive slots = 64 buckets = one word of the occupancy bitmap at a time; a lane
+// looks at one slot of eight of those buckets (eight independent 8-byte loads, the eight lanes of a group
+// covering a bucket's meta words as one 64-byte access), and only at buckets whose bit is set: a sweep
+// over a sparsely filled table reads the bitmap and little else.  A bucket found empty gets its bit
+// cleared.  A wave walks `iters` consecutive words (a large table would otherwise need 10^5 blocks that do
+// next to nothing each) and asks for all of them at once, one per lane.  Waves never wait for each other:
+// a wave that found expired slots reserves its room in a sub-list with one atomic of its own.
+constexpr uint32_t kSweepMaxIters = 64;
+__global__ __launch_bounds__(256) void sweep_find_kernel(TableView t, uint32_t now, uint32_t iters) {
   const uint32_t lane = lane_id(), grp = lane >> 3, l8 = lane & 7;
-  const uint64_t slot0 = wave_global * 512;
+  const uint64_t n_words = occupancy_words(t.capacity);
+  const uint64_t word0 = (((uint64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6) * iters;
+  if (word0 >= n_words) return;  // wave-uniform
   // a table that is at least a quarter full has hardly an empty bucket: its sweep does not wait for the
-  // bitmap word before it asks for the buckets (and leaves the bitmap alone)
+  // bitmap words before it asks for the buckets (and leaves the bitmap alone)
   const int32_t free_n = t.ctl->free_n;
   const bool dense = ((uint64_t)t.capacity - (uint64_t)(free_n < 0 ? 0 : free_n)) * 4 > t.capacity;
-  unsigned long long bits = 0;
-  if (slot0 < t.capacity) bits = dense ? ~0ull : t.occupied[wave_global];
-  unsigned long long m[kSweepSlotsPerThread];
+  unsigned long long mine = 0;  // lane i: the bitmap word of the wave's i-th turn
+  if (lane < iters && word0 + lane < n_words) mine = dense ? ~0ull : t.occupied[word0 + lane];
+#pragma unroll 1
+  for (uint32_t i = 0; i < iters; ++i) {
+    const unsigned long long bits = __shfl(mine, (int)i);
+    if (bits == 0) continue;  // wave-uniform: no bucket of these 64 holds anything (or past the end)
+    const uint64_t word = word0 + i;
+    const uint64_t slot0 = word * 512;
+    unsigned long long m[kSweepSlotsPerThread];
 #pragma unroll
-  for (int s = 0; s < kSweepSlotsPerThread; ++s) {
-    const uint32_t bucket_here = 8u * (uint32_t)s + grp;
-    const uint64_t slot = slot0 + (uint64_t)bucket_here * 8 + l8;
-    m[s] = kNoMeta;
-    if (((bits >> bucket_here) & 1ull) && slot < t.capacity) m[s] = t.buckets[slot >> 3].meta[l8];
-  }
-  uint64_t found[kSweepSlotsPerThread];
-  unsigned long long now_empty = 0;  // buckets of this wave that are flagged but hold nothing
-  uint32_t wave_total = 0;
-#pragma unroll
-  for (int s = 0; s < kSweepSlotsPerThread; ++s) {
-    const bool live = meta_row(m[s]) != kNoRow;
-    const uint64_t live_mask = __ballot(live);
-    const uint32_t bucket_here = 8u * (uint32_t)s + grp;
-    if (!dense && ((bits >> bucket_here) & 1ull) && ((live_mask >> (8 * grp)) & 0xFFull) == 0)
-      now_empty |= 1ull << bucket_here;
-    found[s] = __ballot(live && is_expired(t, now, meta_seen(m[s])));
-    wave_total += (uint32_t)__popcll(found[s]);
-  }
-  // every lane of a group computed the same verdict for its eight buckets: one lane per group clears
-#pragma unroll
-  for (int d = 8; d < 64; d <<= 1) now_empty |= __shfl_xor(now_empty, d);
-  if (lane == 0 && now_empty) atomicAnd(&t.occupied[wave_global], ~now_empty);
-  const uint32_t wave = threadIdx.x >> 6;
-  if (lane == 0) wave_cnt[wave] = wave_total;
-  __syncthreads();
-  const uint32_t list = blockIdx.x & (kWinLists - 1);
-  if (threadIdx.x == 0) {
-    const uint32_t total = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
-    block_base = total ? atomicAdd(&t.sweep_cnt[list * kWinStride], total) : 0u;
-  }
-  __syncthreads();
-  if (wave_total == 0) return;  // wave-uniform
-  uint32_t p = block_base;
-  for (uint32_t w = 0; w < wave; ++w) p += wave_cnt[w];
-#pragma unroll
-  for (int s = 0; s < kSweepSlotsPerThread; ++s) {
-    if ((found[s] >> lane) & 1ull) {
-      const uint64_t slot = slot0 + (uint64_t)(8u * (uint32_t)s + grp) * 8 + l8;
-      t.sweep_list[(uint64_t)list * t.sweep_cap + p + (uint32_t)__popcll(found[s] & lanes_below())] = (uint32_t)slot;
+    for (int s = 0; s < kSweepSlotsPerThread; ++s) {
+      const uint32_t bucket_here = 8u * (uint32_t)s + grp;
+      const uint64_t slot = slot0 + (uint64_t)bucket_here * 8 + l8;
+      m[s] = kNoMeta;
+      if (((bits >> bucket_here) & 1ull) && slot < t.capacity) m[s] = t.buckets[slot >> 3].meta[l8];
     }
-    p += (uint32_t)__popcll(found[s]);
+    uint64_t found[kSweepSlotsPerThread];
+    unsigned long long now_empty = 0;  // buckets of this word that are flagged but hold nothing
+    uint32_t total = 0;
+#pragma unroll
+    for (int s = 0; s < kSweepSlotsPerThread; ++s) {
+      const bool live = meta_row(m[s]) != kNoRow;
+      const uint64_t live_mask = __ballot(live);
+      const uint32_t bucket_here = 8u * (uint32_t)s + grp;
+      if (!dense && ((bits >> bucket_here) & 1ull) && ((live_mask >> (8 * grp)) & 0xFFull) == 0)
+        now_empty |= 1ull << bucket_here;
+      found[s] = __ballot(live && is_expired(t, now, meta_seen(m[s])));
+      total += (uint32_t)__popcll(found[s]);
+    }
+    // every lane of a group computed the same verdict for its eight buckets: one lane clears for the wave
+#pragma unroll
+    for (int d = 8; d < 64; d <<= 1) now_empty |= __shfl_xor(now_empty, d);
+    if (lane == 0 && now_empty) atomicAnd(&t.occupied[word], ~now_empty);
+    if (total == 0) continue;  // wave-uniform
+    const uint32_t list = (uint32_t)(word >> 2) & (kWinLists - 1);  // (the list of the 2048-slot chunk the word lies in)
+    uint32_t p = 0;
+    if (lane == 0) p = atomicAdd(&t.sweep_cnt[list * kWinStride], total);
+    p = __shfl(p, 0);
+#pragma unroll
+    for (int s = 0; s < kSweepSlotsPerThread; ++s) {
+      if ((found[s] >> lane) & 1ull) {
+        const uint64_t slot = slot0 + (uint64_t)(8u * (uint32_t)s + grp) * 8 + l8;
+        t.sweep_list[(uint64_t)list * t.sweep_cap + p + (uint32_t)__popcll(found[s] & lanes_below())] = (uint32_t)slot;
+      }
+      p += (uint32_t)__popcll(found[s]);
+    }
   }
 }
 
@@ -164,8 +167,12 @@ hipError_t launch_expire_sweep(const TableView& t, uint32_t now, uint64_t* d_n_e
     return hipGetLastError();
   }
   MONO_LAUNCH(prof, K_SWEEP_BEGIN, stream, sweep_begin_kernel, dim3(1), dim3(64), t, now, d_expired_keys, max_expired);
-  const dim3 block(256), grid((unsigned)((t.capacity + kSweepSlotsPerBlock - 1) / kSweepSlotsPerBlock));
-  MONO_LAUNCH(prof, K_SWEEP, stream, sweep_find_kernel, grid, block, t, now);
+  const uint64_t words = occupancy_words(t.capacity);
+  uint64_t iters = (words + 32767) / 32768;  // about 32 K waves, at most kSweepMaxIters bitmap words each
+  iters = iters < 1 ? 1 : (iters > kSweepMaxIters ? kSweepMaxIters : iters);
+  const uint64_t waves = (words + iters - 1) / iters;
+  const dim3 block(256), grid((unsigned)((waves + 3) / 4));
+  MONO_LAUNCH(prof, K_SWEEP, stream, sweep_find_kernel, grid, block, t, now, (uint32_t)iters);
   MONO_LAUNCH(prof, K_SWEEP_REMOVE, stream, sweep_remove_kernel, dim3(grid.x < 2048u ? grid.x : 2048u), block, t,
               d_expired_keys, max_expired);
   MONO_LAUNCH(prof, K_SWEEP_END, stream, sweep_end_kernel, dim3(1), dim3(64), t, d_n_expired);
