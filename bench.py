@@ -129,7 +129,7 @@ def algorithmic_bytes(kernel, s, wl):
     if kernel == "seg_reduce":
         return 4 * wl.dim * nb + 2 * row * s["u_present"] + 8 * s["u_present"]
     if kernel == "sweep_find":
-        return 4 * wl.capacity
+        return 4 * s.get("size", wl.capacity)   # the last-seen word of every STORED key (see step_bytes)
     return 0   # expand_bags and the sort kernels move scratch only: no compulsory bytes
 
 
@@ -138,7 +138,9 @@ def step_bytes(s, wl, sweep_every, bucket_bytes=KEY_LINE):
     line per distinct stored key and two per distinct missing key (a miss must look at both buckets), the
     counter sector of a distinct missing key read and written, the stamp, every distinct row read once (and
     written once if new), the pooled output; backward: the pooled gradients, every distinct row read and
-    written, its accumulator read and written; sweep: the last-seen word of every slot and the removed keys.
+    written, its accumulator read and written; sweep: the last-seen word of every STORED key and the removed
+    keys (4 bytes per slot of the whole table would be the figure for a sweep that cannot skip empty buckets;
+    this library's can, so counting every slot would credit it with bytes it never has to move).
     bucket_bytes = 64: the eight keys of a bucket; 128: the bucket line as this library stores it."""
     e = 2 if wl.bf16 else 4
     row = wl.dim * e
@@ -146,7 +148,7 @@ def step_bytes(s, wl, sweep_every, bucket_bytes=KEY_LINE):
     fwd = (8 * n + 8 * (nb + 1) + bucket_bytes * (s["u_hit"] + 2 * s["u_miss"]) + 2 * SECTOR * s["u_miss"]
            + 4 * s["u_present"] + row * s["u_present"] + row * s["u_new"] + 4 * wl.dim * nb)
     bwd = 4 * wl.dim * nb + 2 * row * s["u_present"] + 8 * s["u_present"]
-    sweep = (4 * wl.capacity / sweep_every + 8 * s.get("n_expired", 0)) if wl.expire_steps else 0
+    sweep = (4 * s.get("size", wl.capacity) / sweep_every + 8 * s.get("n_expired", 0)) if wl.expire_steps else 0
     return fwd + bwd + sweep
 
 
@@ -382,9 +384,9 @@ def main():
     pooled = torch.empty((wl.n_bags, wl.dim), dtype=torch.float32, device=dev)
     n_exp = torch.zeros(1, dtype=torch.int64, device=dev)
 
-    # expiry sweep: every step (configs[3] asks for it); configs[4] leaves the cadence open and a sweep
-    # of its 2^28 slots costs about as much as the rest of its step, so there it runs every 10th step
-    sweep_every = 10 if wl.name == "cfg5" else 1
+    # expiry sweep: every step (configs[3] asks for it; configs[4] leaves the cadence open, and a sweep of its
+    # sparsely filled 2^28 slots costs a tenth of its step)
+    sweep_every = 1
 
     def run_step(b):
         r = rows[: b["n"]]
@@ -439,7 +441,8 @@ def main():
         # miss occurrences = occurrences of keys absent before the call: absent now, or admitted in this call
         u_hit = u_present - u_new
         one = {"n": b["n"], "n_bags": wl.n_bags, "u": u_all, "u_present": u_present, "u_new": u_new,
-               "u_hit": u_hit, "u_miss": u_all - u_hit, "n_miss": int((~present).sum().item()), "n_expired": 0}
+               "u_hit": u_hit, "u_miss": u_all - u_hit, "n_miss": int((~present).sum().item()), "n_expired": 0,
+               "size": tab.mono_table_stats()["size"]}
         tab.mono_gather_pool(r, b["offsets"], pooled)
         tab.mono_apply_grad_adagrad(r, b["offsets"], b["grad"], wl.lr, wl.eps)
         if b["step"] % sweep_every == sweep_every - 1:

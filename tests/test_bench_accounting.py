@@ -10,7 +10,7 @@ bench = importlib.util.module_from_spec(_spec)
 _spec.loader.exec_module(bench)
 
 STATS = {"n": 1000, "n_bags": 250, "u": 400, "u_present": 150, "u_new": 50, "u_hit": 100, "u_miss": 300, "n_miss": 600,
-         "n_expired": 7}
+         "n_expired": 7, "size": 9000}
 
 
 def test_kernel_bytes_no_expiry_fp32_dim32():
@@ -32,15 +32,15 @@ def test_kernel_bytes_with_expiry_bf16_dim64():
     wl = synth.CONFIGS["cfg5"]                       # dim 64 bf16 -> 128-byte rows, counters age
     S = 32
     assert bench.algorithmic_bytes("probe_count", STATS, wl) == 12 * 1000 + (128 + 4) * 100 + (256 + 2 * S) * 300
-    assert bench.algorithmic_bytes("sweep_find", STATS, wl) == 4 * wl.capacity
+    assert bench.algorithmic_bytes("sweep_find", STATS, wl) == 4 * 9000          # per STORED key, not per slot
     assert bench.algorithmic_bytes("seg_reduce", STATS, wl) == 4 * 64 * 250 + 2 * 128 * 150 + 8 * 150
 
 
 def test_step_bytes():
     """Whole step: keys, offsets, L bytes of bucket per distinct stored key and 2 L per distinct missing key,
     the counter sector of a missing key read and written, stamp, distinct rows, new rows, pooled output;
-    backward: pooled gradients, distinct rows read and written, their state; sweep: 4 bytes per slot per
-    sweep plus 8 per removed key."""
+    backward: pooled gradients, distinct rows read and written, their state; sweep: 4 bytes per stored key
+    per sweep plus 8 per removed key."""
     S = 32
     wl = synth.CONFIGS["cfg2"]
     for L in (64, 128):
@@ -52,7 +52,7 @@ def test_step_bytes():
     wl5 = synth.CONFIGS["cfg5"]
     fwd5 = 8 * 1000 + 8 * 251 + 64 * 700 + 2 * S * 300 + 4 * 150 + 128 * 150 + 128 * 50 + 4 * 64 * 250
     bwd5 = 4 * 64 * 250 + 2 * 128 * 150 + 8 * 150
-    assert bench.step_bytes(STATS, wl5, 10) == fwd5 + bwd5 + 4 * wl5.capacity / 10 + 8 * 7
+    assert bench.step_bytes(STATS, wl5, 10) == fwd5 + bwd5 + 4 * 9000 / 10 + 8 * 7
 
 
 def test_profile_traffic_is_labelled():
