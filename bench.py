@@ -130,7 +130,7 @@ def algorithmic_bytes(kernel, s, wl):
         return 4 * wl.dim * nb + 2 * row * s["u_present"] + 8 * s["u_present"]
     if kernel == "sweep_find":
         return 4 * s.get("size", wl.capacity)   # the last-seen word of every STORED key (see step_bytes)
-    return 0   # expand_bags and the sort kernels move scratch only: no compulsory bytes
+    return 0   # the sort kernels and combine move scratch only: no compulsory bytes
 
 
 def step_bytes(s, wl, sweep_every, bucket_bytes=KEY_LINE):

@@ -8,7 +8,7 @@ namespace mono {
 
 // Per-call scratch for the update path, carved out of the table's arena.
 struct UpdateWorkspace {
-  uint32_t* bag_of;     // [max_ids]: first [sort_units] words: the bag that holds each sort unit's first occurrence
+  uint32_t* unit_bag;   // [max_ids]: first [sort_units] words: the bag that holds each sort unit's first occurrence
                         // (a restore call borrows the whole array for its per-record results)
   uint2* pair_a;        // [max_ids] (row, bag) pairs, ping
   uint2* pair_b;        // [max_ids] pong

@@ -322,11 +322,11 @@ hipError_t launch_sort_pairs(const TableView& t, const UpdateWorkspace& ws, cons
     const uint2* src = p % 2 == 0 ? ws.pair_a : ws.pair_b;
     uint2* dst = p % 2 == 0 ? ws.pair_b : ws.pair_a;
     MONO_LAUNCH(prof, K_SORT_HIST, stream, sort_hist_kernel, grid, block, t.ctl, p, d_rows, src, n, units, ws.hist,
-                d_offsets, n_bags, ws.bag_of);
+                d_offsets, n_bags, ws.unit_bag);
     MONO_LAUNCH(prof, K_SORT_SCAN, stream, sort_scan_kernel, dim3(kSortMaxBins), dim3(256), t.ctl, p, ws.hist, units,
                 totals);
     MONO_LAUNCH(prof, K_SORT_SCATTER, stream, sort_scatter_kernel, grid, block, t.ctl, p, d_rows, d_offsets, n_bags,
-                ws.bag_of, src, n, units, ws.hist, totals, dst);
+                ws.unit_bag, src, n, units, ws.hist, totals, dst);
   }
   return hipGetLastError();
 }

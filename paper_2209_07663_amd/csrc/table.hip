@@ -107,7 +107,7 @@ size_t layout(mono_table* t, char* base, uint64_t capacity, uint32_t dim, uint32
   char* sweep_list = take(kWinLists * sweep_cap * sizeof(uint32_t));
   char* sweep_cnt = take(kWinLists * kWinStride * sizeof(uint32_t));
   const uint64_t tiles = reduce_tiles(max_ids);
-  char* bag_of = take(max_ids * 4);
+  char* unit_bag = take(max_ids * 4);
   char* pair_a = take(max_ids * sizeof(uint2));
   char* pair_b = take(max_ids * sizeof(uint2));
   char* hist = take(sort_hist_words(max_ids) * 4);
@@ -132,7 +132,7 @@ size_t layout(mono_table* t, char* base, uint64_t capacity, uint32_t dim, uint32
     v.sweep_list = (uint32_t*)sweep_list;
     v.sweep_cnt = (uint32_t*)sweep_cnt;
     v.sweep_cap = sweep_cap;
-    t->ws.bag_of = (uint32_t*)bag_of;
+    t->ws.unit_bag = (uint32_t*)unit_bag;
     t->ws.pair_a = (uint2*)pair_a;
     t->ws.pair_b = (uint2*)pair_b;
     t->ws.hist = (uint32_t*)hist;
@@ -172,7 +172,7 @@ hipError_t static_workspace(int device, uint32_t dim, UpdateWorkspace* ws) {
     return p;
   };
   const uint64_t tiles = reduce_tiles(kStaticMaxIds);
-  ws->bag_of = (uint32_t*)take(kStaticMaxIds * 4);
+  ws->unit_bag = (uint32_t*)take(kStaticMaxIds * 4);
   ws->pair_a = (uint2*)take(kStaticMaxIds * sizeof(uint2));
   ws->pair_b = (uint2*)take(kStaticMaxIds * sizeof(uint2));
   ws->hist = (uint32_t*)take(sort_hist_words(kStaticMaxIds) * 4);
@@ -449,7 +449,7 @@ int mono_table_import(mono_table* t, const int64_t* d_keys, const float* d_value
     return MONO_EHIP;
   const RestoreSource src = {d_values, d_acc, d_last_seen};
   // the per-occurrence result array of the four kernels lives in the update workspace (max_ids words)
-  if (launch_lookup_or_insert(t->view, d_keys, n, 0, t->epoch, (int32_t*)t->ws.bag_of, src, s, &t->prof) != hipSuccess)
+  if (launch_lookup_or_insert(t->view, d_keys, n, 0, t->epoch, (int32_t*)t->ws.unit_bag, src, s, &t->prof) != hipSuccess)
     return MONO_EHIP;
   if (h_refused) {
     unsigned long long r = 0;
