@@ -262,6 +262,27 @@ def test_edge_cases(dev):
     tab.close()
 
 
+def test_long_stretches_of_empty_bags(dev):
+    """The update finds the bag of every occurrence from the offsets, a sort unit at a time, starting at the
+    bag that holds the unit's first occurrence: thousands of empty bags before the first ID, between two
+    IDs of one sort unit, across unit borders and after the last ID must not shift a single gradient."""
+    from paper_2209_07663_amd.binding import Table
+    seed, dim = 47, 8
+    tab = Table(1 << 14, dim, seed, freq_threshold=1, max_ids=1 << 16, max_bags=1 << 16, device=dev)
+    orc = Oracle(1 << 14, dim, seed, 1, 0, False, kind="cuckoo")
+    rng = np.random.default_rng(11)
+    lens = np.concatenate([np.zeros(5000), rng.integers(1, 6, 300), np.zeros(7000), [1], np.zeros(3000), [2500],
+                           np.zeros(1200), rng.integers(0, 3, 2000), np.zeros(9000)]).astype(np.int64)
+    offs_h = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    keys_h = rng.integers(0, 900, size=int(offs_h[-1])).astype(np.int64)
+    grad_h = rng.standard_normal((lens.shape[0], dim)).astype(np.float32)
+    assert offs_h[-1] > 4096                               # several sort units
+    for step in range(2):
+        compare_step(tab, orc, {"keys": keys_h, "offsets": offs_h, "grad": grad_h, "step": step}, dev, RTOL_F32,
+                     exact_rows=False, train=True)
+    tab.close()
+
+
 def test_sweeps_of_a_sparse_table_find_keys_that_come_back_to_emptied_buckets(dev):
     """A sweep only looks at buckets that a bitmap does not prove empty.  Keys are admitted into a large,
     almost empty table, expire (their buckets empty out), a later sweep notes those buckets as empty, the
@@ -381,13 +402,13 @@ def test_update_at_the_sort_width_boundaries(dev, stored):
     tab.close()
 
 
-@pytest.mark.parametrize("case", range(12))
+@pytest.mark.parametrize("case", range(20))
 def test_seeded_random_configurations(dev, case):
     """Combinations that no named configuration covers: a seeded draw of dim, storage type, threshold,
     expiry, number of counter hashes, counter array size, bag lengths, key skew and padding keys."""
     from paper_2209_07663_amd.binding import Table
     rng = np.random.default_rng(1000 + case)
-    dim = int(rng.choice([4, 8, 12, 32, 64, 100, 256, 512]))
+    dim = int(rng.choice([4, 8, 12, 32, 64, 100, 256, 512, 768, 1024]))
     bf16 = bool(rng.integers(0, 2))
     thr = int(rng.choice([0, 1, 2, 3, 7]))
     expire = int(rng.choice([0, 0, 2, 5]))

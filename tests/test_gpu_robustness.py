@@ -93,6 +93,38 @@ def test_overfull_table_loses_nothing_and_recovers(dev):
     tab.close()
 
 
+def test_restore_calls_at_the_fill_limit_place_all_their_records_or_none(dev):
+    from paper_2209_07663_amd.binding import Table
+    seed, cap, dim = 23, 1 << 10, 4
+    limit = cap - cap // 32
+    tab = Table(cap, dim, seed, freq_threshold=2, max_ids=4096, max_bags=4096, device=dev)
+    orc = Oracle(cap, dim, seed, 2, 0, False, kind="cuckoo")
+    rng = np.random.default_rng(6)
+    keys = (rng.permutation(1 << 20)[:limit + 10].astype(np.int64) + 1) * 7919
+
+    def restore(k):
+        vals = rng.standard_normal((k.shape[0], dim)).astype(np.float32)
+        acc = rng.random(k.shape[0]).astype(np.float32)
+        seen = np.zeros(k.shape[0], dtype=np.uint32)
+        to_dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+        got = tab.mono_table_import(to_dev(k), to_dev(vals), to_dev(acc), to_dev(seen.view(np.int32)))
+        want = orc.import_entries(k, vals, acc, seen)
+        assert got == want
+        return got
+
+    assert restore(keys[:limit - 2]) == 0                       # two rows of room left
+    assert restore(keys[limit - 2:limit + 3]) == 5              # five new keys: none is placed
+    assert restore(np.concatenate([keys[:3], keys[limit - 2:limit]])) == 3    # three stored keys refused, two new ones fit
+    assert restore(keys[limit:limit + 1]) == 1                  # full
+    st = tab.mono_table_stats()
+    assert st["size"] == limit and st["n_full"] == orc.refused_full == 6
+    d = tab.mono_table_export()
+    tc.check_placement(d, cap, 8, seed)
+    tc.assert_same_table(d, orc.dump(), exact_rows=True)
+    assert (tab.mono_filter_export() == orc.filter_words()).all()   # restored keys count as seen twice
+    tab.close()
+
+
 def test_calls_on_a_side_stream(dev):
     """Every call takes the stream it is given: a whole run on a non-default stream matches the oracle."""
     from paper_2209_07663_amd.binding import Table
