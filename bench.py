@@ -42,9 +42,9 @@ BUCKET_LINE = 128       # bytes of a bucket as this library stores it (keys + ro
 # profiled command, together with the name of the summary it comes from; otherwise `traffic` is null.
 TRAFFIC_FROM_PROFILE = {
     "cfg2": {"profile": "profiles/bench_cfg2_full_step.md", "fill_load": 0.5,
-             "step": 3705.2e6,
-             "kernels": {"probe_count": 976.4e6, "seg_reduce": 1130.2e6, "gather_pool": 548.2e6,
-                         "admit_elect": 280.6e6, "sort_scatter": 140.4e6, "sort_hist": 73.3e6, "insert": 79.2e6}},
+             "step": 3713.1e6,
+             "kernels": {"probe_count": 976.5e6, "seg_reduce": 1130.3e6, "gather_pool": 548.7e6,
+                         "admit_elect": 280.6e6, "sort_scatter": 140.3e6, "sort_hist": 72.9e6, "insert": 87.7e6}},
 }
 
 
