@@ -51,7 +51,8 @@ typedef struct mono_stats {
   uint64_t n_admitted;      /* keys admitted since creation */
   uint64_t n_expired;       /* keys removed by expire_sweep since creation */
   uint64_t n_insert_failed; /* eviction chains that hit the kick bound (element went to the stash) */
-  uint64_t n_lost;          /* elements dropped because the stash was full too (must stay 0) */
+  uint64_t n_lost;          /* elements dropped because the stash was full too, or updates skipped because the
+                               library's own bound on the rows in use was wrong (must stay 0) */
   uint64_t n_full;          /* admissible keys refused because their call would have passed the fill limit (see capacity) */
   uint64_t stash_size;      /* elements currently in the stash */
   uint64_t max_chain;       /* longest eviction chain seen */

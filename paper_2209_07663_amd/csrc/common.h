@@ -104,6 +104,8 @@ struct TableView {
   uint32_t bf16;
   uint32_t filter_hashes;    // counters per key (1..4); the key's count is their minimum
   uint32_t sync_epoch;       // current synchronisation window (>= 1); rows with touch == sync_epoch are "touched"
+  unsigned long long* hwm_mail;  // pinned HOST word (or null): every lookup_or_insert leaves (its call tag << 32 | hwm)
+                                 // there, so that the host can bound the sort's key width without waiting
 };
 
 __host__ __device__ inline uint64_t mix64(uint64_t z) {

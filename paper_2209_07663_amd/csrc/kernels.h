@@ -76,14 +76,18 @@ hipError_t launch_qr_gather_pool(const void* d_rem, const void* d_quot, uint32_t
                                  const int64_t* d_ids, uint64_t n, const int64_t* d_offsets, uint64_t n_bags,
                                  float* d_out, hipStream_t stream);
 
+// hwm_bound: a number the table's high-water mark of rows cannot exceed when the call runs (the capacity, or
+// less if the host knows better): it decides how many sort passes are launched.
 hipError_t launch_apply_grad_adagrad(const TableView& t, const UpdateWorkspace& ws, const int32_t* d_rows, uint64_t n,
                                      const int64_t* d_offsets, uint64_t n_bags, const float* d_grad, float lr, float eps,
-                                     hipStream_t stream, Profiler* prof);
+                                     uint32_t hwm_bound, hipStream_t stream, Profiler* prof);
 
 // Stable LSD radix sort of the (row, bag) pairs of a batch; the result is in pair_b if the plan for
-// the device's high-water mark has an odd number of passes, else in pair_a.
+// the device's high-water mark has an odd number of passes, else in pair_a.  Returns through *launched how many
+// passes were queued (those the plan for hwm_bound needs).
 hipError_t launch_sort_pairs(const TableView& t, const UpdateWorkspace& ws, const int32_t* d_rows, uint64_t n,
-                             const int64_t* d_offsets, uint64_t n_bags, hipStream_t stream, Profiler* prof);
+                             const int64_t* d_offsets, uint64_t n_bags, uint32_t hwm_bound, uint32_t* launched,
+                             hipStream_t stream, Profiler* prof);
 
 hipError_t launch_expire_sweep(const TableView& t, uint32_t now, uint64_t* d_n_expired, int64_t* d_expired_keys,
                                uint64_t max_expired, hipStream_t stream, Profiler* prof);

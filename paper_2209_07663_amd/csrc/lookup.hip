@@ -497,7 +497,7 @@ __global__ __launch_bounds__(256) void insert_kernel(TableView t, uint32_t step,
   }
 }
 
-__global__ __launch_bounds__(256) void resolve_kernel(TableView t, uint64_t n, int32_t* rows_out) {
+__global__ __launch_bounds__(256) void resolve_kernel(TableView t, uint64_t n, int32_t* rows_out, uint32_t epoch) {
   const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) {
     const int32_t v = rows_out[i];
@@ -515,6 +515,9 @@ __global__ __launch_bounds__(256) void resolve_kernel(TableView t, uint64_t n, i
     t.ctl->free_n = free0 - (int32_t)got;
     const uint32_t in_use = (uint32_t)t.capacity - (uint32_t)(free0 - (int32_t)got);
     if (in_use > t.ctl->hwm) t.ctl->hwm = in_use;  // rows are handed out in ascending order
+    if (t.hwm_mail)  // the host reads this word when it pleases; the mark only ever grows, so a stale value is a safe one
+      __hip_atomic_store(t.hwm_mail, ((unsigned long long)epoch << 32) | (unsigned long long)t.ctl->hwm, __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_SYSTEM);
     t.ctl->n_admitted += got;
     t.ctl->n_full += total - got;
   }
@@ -546,7 +549,7 @@ hipError_t launch_lookup_or_insert(const TableView& t, const int64_t* d_keys, ui
     MONO_LAUNCH(prof, K_INSERT, stream, insert_kernel<uint16_t>, igrid, block, t, step, d_rows_out, src);
   else
     MONO_LAUNCH(prof, K_INSERT, stream, insert_kernel<float>, igrid, block, t, step, d_rows_out, src);
-  MONO_LAUNCH(prof, K_RESOLVE, stream, resolve_kernel, grid, block, t, n, d_rows_out);
+  MONO_LAUNCH(prof, K_RESOLVE, stream, resolve_kernel, grid, block, t, n, d_rows_out, epoch);
   if (restore) hipLaunchKernelGGL(count_refused_kernel, grid, block, 0, stream, t, n, d_rows_out);
   return hipGetLastError();
 }

@@ -4,8 +4,9 @@
 // The key width is decided ON THE DEVICE: row indices are handed out in ascending order, so every
 // row in use is below the high-water mark `hwm` kept in the control block.  bit_length(hwm - 1)
 // bits are sorted in the fewest passes of at most kSortMaxBits bits, of equal width (eight bits or fewer
-// up to 16 M rows: a block's share of a bin is then long enough to leave as whole lines); the host launches the worst-case number of passes
-// and the superfluous ones return at once.  Pass p reads buffer (p even ? a : b)
+// up to 16 M rows: a block's share of a bin is then long enough to leave as whole lines); the host launches the
+// passes that an upper bound of `hwm` needs (it keeps one without waiting for the device: see the table's
+// host side) and the superfluous ones return at once.  Pass p reads buffer (p even ? a : b)
 // and writes the other one.  Pass 0 reads the row indices as the caller holds them and finds the bag
 // of every occurrence from the offsets (no array of bag numbers is ever written to memory); dropped
 // occurrences (row -1) are left out by it, and it publishes the number of pairs that remain
@@ -312,11 +313,15 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
 }
 
 hipError_t launch_sort_pairs(const TableView& t, const UpdateWorkspace& ws, const int32_t* d_rows, uint64_t n,
-                             const int64_t* d_offsets, uint64_t n_bags, hipStream_t stream, Profiler* prof) {
+                             const int64_t* d_offsets, uint64_t n_bags, uint32_t hwm_bound, uint32_t* launched,
+                             hipStream_t stream, Profiler* prof) {
   if (n == 0) return hipSuccess;
   const uint64_t units = sort_units(n);
   uint32_t* totals = ws.hist + (uint64_t)kSortMaxBins * units;
-  const SortPlan worst = make_sort_plan((uint32_t)t.capacity);
+  // as many passes as the largest high-water mark the table can have by now needs (the device knows the
+  // real mark: passes beyond its plan return at once)
+  const SortPlan worst = make_sort_plan(hwm_bound < (uint32_t)t.capacity ? hwm_bound : (uint32_t)t.capacity);
+  if (launched) *launched = worst.passes;
   const dim3 block(kSortBlock), grid((unsigned)units);
   for (uint32_t p = 0; p < worst.passes; ++p) {
     const uint2* src = p % 2 == 0 ? ws.pair_a : ws.pair_b;

@@ -20,6 +20,14 @@ struct mono_table {
   int device = 0;
   hipStream_t last_stream = nullptr;  // stream of the latest call that queued work for this table
   bool used_stream = false;
+  // Bound on the device's high-water mark of rows, kept without waiting for the device: every
+  // lookup_or_insert leaves (its call tag << 32 | mark) in a pinned host word when it ends, and the host
+  // remembers how many keys each of its latest calls held (a call hands out at most one row per key).
+  unsigned long long* h_mail = nullptr;       // pinned; null: no bound is kept (the capacity is used)
+  static constexpr uint32_t kRecentCalls = 256;
+  uint32_t recent_tag[kRecentCalls] = {0};    // call tags, by tag % kRecentCalls (0 = unused)
+  uint64_t recent_n[kRecentCalls] = {0};      // keys of that call
+  bool tags_wrapped = false;                  // the 32-bit call tag has wrapped: the bound is given up
   Profiler prof;
 };
 
@@ -181,6 +189,29 @@ hipError_t static_workspace(int device, uint32_t dim, UpdateWorkspace* ws) {
   return hipSuccess;
 }
 
+void note_call(mono_table* t, uint32_t tag, uint64_t n) {
+  t->recent_tag[tag % mono_table::kRecentCalls] = tag;
+  t->recent_n[tag % mono_table::kRecentCalls] = n;
+}
+
+// A number that the table's high-water mark cannot exceed when work queued now runs: the mark that the
+// device reported last, plus the keys of every call queued after the one that reported it.  A stale report
+// only makes the bound larger (the mark never shrinks).
+uint32_t hwm_bound(const mono_table* t) {
+  const uint64_t capacity = t->view.capacity;
+  if (!t->h_mail || t->tags_wrapped) return (uint32_t)capacity;
+  const unsigned long long mail = *(volatile const unsigned long long*)t->h_mail;
+  const uint32_t tag = (uint32_t)(mail >> 32);
+  uint64_t bound = (uint32_t)mail;
+  if (t->epoch < tag || t->epoch - tag >= mono_table::kRecentCalls) return (uint32_t)capacity;
+  for (uint32_t c = tag + 1; c <= t->epoch && c != 0; ++c) {
+    if (t->recent_tag[c % mono_table::kRecentCalls] != c) return (uint32_t)capacity;  // not on record
+    bound += t->recent_n[c % mono_table::kRecentCalls];
+    if (bound >= capacity) return (uint32_t)capacity;
+  }
+  return (uint32_t)(bound < capacity ? bound : capacity);
+}
+
 void note_stream(mono_table* t, void* stream) {
   t->last_stream = (hipStream_t)stream;
   t->used_stream = true;
@@ -270,9 +301,24 @@ int mono_table_create_ex(mono_table** out, uint64_t capacity, uint32_t dim, uint
   v.sync_epoch = 1;
   t->max_ids = max_ids;
   t->max_bags = max_bags;
+  {  // (pinned host memory is allocated, never registered; without it the sort is simply sized for the capacity)
+    void* mail = nullptr;
+    void* mail_dev = nullptr;
+    if (hipHostMalloc(&mail, sizeof(unsigned long long), hipHostMallocMapped) == hipSuccess && mail &&
+        hipHostGetDevicePointer(&mail_dev, mail, 0) == hipSuccess && mail_dev) {
+      t->h_mail = (unsigned long long*)mail;
+      *t->h_mail = 0;  // call tag 0, mark 0: an empty table
+      v.hwm_mail = (unsigned long long*)mail_dev;
+    } else {
+      (void)hipGetLastError();
+      if (mail) (void)hipHostFree(mail);
+      v.hwm_mail = nullptr;
+    }
+  }
   note_stream(t, stream);
   if (launch_table_init(v, t->dset_size, (hipStream_t)stream) != hipSuccess) {
     if (t->owned_arena) (void)hipFree(t->owned_arena);
+    if (t->h_mail) (void)hipHostFree(t->h_mail);
     delete t;
     return MONO_EHIP;
   }
@@ -286,6 +332,7 @@ int mono_table_destroy(mono_table* t) {
   // the calls of a table go to one stream in order: waiting for the latest one is waiting for all of them
   if ((t->used_stream ? hipStreamSynchronize(t->last_stream) : hipDeviceSynchronize()) != hipSuccess) rc = MONO_EHIP;
   if (t->owned_arena && hipFree(t->owned_arena) != hipSuccess) rc = MONO_EHIP;
+  if (t->h_mail && hipHostFree(t->h_mail) != hipSuccess) rc = MONO_EHIP;
   for (auto& r : t->prof.recs) {  // timings nobody read
     (void)hipEventDestroy(r.start);
     (void)hipEventDestroy(r.stop);
@@ -305,12 +352,14 @@ int mono_lookup_or_insert(mono_table* t, const int64_t* d_keys, uint64_t n, uint
     if (hipMemsetAsync(t->view.dset, 0, t->dset_size * sizeof(unsigned long long), (hipStream_t)stream) != hipSuccess)
       return MONO_EHIP;
     epoch = 1;
+    t->tags_wrapped = true;
   }
   const RestoreSource none = {nullptr, nullptr, nullptr};
   if (launch_lookup_or_insert(t->view, d_keys, n, step, epoch, d_rows_out, none, (hipStream_t)stream, &t->prof) != hipSuccess)
     return MONO_EHIP;  // (the table's step and call tag move on only when the call was queued)
   t->epoch = epoch;
   t->last_step = step;
+  note_call(t, epoch, n);
   return MONO_OK;
 }
 
@@ -342,7 +391,7 @@ int mono_apply_grad_adagrad(mono_table* t, const int32_t* d_rows, uint64_t n, co
   note_stream(t, stream);
   if (n == 0 || n_bags == 0) return MONO_OK;
   if (!d_rows || !d_offsets || !d_grad) return MONO_EINVAL;
-  return launch_apply_grad_adagrad(t->view, t->ws, d_rows, n, d_offsets, n_bags, d_grad, lr, eps,
+  return launch_apply_grad_adagrad(t->view, t->ws, d_rows, n, d_offsets, n_bags, d_grad, lr, eps, hwm_bound(t),
                                    (hipStream_t)stream, &t->prof) == hipSuccess
              ? MONO_OK
              : MONO_EHIP;
@@ -360,8 +409,8 @@ int mono_apply_grad_adagrad_noalloc(mono_table* t, const int32_t* d_rows, uint64
   UpdateWorkspace ws;
   if (static_workspace(t->device, t->view.dim, &ws) != hipSuccess) return MONO_EHIP;
   // (no per-kernel events here: creating one may allocate)
-  return launch_apply_grad_adagrad(t->view, ws, d_rows, n, d_offsets, n_bags, d_grad, lr, eps, (hipStream_t)stream,
-                                   nullptr) == hipSuccess
+  return launch_apply_grad_adagrad(t->view, ws, d_rows, n, d_offsets, n_bags, d_grad, lr, eps, hwm_bound(t),
+                                   (hipStream_t)stream, nullptr) == hipSuccess
              ? MONO_OK
              : MONO_EHIP;
 }
@@ -382,6 +431,9 @@ int mono_table_stats(mono_table* t, mono_stats* h_out, void* stream) {
   if (hipMemcpyAsync(&c, t->view.ctl, sizeof(Control), hipMemcpyDeviceToHost, (hipStream_t)stream) != hipSuccess ||
       hipStreamSynchronize((hipStream_t)stream) != hipSuccess)
     return MONO_EHIP;
+  // (if that was the table's own stream, everything queued for the table has run: the mark just read is exact)
+  if (t->h_mail && !t->tags_wrapped && t->used_stream && (hipStream_t)stream == t->last_stream)
+    *t->h_mail = ((unsigned long long)t->epoch << 32) | (unsigned long long)c.hwm;
   h_out->capacity = t->view.capacity;
   h_out->size = t->view.capacity - (uint64_t)(c.free_n < 0 ? 0 : c.free_n);
   h_out->n_admitted = c.n_admitted;
@@ -444,7 +496,9 @@ int mono_table_import(mono_table* t, const int64_t* d_keys, const float* d_value
   if (++t->epoch == 0) {
     if (hipMemsetAsync(t->view.dset, 0, t->dset_size * sizeof(unsigned long long), s) != hipSuccess) return MONO_EHIP;
     t->epoch = 1;
+    t->tags_wrapped = true;
   }
+  note_call(t, t->epoch, n);
   if (hipMemsetAsync(&t->view.ctl->scratch[kRefusedRecords], 0, sizeof(unsigned long long), s) != hipSuccess)
     return MONO_EHIP;
   const RestoreSource src = {d_values, d_acc, d_last_seen};
@@ -489,6 +543,7 @@ int mono_table_migrate(mono_table* dst, mono_table* src, uint32_t generation, vo
   dst->generation = generation;
   dst->last_step = src->last_step;
   dst->epoch = 1;  // dst counts as used from here on (a second migration into it is refused)
+  if (dst->h_mail) *dst->h_mail = (1ull << 32) | (unsigned long long)c.hwm;  // rows keep their indices: so does the mark
   // rows and their state keep their indices: copied position for position up to the high-water mark
   const size_t esize = a.bf16 ? 2 : 4;
   if (c.hwm) {

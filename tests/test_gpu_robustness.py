@@ -223,3 +223,36 @@ def test_out_of_range_rows_and_offsets_are_bounded_by_the_kernels(dev):
     tc.rows_close(after["rows"], ref["rows"].astype(np.float64), RTOL_F32)
     tab.close()
     twin.close()
+
+
+def test_many_calls_queued_without_a_wait_then_updates(dev):
+    """The number of sort passes an update launches follows a bound on the rows in use that the host keeps
+    without waiting for the device (the device reports its mark after every lookup; the host adds the keys
+    of the calls queued since).  Hundreds of lookups and updates queued back to back, on a large table that
+    is almost empty (so that the bound, not the capacity, decides), with and without waits in between, must
+    train exactly like the oracle and never skip an update."""
+    from paper_2209_07663_amd.binding import Table
+    seed, dim, cap = 53, 4, 1 << 22                       # capacity needs three passes, the rows in use one or two
+    tab = Table(cap, dim, seed, freq_threshold=1, max_ids=4096, max_bags=4096, device=dev)
+    orc = Oracle(cap, dim, seed, 1, 0, False, kind="cuckoo")
+    rng = np.random.default_rng(19)
+    pending = []
+    for step in range(600):                               # more calls than the host keeps on record (256)
+        n = int(rng.integers(1, 300))
+        keys_h = rng.integers(0, 1 << 40, size=n).astype(np.int64) if step % 3 else rng.integers(0, 50, size=n).astype(np.int64)
+        offs_h = np.arange(n + 1, dtype=np.int64)
+        grad_h = rng.standard_normal((n, dim)).astype(np.float32)
+        keys, offs, grad = (torch.from_numpy(a).to(dev) for a in (keys_h, offs_h, grad_h))
+        rows = tab.mono_lookup_or_insert(keys, step)
+        tab.mono_apply_grad_adagrad(rows, offs, grad, 0.05, 1e-8)
+        pending.append((keys, offs, grad, rows))          # keep the buffers alive: nothing waits here
+        orc.lookup_or_insert(keys_h, step)
+        orc.apply_grad_adagrad(keys_h, offs_h, grad_h, 0.05, 1e-8)
+        if step in (40, 300, 301):                        # a wait now and then (the stats call refreshes the bound)
+            assert tab.mono_table_stats()["n_lost"] == 0
+            pending.clear()
+    st = tab.mono_table_stats()
+    assert st["n_lost"] == 0 and st["n_insert_failed"] == 0
+    assert 256 < st["size"] < 65536 * 2                   # crossed the one-pass / two-pass border on the way
+    tc.assert_same_table(tab.mono_table_export(), orc.dump(), exact_rows=False, rtol=1e-5)
+    tab.close()
