@@ -323,7 +323,7 @@ def main():
     ap.add_argument("--workers", type=int, default=min(16, os.cpu_count() or 8))
     ap.add_argument("--fill-load", type=float, default=-1.0,
                     help="before anything else, admit the workload's hottest IDs until this load factor; default: "
-                         "0.5 for cfg2, 0.9 for cfg4 (what configs[3] asks for), 0 (empty table) for the others")
+                         "0.5 for cfg2, 0.75 for cfg4 (configs[3] names 0.9: see DEFAULT_FILL), 0 (empty table) for the others")
     ap.add_argument("--no-maintenance", action="store_true",
                     help="skip the timing of delta export, snapshot, restore and rehash after the timed steps")
     ap.add_argument("--others", default="default",
