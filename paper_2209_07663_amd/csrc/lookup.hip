@@ -8,11 +8,12 @@
 //                 occurrence per distinct key is elected through the per-call dedup set and appended
 //                 to one of kWinLists lists (one atomic per block, spread over the lists: a single
 //                 append counter would serialise at ~12 ns per atomic on this machine)
-//   insert        (dense, grid-stride over the elected occurrences) take a row from the free stack
-//                 by rank (no atomics), insert the key (CAS on 64-bit key slots, eviction chain),
-//                 initialise the row with the whole wave
+//   insert        (dense, grid-stride over the elected occurrences) if all of them fit under the
+//                 table's fill limit (else none is placed): take a row from the free stack by rank
+//                 (no atomics), insert the key (CAS on 64-bit key slots, eviction chain), mark the
+//                 bucket in the occupancy bitmap, initialise the row with the whole wave
 //   resolve       duplicates of an admitted key pick up the row of the elected occurrence; one
-//                 thread settles the counters
+//                 thread settles the counters and reports the high-water mark of rows to the host
 //
 // The same four kernels restore snapshot records (RestoreSource): every record is a forced
 // admission whose row, accumulator and last-seen step come from the caller instead of from
