@@ -155,11 +155,25 @@ __global__ __launch_bounds__(kProbeBlock) void probe_count_kernel(TableView t, c
     maybe = cnt >= (t.freq_threshold > 1u ? t.freq_threshold : 1u);
   }
   const uint64_t b0 = bucket_index(t, 0, k), b1 = bucket_index(t, 1, k);
+  // Where counters age nothing above could prove a key absent.  On a sparsely filled table (less than a
+  // quarter full) the occupancy bitmap, which is small enough to stay in the caches, often proves a bucket
+  // empty: such a bucket is not read.  (Where the counters do the proving, the bitmap would only add a
+  // dependent access: measured, 4 % on the step.)
+  bool look0 = maybe, look1 = maybe;
+  if (t.expire_steps != 0) {
+    const int32_t free_n = t.ctl->free_n;
+    const bool sparse = ((uint64_t)t.capacity - (uint64_t)(free_n < 0 ? 0 : free_n)) * 4 <= t.capacity;
+    if (sparse && maybe) {
+      look0 = (t.occupied[b0 >> 6] >> (b0 & 63)) & 1ull;
+      look1 = (t.occupied[b1 >> 6] >> (b1 & 63)) & 1ull;
+    }
+  }
   unsigned long long m = kNoMeta;
   int slot = -1;
-  probe_side(t, k, b0, maybe, gi, gbase, &m, &slot);
   uint64_t where = b0;
-  const bool again = maybe && slot < 0;
+  if (__ballot(look0))  // wave-uniform
+    probe_side(t, k, b0, look0, gi, gbase, &m, &slot);
+  const bool again = look1 && slot < 0;
   if (__ballot(again)) {  // wave-uniform
     probe_side(t, k, b1, again, gi, gbase, &m, &slot);
     if (again) where = b1;
