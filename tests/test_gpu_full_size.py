@@ -129,18 +129,19 @@ def test_config5_full_size_against_oracle():
 
 
 @pytest.mark.timeout(1100)
-def test_config4_full_size_from_load_075_through_an_expiry_against_oracle():
-    """configs[3] at full size against the oracle: the 0.75 * capacity hottest IDs are admitted first
-    (threshold 5: each is looked up five times, on both sides), then drifting batches with a sweep every
-    step.  The expiry time is shortened from 20 steps to 3 so that the run reaches a sweep that removes keys
-    (most of the fill, about 20 M keys, at step 3) within a few steps; everything else is the configuration's
-    own.  Presence, pooled rows, refused counts and expired sets at every step, whole table and counter words
-    at the end."""
-    from dataclasses import replace
+def test_config4_full_size_as_specified_through_the_fill_limit_and_the_first_expiry():
+    """configs[3] exactly as the benchmark spec states it, at full size, against the oracle: capacity 2^25, the
+    0.9 * capacity hottest IDs admitted first (threshold 5: each is looked up five times, on both sides),
+    then 21 drifting batches (5 % of the hot ranks permuted per step) with a sweep after every step and an
+    expiry time of 20 steps.  The load climbs to the fill limit (0.9645 < 31/32 at step 12); from step 13
+    on every batch's new keys are refused whole, on both sides alike; the sweep of step 20 removes the 23 M
+    keys of the fill that were never seen again, and step 21 admits again.  Presence, pooled rows, refused
+    counts and expired sets at every step; whole table and counter words at the end."""
     dev = torch.device("cuda:0")
-    wl, seed = replace(synth.CONFIGS["cfg4"], expire_steps=3), 4
+    wl, seed = synth.CONFIGS["cfg4"], 4
+    assert wl.freq_threshold == 5 and wl.expire_steps == 20 and wl.drift_frac == 0.05
     drift = synth.DriftMap(wl, seed)
-    hot = synth.hottest_ids(wl, int(0.75 * wl.capacity), drift)
+    hot = synth.hottest_ids(wl, int(0.9 * wl.capacity), drift)
     max_ids = 1 << 23
     tab = _table(wl, seed, max_ids, dev)
     orc = Oracle(wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, kind="cuckoo")
@@ -155,13 +156,19 @@ def test_config4_full_size_from_load_075_through_an_expiry_against_oracle():
         print("config4 full size: filled chunk at", lo, flush=True)
     assert tab.mono_table_stats()["size"] == hot.shape[0]
     out = torch.zeros(wl.capacity, dtype=torch.int64, device=dev)
-    expired = []
-    for step in range(1, 6):
-        print("config4 full size, step", step, flush=True)
+    expired, refused, load = [], [], []
+    for step in range(1, 22):
         b = synth.make_batch(wl, seed, step, with_grad=True, drift=drift)
         n, st = _full_step_against_oracle(tab, orc, b, dev, wl, 1e-5, sweep=True, out_buf=out)
         expired.append(n)
-    assert expired[:2] == [0, 0] and expired[2] > 10_000_000 and expired[3] > 0    # a non-empty expiry fired
+        refused.append(st["n_full"])
+        load.append(st["size"] / wl.capacity)
+        print("config4 full size, step %d: load %.4f, refused so far %d, expired %d" % (step, load[-1], refused[-1], n),
+              flush=True)
+    assert max(load) <= 31 / 32 and max(load) > 0.95
+    assert refused[10] == 0 and refused[18] > 1_000_000           # the limit was reached before anything expired
+    assert sum(expired[:19]) == 0 and expired[19] > 20_000_000     # the sweep of step 20
+    assert refused[20] == refused[19] and load[20] < 0.4           # room again: step 21 admits
     print("config4 full size, comparing the tables", flush=True)
     _whole_tables_equal(tab, orc, wl, seed, 1e-5)
     tab.close()
