@@ -15,3 +15,15 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
+
+
+@pytest.fixture
+def say(request):
+    """Progress lines of long tests, written past pytest's output capture: a test that runs for minutes
+    must not look hung to whoever watches the run."""
+    capman = request.config.pluginmanager.getplugin("capturemanager")
+
+    def _say(*args):
+        with capman.global_and_fixture_disabled():
+            print(*args, flush=True)
+    return _say

@@ -22,14 +22,14 @@ def _table(wl, seed, max_ids, dev):
 
 
 @pytest.mark.timeout(900)
-def test_config2_full_size_against_oracle():
+def test_config2_full_size_against_oracle(say):
     dev = torch.device("cuda:0")
     wl, seed = synth.CONFIGS["cfg2"], 1
     batches = [synth.make_batch(wl, seed, s, with_grad=True) for s in range(3)]
     tab = _table(wl, seed, max(b["keys"].shape[0] for b in batches), dev)
     orc = Oracle(wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, kind="cuckoo")
     for b in batches:
-        print("config2 full size, step", b["step"], flush=True)
+        say("config2 full size, step", b["step"])
         keys, offs = torch.from_numpy(b["keys"]).to(dev), torch.from_numpy(b["offsets"]).to(dev)
         rows = tab.mono_lookup_or_insert(keys, b["step"])
         present = orc.lookup_or_insert(b["keys"], b["step"])
@@ -87,7 +87,7 @@ def _whole_tables_equal(tab, orc, wl, seed, rtol):
 
 
 @pytest.mark.timeout(900)
-def test_config3_full_size_against_oracle():
+def test_config3_full_size_against_oracle(say):
     """configs[2] whole against the oracle: 131072 samples x 40 slots (26 M IDs per step), dim 64, Adagrad,
     two steps from the empty table (about 4 M keys admitted per step); whole table, every pooled row and
     every counter word compared."""
@@ -95,19 +95,19 @@ def test_config3_full_size_against_oracle():
     wl, seed = synth.CONFIGS["cfg3"], 3
     tab, orc = None, Oracle(wl.capacity, wl.dim, seed, wl.freq_threshold, wl.expire_steps, wl.bf16, kind="cuckoo")
     for step in range(2):
-        print("config3 full size, step", step, flush=True)
+        say("config3 full size, step", step)
         b = synth.make_batch(wl, seed, step, with_grad=True)
         if tab is None:
             tab = _table(wl, seed, int(b["keys"].shape[0] * 1.05) + 1024, dev)
         _full_step_against_oracle(tab, orc, b, dev, wl, 1e-5, sweep=False, out_buf=None)
-    print("config3 full size, comparing the tables", flush=True)
+    say("config3 full size, comparing the tables")
     _whole_tables_equal(tab, orc, wl, seed, 1e-5)
     assert tab.mono_table_stats()["size"] > 5_000_000
     tab.close()
 
 
 @pytest.mark.timeout(900)
-def test_config5_full_size_against_oracle():
+def test_config5_full_size_against_oracle(say):
     """configs[4] whole against the oracle: capacity 2^28, bf16 rows of dim 64, threshold 2, one ID per bag,
     1 M IDs per step; three steps with a sweep each (nothing is 50 steps old yet: the scaled run in
     test_gpu_parity.py crosses the expiry), whole table (rows within the bf16 tolerance), all 2^30 counter
@@ -118,18 +118,18 @@ def test_config5_full_size_against_oracle():
     tab = _table(wl, seed, wl.n_bags, dev)
     out = torch.zeros(1 << 20, dtype=torch.int64, device=dev)
     for step in range(3):
-        print("config5 full size, step", step, flush=True)
+        say("config5 full size, step", step)
         b = synth.make_batch(wl, seed, step, with_grad=True)
         n, st = _full_step_against_oracle(tab, orc, b, dev, wl, 1e-2, sweep=True, out_buf=out)
         assert n == 0
-    print("config5 full size, comparing the tables", flush=True)
+    say("config5 full size, comparing the tables")
     _whole_tables_equal(tab, orc, wl, seed, 1e-2)
     assert tab.mono_table_stats()["size"] > 50_000
     tab.close()
 
 
 @pytest.mark.timeout(1100)
-def test_config4_full_size_as_specified_through_the_fill_limit_and_the_first_expiry():
+def test_config4_full_size_as_specified_through_the_fill_limit_and_the_first_expiry(say):
     """configs[3] exactly as the benchmark spec states it, at full size, against the oracle: capacity 2^25, the
     0.9 * capacity hottest IDs admitted first (threshold 5: each is looked up five times, on both sides),
     then 21 drifting batches (5 % of the hot ranks permuted per step) with a sweep after every step and an
@@ -153,7 +153,7 @@ def test_config4_full_size_as_specified_through_the_fill_limit_and_the_first_exp
             tab.mono_lookup_or_insert(dchunk, 0, rows[: chunk.shape[0]])
             present = orc.lookup_or_insert(chunk, 0)
         assert ((rows[: chunk.shape[0]].cpu().numpy() >= 0) == present).all() and present.all()
-        print("config4 full size: filled chunk at", lo, flush=True)
+        say("config4 full size: filled chunk at", lo)
     assert tab.mono_table_stats()["size"] == hot.shape[0]
     out = torch.zeros(wl.capacity, dtype=torch.int64, device=dev)
     expired, refused, load = [], [], []
@@ -163,19 +163,18 @@ def test_config4_full_size_as_specified_through_the_fill_limit_and_the_first_exp
         expired.append(n)
         refused.append(st["n_full"])
         load.append(st["size"] / wl.capacity)
-        print("config4 full size, step %d: load %.4f, refused so far %d, expired %d" % (step, load[-1], refused[-1], n),
-              flush=True)
+        say("config4 full size, step %d: load %.4f, refused so far %d, expired %d" % (step, load[-1], refused[-1], n))
     assert max(load) <= 31 / 32 and max(load) > 0.95
     assert refused[10] == 0 and refused[18] > 1_000_000           # the limit was reached before anything expired
     assert sum(expired[:19]) == 0 and expired[19] > 20_000_000     # the sweep of step 20
     assert refused[20] == refused[19] and load[20] < 0.4           # room again: step 21 admits
-    print("config4 full size, comparing the tables", flush=True)
+    say("config4 full size, comparing the tables")
     _whole_tables_equal(tab, orc, wl, seed, 1e-5)
     tab.close()
 
 
 @pytest.mark.timeout(600)
-def test_update_with_more_than_16M_rows_in_use():
+def test_update_with_more_than_16M_rows_in_use(say):
     """Beyond 2^24 rows in use the backward's sort needs a fourth pass (25 bits in passes of seven).
     17 M keys are admitted on both sides (threshold 1, dim 4 keeps the oracle small), then one batch
     whose occurrences reach rows over the whole range — every 64th key once, the lowest and highest
@@ -191,7 +190,7 @@ def test_update_with_more_than_16M_rows_in_use():
     assert np.unique(keys_all).shape[0] == stored
     top_key, low_key = None, None
     for step, lo in enumerate(range(0, stored, chunk_n)):
-        print("17M rows: admitting chunk", step, flush=True)
+        say("17M rows: admitting chunk", step)
         chunk = keys_all[lo:lo + chunk_n]
         r = tab.mono_lookup_or_insert(torch.from_numpy(chunk).to(dev), step).cpu().numpy()
         assert orc.lookup_or_insert(chunk, step).all() and (r >= 0).all()
@@ -207,7 +206,7 @@ def test_update_with_more_than_16M_rows_in_use():
     offs_h[-1] = keys_h.shape[0]
     grad_h = rng.standard_normal((offs_h.shape[0] - 1, dim)).astype(np.float32)
     step = 10
-    print("17M rows: training step", flush=True)
+    say("17M rows: training step")
     rows = tab.mono_lookup_or_insert(torch.from_numpy(keys_h).to(dev), step)
     present = orc.lookup_or_insert(keys_h, step)
     rows_h = rows.cpu().numpy()
@@ -218,7 +217,7 @@ def test_update_with_more_than_16M_rows_in_use():
     tc.rows_close(pooled, orc.pool(keys_h, offs_h), 1e-5)
     tab.mono_apply_grad_adagrad(rows, offs, torch.from_numpy(grad_h).to(dev), 0.1, 1e-6)
     orc.apply_grad_adagrad(keys_h, offs_h, grad_h, 0.1, 1e-6)
-    print("17M rows: comparing the tables", flush=True)
+    say("17M rows: comparing the tables")
     d = tab.mono_table_export()
     tc.check_placement(d, cap, 8, seed)
     tc.assert_same_table(d, orc.dump(), exact_rows=False, rtol=1e-5)
