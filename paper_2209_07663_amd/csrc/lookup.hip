@@ -117,101 +117,115 @@ __device__ inline void probe_side(const TableView& t, uint64_t k, uint64_t bucke
 //     missing keys are rare after the first steps (measured on the default workload: 0.200 ms per
 //     launch with 256, 0.225 ms with 1024).
 //   kProbeBlockAgeing: tables with expiry, whose counters age and whose hot set may drift: every step
-//     brings hot IDs that are new (measured on the streaming workload: 0.55 ms with 1024, 1.5 ms with 256).
+//     brings hot IDs that are new (measured on the streaming workload: 0.55 ms with 1024, 1.5 ms with 256
+//     from an empty table; 0.43 / 0.72 / 1.10 ms with 1024 / 512 / 256 on a table at load 0.77).
 constexpr int kProbeBlockStatic = 256;
 constexpr int kProbeBlockAgeing = 1024;
+// Keys per thread on tables with expiry: two turns halve the touches of a hot missing key once more
+// (streaming workload at load 0.77: 0.424 ms per launch with one key per thread, 0.380 with two, 0.391
+// with four, whose 96 KB set of missing keys leaves one block per compute unit; blocks of 512 and 256
+// threads with one key each take 0.72 and 1.10 ms: the kernel's time follows the number of blocks that
+// touch the hottest counters, ~12 ns per touch of one word).
+constexpr int kProbeTurnsAgeing = 2;
 
 // restore != 0: the keys are snapshot records; a stored key is marked absent (its record is refused)
 // and nothing is stamped or counted.
-template <int kProbeBlock>
+// kTurns: keys per thread.  A block owns kProbeBlock * kTurns consecutive keys and takes them in kTurns
+// turns of one key per thread; the LDS set of missing keys spans all turns, so that a hot missing key
+// costs one counter touch per kProbeBlock * kTurns keys.
+template <int kProbeBlock, int kTurns>
 __global__ __launch_bounds__(kProbeBlock) void probe_count_kernel(TableView t, const int64_t* __restrict__ keys,
                                                                   uint64_t n, uint32_t step,
                                                                   int32_t* __restrict__ rows_out, int restore) {
-  constexpr int kMissSlots = 2 * kProbeBlock;  // slots of the block's LDS set of missing keys
+  constexpr int kMissSlots = 2 * kProbeBlock * kTurns;  // slots of the block's LDS set of missing keys
   __shared__ unsigned long long miss_key[kMissSlots];
   __shared__ uint32_t miss_cnt[kMissSlots];
   for (int s = threadIdx.x; s < kMissSlots; s += kProbeBlock) {
     miss_key[s] = kEmptyKey;
     miss_cnt[s] = 0;
   }
-  const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  __syncthreads();  // the LDS set is cleared
   const uint32_t lane = lane_id(), gi = lane & 7u, gbase = lane & ~7u;
-  const uint64_t k = i < n ? (uint64_t)keys[i] : kEmptyKey;
-  const bool live = k != kEmptyKey;
-  // Negative lookup through the admission counters.  When nothing ages (expire_steps == 0) a
-  // counter never decreases, and a stored key reached freq_threshold on its counter when it was
-  // admitted: a counter below the threshold proves the key absent, and both bucket probes are saved
-  // (most misses are tail IDs seen once).  Counts added by this very batch can only make the test
-  // err on the side of probing.
-  bool maybe = live;
-  if (t.expire_steps == 0 && live && !restore) {
-    uint32_t cnt = 0xFFFFFFFFu;
-    for (uint32_t j = 0; j < t.filter_hashes; ++j) {  // the key's count is the smallest of its counters
-      uint32_t* w = reinterpret_cast<uint32_t*>(&t.filter[filter_index(t, k, j)]);
-      const uint32_t c = *w;
-      if (c > kCountGuard) atomicMin(w, 255u);  // an unsaturated count (read as min(count, 255)) must never wrap
-      cnt = c < cnt ? c : cnt;
-    }
-    maybe = cnt >= (t.freq_threshold > 1u ? t.freq_threshold : 1u);
-  }
-  const uint64_t b0 = bucket_index(t, 0, k), b1 = bucket_index(t, 1, k);
-  // Where counters age nothing above could prove a key absent.  On a sparsely filled table (less than a
-  // quarter full) the occupancy bitmap, which is small enough to stay in the caches, often proves a bucket
-  // empty: such a bucket is not read.  (Where the counters do the proving, the bitmap would only add a
-  // dependent access: measured, 4 % on the step.)
-  bool look0 = maybe, look1 = maybe;
+  bool sparse = false;  // (tables with expiry) less than a quarter full: the occupancy bitmap is worth a look
   if (t.expire_steps != 0) {
     const int32_t free_n = t.ctl->free_n;
-    const bool sparse = ((uint64_t)t.capacity - (uint64_t)(free_n < 0 ? 0 : free_n)) * 4 <= t.capacity;
+    sparse = ((uint64_t)t.capacity - (uint64_t)(free_n < 0 ? 0 : free_n)) * 4 <= t.capacity;
+  }
+#pragma unroll 1
+  for (int turn = 0; turn < kTurns; ++turn) {
+    const uint64_t i = ((uint64_t)blockIdx.x * kTurns + (uint64_t)turn) * kProbeBlock + threadIdx.x;
+    const uint64_t k = i < n ? (uint64_t)keys[i] : kEmptyKey;
+    const bool live = k != kEmptyKey;
+    // Negative lookup through the admission counters.  When nothing ages (expire_steps == 0) a
+    // counter never decreases, and a stored key reached freq_threshold on its counter when it was
+    // admitted: a counter below the threshold proves the key absent, and both bucket probes are saved
+    // (most misses are tail IDs seen once).  Counts added by this very batch can only make the test
+    // err on the side of probing.
+    bool maybe = live;
+    if (t.expire_steps == 0 && live && !restore) {
+      uint32_t cnt = 0xFFFFFFFFu;
+      for (uint32_t j = 0; j < t.filter_hashes; ++j) {  // the key's count is the smallest of its counters
+        uint32_t* w = reinterpret_cast<uint32_t*>(&t.filter[filter_index(t, k, j)]);
+        const uint32_t c = *w;
+        if (c > kCountGuard) atomicMin(w, 255u);  // an unsaturated count (read as min(count, 255)) must never wrap
+        cnt = c < cnt ? c : cnt;
+      }
+      maybe = cnt >= (t.freq_threshold > 1u ? t.freq_threshold : 1u);
+    }
+    const uint64_t b0 = bucket_index(t, 0, k), b1 = bucket_index(t, 1, k);
+    // Where counters age nothing above could prove a key absent.  On a sparsely filled table the
+    // occupancy bitmap, which is small enough to stay in the caches, often proves a bucket empty: such a
+    // bucket is not read.  (Where the counters do the proving, the bitmap would only add a dependent
+    // access: measured, 4 % on the step.)
+    bool look0 = maybe, look1 = maybe;
     if (sparse && maybe) {
       look0 = (t.occupied[b0 >> 6] >> (b0 & 63)) & 1ull;
       look1 = (t.occupied[b1 >> 6] >> (b1 & 63)) & 1ull;
     }
-  }
-  unsigned long long m = kNoMeta;
-  int slot = -1;
-  uint64_t where = b0;
-  if (__ballot(look0))  // wave-uniform
-    probe_side(t, k, b0, look0, gi, gbase, &m, &slot);
-  const bool again = look1 && slot < 0;
-  if (__ballot(again)) {  // wave-uniform
-    probe_side(t, k, b1, again, gi, gbase, &m, &slot);
-    if (again) where = b1;
-  }
-  bool miss = false;
-  if (i < n) {
-    if (!live) {
-      rows_out[i] = kRowAbsent;
-    } else if (slot >= 0) {
-      rows_out[i] = restore ? kRowAbsent : (int32_t)meta_row(m);
-      if (!restore && meta_seen(m) != step)
-        reinterpret_cast<uint32_t*>(&t.buckets[where].meta[slot])[1] = step;  // stamp
-    } else {
-      miss = true;
-      const uint32_t sn = t.ctl->stash_n;
-      if (sn) {
-        const uint32_t lim = sn < kStashCap ? sn : kStashCap;
-        for (uint32_t s = 0; s < lim && miss; ++s)
-          if (t.stash[s].key == k) {
-            rows_out[i] = restore ? kRowAbsent : (int32_t)t.stash[s].row;
-            if (!restore) t.stash[s].seen = step;
-            miss = false;
-          }
+    unsigned long long m = kNoMeta;
+    int slot = -1;
+    uint64_t where = b0;
+    if (__ballot(look0))  // wave-uniform
+      probe_side(t, k, b0, look0, gi, gbase, &m, &slot);
+    const bool again = look1 && slot < 0;
+    if (__ballot(again)) {  // wave-uniform
+      probe_side(t, k, b1, again, gi, gbase, &m, &slot);
+      if (again) where = b1;
+    }
+    bool miss = false;
+    if (i < n) {
+      if (!live) {
+        rows_out[i] = kRowAbsent;
+      } else if (slot >= 0) {
+        rows_out[i] = restore ? kRowAbsent : (int32_t)meta_row(m);
+        if (!restore && meta_seen(m) != step)
+          reinterpret_cast<uint32_t*>(&t.buckets[where].meta[slot])[1] = step;  // stamp
+      } else {
+        miss = true;
+        const uint32_t sn = t.ctl->stash_n;
+        if (sn) {
+          const uint32_t lim = sn < kStashCap ? sn : kStashCap;
+          for (uint32_t s = 0; s < lim && miss; ++s)
+            if (t.stash[s].key == k) {
+              rows_out[i] = restore ? kRowAbsent : (int32_t)t.stash[s].row;
+              if (!restore) t.stash[s].seen = step;
+              miss = false;
+            }
+        }
+        if (miss) rows_out[i] = kRowMiss;
       }
-      if (miss) rows_out[i] = kRowMiss;
+    }
+    if (miss && !restore) {  // (records of a restore call are not occurrences: nothing is counted)
+      uint32_t pos = (uint32_t)(mix64(k ^ t.s_dedup) >> 40) & (kMissSlots - 1);
+      for (;;) {  // at most half of the slots are ever taken: a free slot always turns up
+        const unsigned long long old = atomicCAS(&miss_key[pos], (unsigned long long)kEmptyKey, (unsigned long long)k);
+        if (old == kEmptyKey || old == k) break;
+        pos = (pos + 1) & (kMissSlots - 1);
+      }
+      atomicAdd(&miss_cnt[pos], 1u);
     }
   }
-  if (restore) return;  // block-uniform: records are not occurrences, nothing is counted
-  __syncthreads();  // the LDS set is cleared
-  if (miss) {
-    uint32_t pos = (uint32_t)(mix64(k ^ t.s_dedup) >> 40) & (kMissSlots - 1);
-    for (;;) {  // at most kProbeBlock keys in 2 * kProbeBlock slots: a free slot always turns up
-      const unsigned long long old = atomicCAS(&miss_key[pos], (unsigned long long)kEmptyKey, (unsigned long long)k);
-      if (old == kEmptyKey || old == k) break;
-      pos = (pos + 1) & (kMissSlots - 1);
-    }
-    atomicAdd(&miss_cnt[pos], 1u);
-  }
+  if (restore) return;  // block-uniform
   __syncthreads();
   for (int s = threadIdx.x; s < kMissSlots; s += kProbeBlock)
     if (miss_cnt[s]) touch_counter(t, miss_key[s], step, miss_cnt[s]);
@@ -552,13 +566,15 @@ hipError_t launch_lookup_or_insert(const TableView& t, const int64_t* d_keys, ui
   const dim3 block(256), grid((unsigned)((n + 255) / 256));
   const dim3 igrid(grid.x < 2048u ? grid.x : 2048u);
   if (t.expire_steps == 0)
-    MONO_LAUNCH(prof, K_PROBE_COUNT, stream, probe_count_kernel<kProbeBlockStatic>,
+    MONO_LAUNCH(prof, K_PROBE_COUNT, stream, (probe_count_kernel<kProbeBlockStatic, 1>),
                 dim3((unsigned)((n + kProbeBlockStatic - 1) / kProbeBlockStatic)), dim3(kProbeBlockStatic), t, d_keys, n,
                 step, d_rows_out, restore);
-  else
-    MONO_LAUNCH(prof, K_PROBE_COUNT, stream, probe_count_kernel<kProbeBlockAgeing>,
-                dim3((unsigned)((n + kProbeBlockAgeing - 1) / kProbeBlockAgeing)), dim3(kProbeBlockAgeing), t, d_keys, n,
-                step, d_rows_out, restore);
+  else {
+    constexpr uint64_t per_block = (uint64_t)kProbeBlockAgeing * kProbeTurnsAgeing;
+    MONO_LAUNCH(prof, K_PROBE_COUNT, stream, (probe_count_kernel<kProbeBlockAgeing, kProbeTurnsAgeing>),
+                dim3((unsigned)((n + per_block - 1) / per_block)), dim3(kProbeBlockAgeing), t, d_keys, n, step, d_rows_out,
+                restore);
+  }
   MONO_LAUNCH(prof, K_ADMIT_ELECT, stream, admit_elect_kernel, grid, block, t, d_keys, n, epoch, d_rows_out, restore);
   if (t.bf16)
     MONO_LAUNCH(prof, K_INSERT, stream, insert_kernel<uint16_t>, igrid, block, t, step, d_rows_out, src);
