@@ -233,18 +233,23 @@ __global__ __launch_bounds__(kProbeBlock) void probe_count_kernel(TableView t, c
 
 // ---- election ------------------------------------------------------------------------------------
 
-constexpr int kElectSlots = 512;  // slots of a block's LDS set of missing keys (256 keys at most)
-
-__global__ __launch_bounds__(256) void admit_elect_kernel(TableView t, const int64_t* __restrict__ keys, uint64_t n,
-                                                          uint32_t epoch, int32_t* rows_out, int restore) {
-  __shared__ uint32_t wave_cnt[4];
+// kElectBlock: occurrences (= threads) per block.  256 on tables that never expire keys; 1024 on tables
+// with expiry, where an ID that turns hot before it is admitted is led by one occurrence per block, and
+// all those leaders meet at one position of the dedup set.
+template <int kElectBlock>
+__global__ __launch_bounds__(kElectBlock) void admit_elect_kernel(TableView t, const int64_t* __restrict__ keys,
+                                                                  uint64_t n, uint32_t epoch, int32_t* rows_out,
+                                                                  int restore) {
+  constexpr int kElectSlots = 2 * kElectBlock;  // slots of a block's LDS set of missing keys
+  constexpr int kElectWaves = kElectBlock / 64;
+  __shared__ uint32_t wave_cnt[kElectWaves];
   __shared__ uint32_t block_base;
   // The block's occurrences of one missing key are represented by one of them (the leader): a key
   // that turns hot before it is admitted arrives here in thousands of occurrences, and each of them
   // re-reading the counter and competing for the same position of the dedup set serialised.
   __shared__ unsigned long long s_key[kElectSlots];
   __shared__ int32_t s_res[kElectSlots];  // what the leader found: kRowAbsent, or the dedup-set position as -(pos) - 3
-  for (int s = threadIdx.x; s < kElectSlots; s += 256) s_key[s] = kEmptyKey;
+  for (int s = threadIdx.x; s < kElectSlots; s += kElectBlock) s_key[s] = kEmptyKey;
   __syncthreads();
   const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const bool miss = i < n && rows_out[i] == kRowMiss;
@@ -253,7 +258,7 @@ __global__ __launch_bounds__(256) void admit_elect_kernel(TableView t, const int
   uint32_t ls = 0;
   if (miss) {
     ls = (uint32_t)(mix64(k ^ t.s_dedup) >> 32) & (kElectSlots - 1);
-    for (;;) {  // at most 256 keys in 512 slots: a free slot always turns up
+    for (;;) {  // at most half of the slots are ever taken: a free slot always turns up
       const unsigned long long old = atomicCAS(&s_key[ls], (unsigned long long)kEmptyKey, (unsigned long long)k);
       if (old == kEmptyKey) leader = true;
       if (old == kEmptyKey || old == k) break;
@@ -306,7 +311,8 @@ __global__ __launch_bounds__(256) void admit_elect_kernel(TableView t, const int
   __syncthreads();
   const uint32_t list = blockIdx.x & (kWinLists - 1);
   if (threadIdx.x == 0) {
-    const uint32_t total = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+    uint32_t total = 0;
+    for (int w = 0; w < kElectWaves; ++w) total += wave_cnt[w];
     block_base = total ? atomicAdd(&t.win_cnt[list * kWinStride], total) : 0u;
   }
   __syncthreads();
@@ -575,7 +581,11 @@ hipError_t launch_lookup_or_insert(const TableView& t, const int64_t* d_keys, ui
                 dim3((unsigned)((n + per_block - 1) / per_block)), dim3(kProbeBlockAgeing), t, d_keys, n, step, d_rows_out,
                 restore);
   }
-  MONO_LAUNCH(prof, K_ADMIT_ELECT, stream, admit_elect_kernel, grid, block, t, d_keys, n, epoch, d_rows_out, restore);
+  if (t.expire_steps == 0)
+    MONO_LAUNCH(prof, K_ADMIT_ELECT, stream, admit_elect_kernel<256>, grid, block, t, d_keys, n, epoch, d_rows_out, restore);
+  else
+    MONO_LAUNCH(prof, K_ADMIT_ELECT, stream, admit_elect_kernel<1024>, dim3((unsigned)((n + 1023) / 1024)), dim3(1024), t,
+                d_keys, n, epoch, d_rows_out, restore);
   if (t.bf16)
     MONO_LAUNCH(prof, K_INSERT, stream, insert_kernel<uint16_t>, igrid, block, t, step, d_rows_out, src);
   else

@@ -106,7 +106,9 @@ size_t layout(mono_table* t, char* base, uint64_t capacity, uint32_t dim, uint32
   char* stash = take(kStashCap * sizeof(StashEntry));
   char* dset_p = take(dset * sizeof(unsigned long long));
   char* dset_row = take(dset * sizeof(int32_t));
-  const uint64_t win_cap = ((max_ids + 255) / 256 + kWinLists - 1) / kWinLists * 256;
+  // a sub-list takes the winners of every kWinLists-th block of the election kernel, whose blocks hold 256 or
+  // 1024 occurrences: sized for the larger, which also covers the smaller
+  const uint64_t win_cap = ((max_ids + 1023) / 1024 + kWinLists - 1) / kWinLists * 1024;
   const uint64_t sweep_blocks = (capacity + kSweepSlotsPerBlock - 1) / kSweepSlotsPerBlock;
   const uint64_t sweep_cap = (sweep_blocks + kWinLists - 1) / kWinLists * kSweepSlotsPerBlock;
   char* win_list = take(kWinLists * win_cap * sizeof(Winner));

@@ -256,3 +256,20 @@ def test_many_calls_queued_without_a_wait_then_updates(dev):
     assert 256 < st["size"] < 65536 * 2                   # crossed the one-pass / two-pass border on the way
     tc.assert_same_table(tab.mono_table_export(), orc.dump(), exact_rows=False, rtol=1e-5)
     tab.close()
+
+
+@pytest.mark.parametrize("expire_steps", [0, 5])
+@pytest.mark.parametrize("n", [1000, 65 * 1024, 65 * 1024 + 1, 4 * 65 * 256 + 7])
+def test_every_occurrence_a_new_key_fills_the_winner_lists_to_the_brim(dev, n, expire_steps):
+    """Batches made of distinct new keys only, admitted on first sight: every occurrence is elected, so the
+    sub-lists of elected occurrences hold as much as they ever can, at batch sizes where the blocks of the
+    election kernel (256 occurrences without expiry, 1024 with) are dealt to the 64 sub-lists unevenly."""
+    from paper_2209_07663_amd.binding import Table
+    seed, dim, cap = 59, 4, 1 << 18
+    tab = Table(cap, dim, seed, freq_threshold=1, expire_steps=expire_steps, max_ids=n, max_bags=n, device=dev)
+    orc = Oracle(cap, dim, seed, 1, expire_steps, False, kind="cuckoo")
+    keys_h = (np.random.default_rng(n).permutation(1 << 22)[:n].astype(np.int64) + 1) * 1000003
+    offs_h = np.arange(n + 1, dtype=np.int64)
+    compare_step(tab, orc, {"keys": keys_h, "offsets": offs_h, "step": 0}, dev, RTOL_F32, exact_rows=True, train=False)
+    assert tab.mono_table_stats()["size"] == n
+    tab.close()
