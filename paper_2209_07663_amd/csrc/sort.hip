@@ -3,17 +3,17 @@
 //
 // The key width is decided ON THE DEVICE: row indices are handed out in ascending order, so every
 // row in use is below the high-water mark `hwm` kept in the control block.  bit_length(hwm - 1)
-// bits are sorted in the fewest passes of at most kSortMaxBits bits, of equal width (eight bits or fewer
-// up to 16 M rows: a block's share of a bin is then long enough to leave as whole lines); the host launches the
-// passes that an upper bound of `hwm` needs (it keeps one without waiting for the device: see the table's
-// host side) and the superfluous ones return at once.  Pass p reads buffer (p even ? a : b)
+// bits are sorted in the fewest passes of equal width that the call's shape allows (digits of at most eight
+// bits in blocks of 2048 elements up to 16 M rows, of at most nine bits in blocks of 4096 elements beyond:
+// either way a block's share of a bin leaves as pieces of eight elements on average); the host picks the
+// shape and launches the passes that an upper bound of `hwm` needs (it keeps one without waiting for the
+// device: see the table's host side) and the superfluous ones return at once.  Pass p reads buffer (p even ? a : b)
 // and writes the other one.  Pass 0 reads the row indices as the caller holds them and finds the bag
 // of every occurrence from the offsets (no array of bag numbers is ever written to memory); dropped
 // occurrences (row -1) are left out by it, and it publishes the number of pairs that remain
 // (kValidPairs slot of the control block's scratch).
 //
-// Unit of work: one block of four waves owns kSortItemsPerBlock consecutive elements, a quarter
-// per wave.  Per pass:
+// Unit of work: one block owns kItems consecutive elements, an equal share per wave.  Per pass:
 //   hist     per-unit digit histogram (LDS atomics), written bin-major: hist[bin * units + unit]
 //   scan     one block per bin: exclusive scan along the units; bin totals to `totals`
 //   scatter  the block loads its elements into registers (all loads independent), counts the digits
@@ -29,15 +29,17 @@
 
 namespace mono {
 
-#ifndef MONO_SORT_BLOCK
-#define MONO_SORT_BLOCK 256
-#endif
-constexpr int kSortBlock = MONO_SORT_BLOCK;
-constexpr int kSortWaves = kSortBlock / 64;
-constexpr int kScanWaves = kSortMaxBins / 64;  // the first kSortMaxBins threads of a block own one bin each
-static_assert(kSortBlock >= (int)kSortMaxBins && kSortBlock % 64 == 0, "one thread per bin");
-constexpr uint32_t kSortPerWave = kSortItemsPerBlock / kSortWaves;
-constexpr uint32_t kSortRounds = kSortPerWave / 64;
+// A kernel of the sort is compiled for one shape (see kernels.h): kBits = widest digit, kBlock = threads,
+// kItems = elements owned by a block.
+template <uint32_t kBits, int kBlock, uint32_t kItems>
+struct Shape {
+  static constexpr uint32_t kBins = 1u << kBits;
+  static constexpr int kWaves = kBlock / 64;
+  static constexpr int kScanWaves = (int)kBins / 64;  // the first kBins threads of a block own one bin each
+  static constexpr uint32_t kPerWave = kItems / kWaves;
+  static constexpr uint32_t kRounds = kPerWave / 64;
+  static_assert(kBlock >= (int)kBins && kBlock % 64 == 0 && kItems % (uint32_t)kBlock == 0, "one thread per bin");
+};
 
 // Lanes of the wave that hold the same digit as this lane (among the lanes with valid == true).
 __device__ inline uint64_t same_digit_lanes(uint32_t digit, uint32_t bits, bool valid) {
@@ -82,28 +84,30 @@ __device__ inline uint32_t bag_holding(const int64_t* offsets, uint64_t n_bags, 
 
 // Pass 0 also notes, for the scatter kernel of the same pass, the bag that holds the unit's first
 // occurrence (the last wave of the block searches while the others count).
-__global__ __launch_bounds__(kSortBlock) void sort_hist_kernel(const Control* __restrict__ ctl, uint32_t pass,
+template <uint32_t kBits, int kBlock, uint32_t kItems>
+__global__ __launch_bounds__(kBlock) void sort_hist_kernel(const Control* __restrict__ ctl, uint32_t pass,
                                                                const int32_t* __restrict__ rows,
                                                                const uint2* __restrict__ src, uint64_t n,
                                                                uint64_t units, uint32_t* __restrict__ hist,
                                                                const int64_t* __restrict__ offsets, uint64_t n_bags,
                                                                uint32_t* __restrict__ unit_bag) {
-  const SortPlan plan = make_sort_plan(ctl->hwm);
+  const SortPlan plan = make_sort_plan(ctl->hwm, kBits);
   if (pass >= plan.passes) return;
-  __shared__ uint32_t cnt[kSortMaxBins];
+  using S = Shape<kBits, kBlock, kItems>;
+  __shared__ uint32_t cnt[S::kBins];
   const uint64_t unit = blockIdx.x;
   const uint32_t shift = plan.shift(pass), nbins = 1u << plan.width(pass), mask = nbins - 1;
-  for (uint32_t b = threadIdx.x; b < nbins; b += kSortBlock) cnt[b] = 0;
+  for (uint32_t b = threadIdx.x; b < nbins; b += kBlock) cnt[b] = 0;
   __syncthreads();
-  const uint64_t base = unit * kSortItemsPerBlock;
+  const uint64_t base = unit * kItems;
   if (pass > 0) n = ctl->scratch[kValidPairs];
   // every key of the thread is requested before the first one is counted (left to itself the compiler
   // keeps each load behind the LDS atomic before it: eight memory round trips in a row)
-  constexpr uint32_t kPerThread = kSortItemsPerBlock / kSortBlock;
+  constexpr uint32_t kPerThread = kItems / kBlock;
   uint32_t key[kPerThread];
 #pragma unroll
   for (uint32_t r = 0; r < kPerThread; ++r) {
-    const uint64_t i = base + (uint64_t)r * kSortBlock + threadIdx.x;
+    const uint64_t i = base + (uint64_t)r * kBlock + threadIdx.x;
     key[r] = plan.hwm;
     if (i < n) key[r] = pass == 0 ? first_key(rows, i, plan.hwm) : src[i].x;
   }
@@ -111,9 +115,9 @@ __global__ __launch_bounds__(kSortBlock) void sort_hist_kernel(const Control* __
   for (uint32_t r = 0; r < kPerThread; ++r)
     if (key[r] < plan.hwm) atomicAdd(&cnt[(key[r] >> shift) & mask], 1u);
   __syncthreads();
-  for (uint32_t b = threadIdx.x; b < nbins; b += kSortBlock) hist[(uint64_t)b * units + unit] = cnt[b];
-  if (pass == 0 && (threadIdx.x >> 6) == kSortWaves - 1) {  // wave-uniform; after the last barrier: nobody waits for it
-    const uint32_t b0 = bag_holding(offsets, n_bags, n, unit * kSortItemsPerBlock);
+  for (uint32_t b = threadIdx.x; b < nbins; b += kBlock) hist[(uint64_t)b * units + unit] = cnt[b];
+  if (pass == 0 && (threadIdx.x >> 6) == S::kWaves - 1) {  // wave-uniform; after the last barrier: nobody waits for it
+    const uint32_t b0 = bag_holding(offsets, n_bags, n, unit * kItems);
     if (lane_id() == 0) unit_bag[unit] = b0;
   }
 }
@@ -122,10 +126,11 @@ __global__ __launch_bounds__(kSortBlock) void sort_hist_kernel(const Control* __
 // One block per bin; thread t owns a run of consecutive units (loaded at once, summed serially),
 // the thread sums are scanned across the block, and the run is written back.
 constexpr uint32_t kScanPerThread = 16;  // units per thread and round
+template <uint32_t kBits>
 __global__ __launch_bounds__(256) void sort_scan_kernel(const Control* __restrict__ ctl, uint32_t pass,
                                                         uint32_t* __restrict__ hist, uint64_t units,
                                                         uint32_t* __restrict__ totals) {
-  const SortPlan plan = make_sort_plan(ctl->hwm);
+  const SortPlan plan = make_sort_plan(ctl->hwm, kBits);
   if (pass >= plan.passes || blockIdx.x >= (1u << plan.width(pass))) return;
   __shared__ uint32_t wave_sum[4];
   __shared__ uint32_t carry_s;
@@ -164,7 +169,8 @@ __global__ __launch_bounds__(256) void sort_scan_kernel(const Control* __restric
   if (threadIdx.x == 0) totals[blockIdx.x] = carry_s;
 }
 
-__global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __restrict__ ctl, uint32_t pass,
+template <uint32_t kBits, int kBlock, uint32_t kItems>
+__global__ __launch_bounds__(kBlock) void sort_scatter_kernel(Control* __restrict__ ctl, uint32_t pass,
                                                                   const int32_t* __restrict__ rows,
                                                                   const int64_t* __restrict__ offsets,
                                                                   uint64_t n_bags,
@@ -174,18 +180,19 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
                                                                   const uint32_t* __restrict__ hist,
                                                                   const uint32_t* __restrict__ totals,
                                                                   uint2* __restrict__ dst) {
-  const SortPlan plan = make_sort_plan(ctl->hwm);
+  const SortPlan plan = make_sort_plan(ctl->hwm, kBits);
   if (pass >= plan.passes) return;
-  __shared__ uint2 stage[kSortItemsPerBlock];          // the block's elements in sorted order
-  __shared__ uint32_t lds[kSortWaves][kSortMaxBins];   // per-wave digit counts, then local start offsets
-  __shared__ uint32_t local_start[kSortMaxBins];       // first position of a bin in `stage`
-  __shared__ uint32_t global_start[kSortMaxBins];      // where this block's part of a bin goes in dst
+  using S = Shape<kBits, kBlock, kItems>;
+  __shared__ uint2 stage[kItems];          // the block's elements in sorted order
+  __shared__ uint32_t lds[S::kWaves][S::kBins];   // per-wave digit counts, then local start offsets
+  __shared__ uint32_t local_start[S::kBins];       // first position of a bin in `stage`
+  __shared__ uint32_t global_start[S::kBins];      // where this block's part of a bin goes in dst
   const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const uint64_t unit = blockIdx.x;
   const uint32_t shift = plan.shift(pass), bits = plan.width(pass), nbins = 1u << bits, mask = nbins - 1;
 
   // 0. what step 3 needs from memory is asked for first: it arrives while the elements are loaded
-  const bool bin_thread = threadIdx.x < kSortMaxBins;
+  const bool bin_thread = threadIdx.x < S::kBins;
   const uint32_t bin = threadIdx.x;
   uint32_t tot = 0, before_me = 0;  // the bin in the whole batch / in the units before this one
   if (bin_thread && bin < nbins) {
@@ -194,19 +201,19 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
   }
   // 1. this wave's elements -> registers (independent, coalesced loads)
   if (pass > 0) n = ctl->scratch[kValidPairs];
-  const uint64_t ubase = unit * kSortItemsPerBlock;
-  const uint64_t base = ubase + (uint64_t)wave * kSortPerWave;
-  uint2 kv[kSortRounds];
+  const uint64_t ubase = unit * kItems;
+  const uint64_t base = ubase + (uint64_t)wave * S::kPerWave;
+  uint2 kv[S::kRounds];
 #pragma unroll
-  for (uint32_t r = 0; r < kSortRounds; ++r) {
+  for (uint32_t r = 0; r < S::kRounds; ++r) {
     const uint64_t i = base + (uint64_t)r * 64 + lane;
     kv[r] = make_uint2(0xFFFFFFFFu, 0u);
     if (i < n) kv[r] = pass == 0 ? make_uint2(first_key(rows, i, plan.hwm), 0u) : src[i];
     if (kv[r].x >= plan.hwm) kv[r].x = 0xFFFFFFFFu;  // dropped occurrence (or past the end): left out
   }
-  for (uint32_t b = threadIdx.x; b < kSortMaxBins; b += kSortBlock) {
+  for (uint32_t b = threadIdx.x; b < S::kBins; b += kBlock) {
 #pragma unroll
-    for (int w = 0; w < kSortWaves; ++w) lds[w][b] = 0;
+    for (int w = 0; w < S::kWaves; ++w) lds[w][b] = 0;
   }
   if (pass == 0) {
     // The bag of every occurrence of the unit (the pooled gradient of bag b is the gradient of each of its
@@ -215,12 +222,12 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
     // yet).  Whatever the offsets hold, every write stays inside the unit and every bag number that is
     // read is bounded to the bags of the batch.
     uint32_t* bag_here = reinterpret_cast<uint32_t*>(stage);
-    const uint64_t uend = ubase + kSortItemsPerBlock < n ? ubase + kSortItemsPerBlock : n;
+    const uint64_t uend = ubase + kItems < n ? ubase + kItems : n;
     constexpr uint32_t kBagsPerThread = 4;  // consecutive bags per thread and round (a unit holds ~500 bags of four IDs)
     // a thread stops at the first of its bags that starts at or after the end of the unit: offsets are
     // non-decreasing, so no later bag of its can reach into the unit (no barrier inside the loop)
     for (uint64_t b = (uint64_t)unit_bag[unit] + (uint64_t)threadIdx.x * kBagsPerThread; b < n_bags;
-         b += (uint64_t)kSortBlock * kBagsPerThread) {
+         b += (uint64_t)kBlock * kBagsPerThread) {
       uint64_t o[kBagsPerThread + 1];
 #pragma unroll
       for (uint32_t q = 0; q <= kBagsPerThread; ++q) o[q] = b + q <= n_bags ? bounded_offset(offsets, b + q, n) : uend;
@@ -234,23 +241,23 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
     __syncthreads();
     const uint32_t last_bag = (uint32_t)(n_bags - 1);  // (an occurrence outside every bag reads whatever the LDS held)
 #pragma unroll
-    for (uint32_t r = 0; r < kSortRounds; ++r) kv[r].y = min(bag_here[wave * kSortPerWave + r * 64 + lane], last_bag);
+    for (uint32_t r = 0; r < S::kRounds; ++r) kv[r].y = min(bag_here[wave * S::kPerWave + r * 64 + lane], last_bag);
   }
   __syncthreads();
   // 2. per-wave digit counts
 #pragma unroll
-  for (uint32_t r = 0; r < kSortRounds; ++r) {
+  for (uint32_t r = 0; r < S::kRounds; ++r) {
     if (kv[r].x != 0xFFFFFFFFu) atomicAdd(&lds[wave][(kv[r].x >> shift) & mask], 1u);
   }
   __syncthreads();
-  // 3. thread b < kSortMaxBins owns bin b: exclusive scans of the bin totals, once within the block
+  // 3. thread b < S::kBins owns bin b: exclusive scans of the bin totals, once within the block
   //    (positions in `stage`) and once over all bins of the pass (start of the bin in dst)
-  __shared__ uint32_t scan_sum[kScanWaves], scan_tot[kScanWaves];
+  __shared__ uint32_t scan_sum[S::kScanWaves], scan_tot[S::kScanWaves];
   {
     uint32_t mine = 0;
     if (bin_thread && bin < nbins) {
 #pragma unroll
-      for (int w = 0; w < kSortWaves; ++w) mine += lds[w][bin];
+      for (int w = 0; w < S::kWaves; ++w) mine += lds[w][bin];
     }
     uint32_t x = mine, y = tot;  // inclusive wave scans
 #pragma unroll
@@ -277,13 +284,13 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
         global_start[bin] = run_tot + before_me;
         uint32_t at = run;
 #pragma unroll
-        for (int w = 0; w < kSortWaves; ++w) {
+        for (int w = 0; w < S::kWaves; ++w) {
           const uint32_t c = lds[w][bin];
           lds[w][bin] = at;
           at += c;
         }
       }
-      if (pass == 0 && blockIdx.x == 0 && threadIdx.x == kSortMaxBins - 1)
+      if (pass == 0 && blockIdx.x == 0 && threadIdx.x == S::kBins - 1)
         ctl->scratch[kValidPairs] = run_tot + tot;  // pairs that remain
     }
   }
@@ -291,7 +298,7 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
   // 4. rank (stable) into `stage`, 64 elements at a time
   volatile uint32_t* off = lds[wave];
 #pragma unroll
-  for (uint32_t r = 0; r < kSortRounds; ++r) {
+  for (uint32_t r = 0; r < S::kRounds; ++r) {
     const bool valid = kv[r].x != 0xFFFFFFFFu;
     const uint32_t digit = (kv[r].x >> shift) & mask;
     const uint64_t peers = same_digit_lanes(digit, bits, valid);
@@ -304,35 +311,50 @@ __global__ __launch_bounds__(kSortBlock) void sort_scatter_kernel(Control* __res
   // 5. out: neighbouring threads write neighbouring elements of a bin
   uint32_t total = 0;
 #pragma unroll
-  for (int w = 0; w < kScanWaves; ++w) total += scan_sum[w];
-  for (uint32_t p = threadIdx.x; p < total; p += kSortBlock) {
+  for (int w = 0; w < S::kScanWaves; ++w) total += scan_sum[w];
+  for (uint32_t p = threadIdx.x; p < total; p += kBlock) {
     const uint2 e = stage[p];
     const uint32_t digit = (e.x >> shift) & mask;
     dst[global_start[digit] + (p - local_start[digit])] = e;
   }
 }
 
-hipError_t launch_sort_pairs(const TableView& t, const UpdateWorkspace& ws, const int32_t* d_rows, uint64_t n,
-                             const int64_t* d_offsets, uint64_t n_bags, uint32_t hwm_bound, uint32_t* launched,
-                             hipStream_t stream, Profiler* prof) {
-  if (n == 0) return hipSuccess;
-  const uint64_t units = sort_units(n);
-  uint32_t* totals = ws.hist + (uint64_t)kSortMaxBins * units;
-  // as many passes as the largest high-water mark the table can have by now needs (the device knows the
-  // real mark: passes beyond its plan return at once)
-  const SortPlan worst = make_sort_plan(hwm_bound < (uint32_t)t.capacity ? hwm_bound : (uint32_t)t.capacity);
-  if (launched) *launched = worst.passes;
-  const dim3 block(kSortBlock), grid((unsigned)units);
-  for (uint32_t p = 0; p < worst.passes; ++p) {
+template <uint32_t kBits, int kBlock, uint32_t kItems>
+static void queue_sort_passes(const TableView& t, const UpdateWorkspace& ws, const int32_t* d_rows, uint64_t n,
+                              const int64_t* d_offsets, uint64_t n_bags, uint32_t passes, hipStream_t stream,
+                              Profiler* prof) {
+  const uint64_t units = sort_units(n, kItems);
+  uint32_t* totals = ws.hist + (uint64_t)(1u << kBits) * units;
+  const dim3 block(kBlock), grid((unsigned)units);
+  for (uint32_t p = 0; p < passes; ++p) {
     const uint2* src = p % 2 == 0 ? ws.pair_a : ws.pair_b;
     uint2* dst = p % 2 == 0 ? ws.pair_b : ws.pair_a;
-    MONO_LAUNCH(prof, K_SORT_HIST, stream, sort_hist_kernel, grid, block, t.ctl, p, d_rows, src, n, units, ws.hist,
-                d_offsets, n_bags, ws.unit_bag);
-    MONO_LAUNCH(prof, K_SORT_SCAN, stream, sort_scan_kernel, dim3(kSortMaxBins), dim3(256), t.ctl, p, ws.hist, units,
+    MONO_LAUNCH(prof, K_SORT_HIST, stream, (sort_hist_kernel<kBits, kBlock, kItems>), grid, block, t.ctl, p, d_rows, src, n,
+                units, ws.hist, d_offsets, n_bags, ws.unit_bag);
+    MONO_LAUNCH(prof, K_SORT_SCAN, stream, sort_scan_kernel<kBits>, dim3(1u << kBits), dim3(256), t.ctl, p, ws.hist, units,
                 totals);
-    MONO_LAUNCH(prof, K_SORT_SCATTER, stream, sort_scatter_kernel, grid, block, t.ctl, p, d_rows, d_offsets, n_bags,
-                ws.unit_bag, src, n, units, ws.hist, totals, dst);
+    MONO_LAUNCH(prof, K_SORT_SCATTER, stream, (sort_scatter_kernel<kBits, kBlock, kItems>), grid, block, t.ctl, p, d_rows,
+                d_offsets, n_bags, ws.unit_bag, src, n, units, ws.hist, totals, dst);
   }
+}
+
+hipError_t launch_sort_pairs(const TableView& t, const UpdateWorkspace& ws, const int32_t* d_rows, uint64_t n,
+                             const int64_t* d_offsets, uint64_t n_bags, uint32_t hwm_bound, uint32_t* launched,
+                             uint32_t* max_bits, hipStream_t stream, Profiler* prof) {
+  // the shape and as many passes as the largest high-water mark the table can have by now needs (the device
+  // knows the real mark: passes beyond its plan return at once)
+  const uint32_t bound = hwm_bound < (uint32_t)t.capacity ? hwm_bound : (uint32_t)t.capacity;
+  const SortShape shape = sort_shape_for(bound);
+  const SortPlan worst = make_sort_plan(bound, shape.max_bits);
+  if (launched) *launched = worst.passes;
+  if (max_bits) *max_bits = shape.max_bits;
+  if (n == 0) return hipSuccess;
+  if (shape.max_bits == kSortWide.max_bits)
+    queue_sort_passes<kSortWide.max_bits, (int)kSortWide.block, kSortWide.items>(t, ws, d_rows, n, d_offsets, n_bags,
+                                                                                 worst.passes, stream, prof);
+  else
+    queue_sort_passes<kSortNarrow.max_bits, (int)kSortNarrow.block, kSortNarrow.items>(t, ws, d_rows, n, d_offsets,
+                                                                                       n_bags, worst.passes, stream, prof);
   return hipGetLastError();
 }
 

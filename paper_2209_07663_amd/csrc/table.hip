@@ -39,7 +39,7 @@ constexpr uint32_t kStaticMaxDim = 1024;
 constexpr size_t static_part(size_t bytes) { return (bytes + 255) & ~(size_t)255; }
 constexpr size_t kStaticScratchBytes =
     static_part(kStaticMaxIds * 4) + 2 * static_part(kStaticMaxIds * sizeof(uint2)) +
-    static_part((size_t)kSortMaxBins * ((kStaticMaxIds + kSortItemsPerBlock - 1) / kSortItemsPerBlock + 1) * 4) +
+    static_part((size_t)512 * ((kStaticMaxIds + 2047) / 2048 + 1) * 4) +  // (at least sort_hist_words: checked below)
     static_part(2 * ((kStaticMaxIds + 255) / 256) * kStaticMaxDim * sizeof(float)) +
     static_part(2 * ((kStaticMaxIds + 255) / 256) * sizeof(uint32_t));
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
@@ -158,6 +158,7 @@ void* g_scratch_ptr[kMaxDevices] = {nullptr};
 std::mutex g_scratch_mutex;
 
 hipError_t static_workspace(int device, uint32_t dim, UpdateWorkspace* ws) {
+  if (sort_hist_words(kStaticMaxIds) > (size_t)512 * ((kStaticMaxIds + 2047) / 2048 + 1)) return hipErrorInvalidValue;
   if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
   void* base = nullptr;
   {

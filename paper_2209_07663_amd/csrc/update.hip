@@ -151,7 +151,7 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(TableView t, const uint
                                                          const uint2* __restrict__ pair_b, uint64_t n,
                                                          const float* __restrict__ grad, float lr, float eps,
                                                          float* __restrict__ part, uint32_t* __restrict__ part_row,
-                                                         uint32_t ppl, uint32_t launched) {
+                                                         uint32_t ppl, uint32_t launched, uint32_t max_bits) {
   static_assert(SEG == 1 || GLOG == 6, "rows wider than 256 elements are held by a whole wave");
   extern __shared__ float4 s_mem[];  // [2 * groups_per_block][dim / 4] vectors, then the slot rows
   using Vec = RowVec<SEG>;
@@ -159,7 +159,7 @@ __global__ __launch_bounds__(256) void seg_reduce_kernel(TableView t, const uint
   const uint32_t chunk = ppl << GLOG, tile = 256u * ppl;
   constexpr int kWide = (int)group < 8 ? (int)group : 8;
   constexpr int kBatch = kWide / SEG > 0 ? kWide / SEG : 1;   // gradient rows in flight per lane
-  const SortPlan plan = make_sort_plan(t.ctl->hwm);
+  const SortPlan plan = make_sort_plan(t.ctl->hwm, max_bits);
   if (plan.passes > launched) {  // the host's bound on the high-water mark was too low: nothing is sorted, nothing is touched
     if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(&t.ctl->n_lost, 1ull);
     if (threadIdx.x == 0) {
@@ -364,8 +364,8 @@ hipError_t launch_apply_grad_adagrad(const TableView& t, const UpdateWorkspace& 
                                      const int64_t* d_offsets, uint64_t n_bags, const float* d_grad, float lr, float eps,
                                      uint32_t hwm_bound, hipStream_t stream, Profiler* prof) {
   if (n == 0 || n_bags == 0) return hipSuccess;
-  uint32_t launched = 0;
-  hipError_t e = launch_sort_pairs(t, ws, d_rows, n, d_offsets, n_bags, hwm_bound, &launched, stream, prof);
+  uint32_t launched = 0, max_bits = 0;
+  hipError_t e = launch_sort_pairs(t, ws, d_rows, n, d_offsets, n_bags, hwm_bound, &launched, &max_bits, stream, prof);
   if (e != hipSuccess) return e;
   uint32_t group_log2 = 0;
   while (group_log2 < 6 && (4u << group_log2) < t.dim) ++group_log2;
@@ -381,7 +381,7 @@ hipError_t launch_apply_grad_adagrad(const TableView& t, const UpdateWorkspace& 
   const size_t lds_combine = gpb * (t.dim / 4) * sizeof(float4);
 #define MONO_SEG_REDUCE(E, GLOG, SEG)                                                                                  \
   MONO_LAUNCH_SMEM(prof, K_SEG_REDUCE, stream, (seg_reduce_kernel<E, GLOG, SEG>), grid, block, lds_reduce, t, ws.pair_a, \
-                   ws.pair_b, n, d_grad, lr, eps, ws.part, ws.part_row, ppl, launched)
+                   ws.pair_b, n, d_grad, lr, eps, ws.part, ws.part_row, ppl, launched, max_bits)
 #define MONO_COMBINE(E, SEG)                                                                                     \
   MONO_LAUNCH_SMEM(prof, K_COMBINE, stream, (combine_kernel<E, SEG>), grid, block, lds_combine, t, n_tiles, ws.part, \
                    ws.part_row, lr, eps, group_log2)
